@@ -1,0 +1,1 @@
+"""CPU oracle package: test infrastructure, never imported by the product path."""

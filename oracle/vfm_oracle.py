@@ -1,0 +1,270 @@
+"""fp64 CPU oracle for packed 3D-RoPE self-attention (forward and backward).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain reference the GPU
+library is judged against.  Only the tests, the smoke check and the
+cpu_baseline leg of the benchmark may import it; the product path never does.
+It shares no code with the HIP kernels and imports nothing from the package.
+
+Everything is numpy float64.  Inputs are widened exactly (a bf16 or fp32 bit
+pattern is representable in fp64), so input quantisation is never charged as
+error.  Each function writes the plain definition out; there is no tiling,
+no online softmax, no fusion.  A matmul (numpy `@`) is used as a library step.
+
+What the paper fixes, and where:
+  * Section 3.1 (dataset preparation and blending): clips of different
+    shapes are concatenated along the sequence dimension with micro-batch 1
+    ("sequence packing"), so the packed layout is [total_tokens, heads,
+    head_dim] with segment boundaries cu_seqlens, and attention never crosses
+    a boundary.
+  * Section 4.2 (training pipeline): the 3D latent tokens of a clip are
+    flattened into one sequence of spacetime patches.  Section 4.6 gives the
+    flattened shape [b, h*w*t, d] and notes that spatial attention views the
+    same buffer as [(b*t), h*w, d]; that view is free only when t is the
+    slowest-varying index, hence r = (t*H + h)*W + w here.
+  * Section 4.4 (context parallel paragraph) and Section 4.6: every query
+    token is computed against the keys and values of all tokens of its own
+    sequence -- full, bidirectional attention, no causal mask.
+  * Section 5.2 and Table 1: multi-head attention, one K/V head per Q head,
+    head_dim = hidden / heads = 128.
+
+What the paper does not fix (readings taken; all are restated in the design
+notes of the repository): the rotary embedding itself (theta, per-axis
+split, adjacent-pair convention, per-axis frequency exponent, integer grid
+positions starting at 0), the softmax scale (an argument), and natural-log
+units for the log-sum-exp.
+
+Pins (tests/test_oracle_*.py): single-token segment returns V; Q = 0 returns
+the segment mean of V and lse = ln N; packed equals per-clip; RoPE keeps
+norms, is the identity at the origin, inverts exactly, is shift-invariant in
+the scores, and reduces to textbook complex-number 1-D RoPE; softmax row
+sums; sum of dK over a segment is zero; key/value permutation invariance;
+central finite differences; a dense masked brute force written with Python
+loops; PyTorch fp64 autograd as a third opinion.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "token_coords",
+    "rope3d",
+    "attn_fwd",
+    "attn_bwd",
+    "attn_fwd_rows",
+    "attn_bwd_rows",
+]
+
+
+def _as_f64(x) -> np.ndarray:
+    return np.asarray(x, dtype=np.float64)
+
+
+def _check_cu(cu_seqlens, total_tokens: int) -> np.ndarray:
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    if cu.ndim != 1 or cu.size < 1 or cu[0] != 0 or cu[-1] != total_tokens:
+        raise ValueError("cu_seqlens must start at 0 and end at total_tokens")
+    if np.any(np.diff(cu) < 0):
+        raise ValueError("cu_seqlens must be non-decreasing")
+    return cu
+
+
+def token_coords(thw, cu_seqlens) -> np.ndarray:
+    """(t, h, w) grid position of every packed token.
+
+    Section 4.2 / 4.6: a clip with latent grid (T, H, W) is flattened with t
+    slowest and w fastest.  Packed token n of segment s has local index
+    r = n - cu[s] and position t = r // (H*W), h = (r // W) % H, w = r % W.
+    Returns int64 [total_tokens, 3].
+    """
+    thw = np.asarray(thw, dtype=np.int64).reshape(-1, 3)
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    if thw.shape[0] != cu.size - 1:
+        raise ValueError("one (T,H,W) triple per segment")
+    total = int(cu[-1])
+    pos = np.zeros((total, 3), dtype=np.int64)
+    for s in range(thw.shape[0]):
+        T, H, W = (int(v) for v in thw[s])
+        a, b = int(cu[s]), int(cu[s + 1])
+        if T * H * W != b - a:
+            raise ValueError(f"segment {s}: T*H*W != segment length")
+        r = np.arange(b - a, dtype=np.int64)
+        pos[a:b, 0] = r // (H * W)
+        pos[a:b, 1] = (r // W) % H
+        pos[a:b, 2] = r % W
+    return pos
+
+
+def rope3d(x, thw, cu_seqlens, dims, theta: float = 10000.0,
+           inverse: bool = False, pos_offset=(0, 0, 0)) -> np.ndarray:
+    """3D rotary position embedding of x[total, heads, head_dim] (fp64 copy).
+
+    The head vector is cut into three contiguous slices of widths
+    dims = (d_t, d_h, d_w), d_t + d_h + d_w = head_dim, all even.  Slice A is
+    an ordinary 1-D rotary embedding driven by the token's position along
+    axis A: for i in [0, d_A/2) the adjacent pair (x[o_A+2i], x[o_A+2i+1]) is
+    rotated by the angle  phi = pos_A * theta**(-2i/d_A):
+        x0' = x0 cos(phi) - x1 sin(phi),   x1' = x0 sin(phi) + x1 cos(phi).
+    inverse=True rotates by -phi (the transpose, used for gradients).
+    pos_offset shifts every position by a constant (only tests use it, to
+    check that scores depend on position differences alone).
+    """
+    x = _as_f64(x)
+    total, _, D = x.shape
+    d_t, d_h, d_w = (int(d) for d in dims)
+    if d_t + d_h + d_w != D or any(d % 2 for d in (d_t, d_h, d_w)):
+        raise ValueError("dims must be even and sum to head_dim")
+    _check_cu(cu_seqlens, total)
+    pos = token_coords(thw, cu_seqlens) + np.asarray(pos_offset, dtype=np.int64)
+    y = x.copy()
+    start = 0
+    for axis, d_a in enumerate((d_t, d_h, d_w)):
+        if d_a == 0:
+            continue
+        i = np.arange(d_a // 2, dtype=np.float64)
+        freq = float(theta) ** (-2.0 * i / d_a)                    # [d_a/2]
+        phi = pos[:, axis].astype(np.float64)[:, None] * freq[None, :]
+        if inverse:
+            phi = -phi
+        c = np.cos(phi)[:, None, :]                                # [total,1,d_a/2]
+        s = np.sin(phi)[:, None, :]
+        x0 = x[:, :, start:start + d_a:2]
+        x1 = x[:, :, start + 1:start + d_a:2]
+        y[:, :, start:start + d_a:2] = x0 * c - x1 * s
+        y[:, :, start + 1:start + d_a:2] = x0 * s + x1 * c
+        start += d_a
+    return y
+
+
+def _softmax_rows(S: np.ndarray):
+    """Row softmax of a score matrix and its natural-log normaliser."""
+    m = S.max(axis=1, keepdims=True)
+    E = np.exp(S - m)
+    l = E.sum(axis=1, keepdims=True)
+    return E / l, (m + np.log(l))[:, 0]
+
+
+def attn_fwd(q, k, v, cu_seqlens, scale: float):
+    """Packed multi-head self-attention forward.
+
+    For each segment [a, b) and head h (Sections 3.1, 4.4, 4.6):
+        S_ij = scale * sum_d Q_id K_jd           i, j in [a, b)
+        P_ij = exp(S_ij) / sum_j' exp(S_ij')
+        O_i  = sum_j P_ij V_j
+        LSE_i = ln sum_j exp(S_ij)               (natural log)
+    Returns out [total, heads, head_dim] and lse [heads, total], both fp64.
+    Empty segments contribute nothing.
+    """
+    q, k, v = _as_f64(q), _as_f64(k), _as_f64(v)
+    total, H, D = q.shape
+    cu = _check_cu(cu_seqlens, total)
+    out = np.zeros((total, H, D))
+    lse = np.zeros((H, total))
+    for s in range(cu.size - 1):
+        a, b = int(cu[s]), int(cu[s + 1])
+        if b == a:
+            continue
+        for h in range(H):
+            S = scale * (q[a:b, h, :] @ k[a:b, h, :].T)
+            P, L = _softmax_rows(S)
+            out[a:b, h, :] = P @ v[a:b, h, :]
+            lse[h, a:b] = L
+    return out, lse
+
+
+def attn_bwd(q, k, v, dout, cu_seqlens, scale: float):
+    """Gradients of  sum(out * dout)  with respect to q, k, v.
+
+    The softmax-attention gradient written out (no gradient flows into lse):
+        Delta_i = sum_d dO_id O_id
+        dV_j    = sum_i P_ij dO_i
+        dP_ij   = sum_d dO_id V_jd
+        dS_ij   = P_ij (dP_ij - Delta_i)
+        dQ_i    = scale * sum_j dS_ij K_j
+        dK_j    = scale * sum_i dS_ij Q_i
+    P is recomputed from this module's own forward.  Returns dq, dk, dv with
+    the shape of q, fp64.
+    """
+    q, k, v, dout = _as_f64(q), _as_f64(k), _as_f64(v), _as_f64(dout)
+    total, H, D = q.shape
+    cu = _check_cu(cu_seqlens, total)
+    dq = np.zeros_like(q)
+    dk = np.zeros_like(k)
+    dv = np.zeros_like(v)
+    for s in range(cu.size - 1):
+        a, b = int(cu[s]), int(cu[s + 1])
+        if b == a:
+            continue
+        for h in range(H):
+            Q, K, V, dO = q[a:b, h, :], k[a:b, h, :], v[a:b, h, :], dout[a:b, h, :]
+            P, _ = _softmax_rows(scale * (Q @ K.T))
+            O = P @ V
+            delta = (dO * O).sum(axis=1, keepdims=True)
+            dv[a:b, h, :] = P.T @ dO
+            dP = dO @ V.T
+            dS = P * (dP - delta)
+            dq[a:b, h, :] = scale * (dS @ K)
+            dk[a:b, h, :] = scale * (dS.T @ Q)
+    return dq, dk, dv
+
+
+def _segment_of(cu: np.ndarray, n: int):
+    s = int(np.searchsorted(cu, n, side="right")) - 1
+    while cu[s + 1] == cu[s]:          # skip empty segments that share a boundary
+        s += 1
+    return int(cu[s]), int(cu[s + 1])
+
+
+def attn_fwd_rows(q, k, v, cu_seqlens, scale: float, head: int, rows):
+    """out and lse for selected packed query rows of one head.
+
+    The same definition as attn_fwd, evaluated only for the query tokens in
+    `rows` (each against all keys of its own segment).  Used where the whole
+    tensor is too large to compute on the CPU.  Returns out [len(rows), D] and
+    lse [len(rows)].
+    """
+    total, _, D = q.shape
+    cu = _check_cu(cu_seqlens, total)
+    rows = np.asarray(rows, dtype=np.int64)
+    out = np.zeros((rows.size, D))
+    lse = np.zeros(rows.size)
+    for a, b in sorted({_segment_of(cu, int(n)) for n in rows}):
+        sel = np.nonzero((rows >= a) & (rows < b))[0]
+        K = _as_f64(k[a:b, head, :])
+        V = _as_f64(v[a:b, head, :])
+        Q = _as_f64(q[rows[sel], head, :])
+        P, L = _softmax_rows(scale * (Q @ K.T))
+        out[sel] = P @ V
+        lse[sel] = L
+    return out, lse
+
+
+def attn_bwd_rows(q, k, v, dout, cu_seqlens, scale: float, head: int, rows):
+    """dQ for selected query rows of one head, and those rows' share of dK, dV.
+
+    dQ_i depends on query row i alone, so it is complete.  dK_j and dV_j are
+    sums over query rows i; the returned dk_part, dv_part hold the terms of
+    those sums with i in `rows` (summing the parts over a partition of a
+    segment's rows gives that segment's dK, dV).  Shapes: dq [len(rows), D],
+    dk_part and dv_part [total, D] (zero outside the touched segments).
+    """
+    total, _, D = q.shape
+    cu = _check_cu(cu_seqlens, total)
+    rows = np.asarray(rows, dtype=np.int64)
+    dq = np.zeros((rows.size, D))
+    dk_part = np.zeros((total, D))
+    dv_part = np.zeros((total, D))
+    for a, b in sorted({_segment_of(cu, int(n)) for n in rows}):
+        sel = np.nonzero((rows >= a) & (rows < b))[0]
+        K = _as_f64(k[a:b, head, :])
+        V = _as_f64(v[a:b, head, :])
+        Q = _as_f64(q[rows[sel], head, :])
+        dO = _as_f64(dout[rows[sel], head, :])
+        P, _ = _softmax_rows(scale * (Q @ K.T))
+        O = P @ V
+        delta = (dO * O).sum(axis=1, keepdims=True)
+        dP = dO @ V.T
+        dS = P * (dP - delta)
+        dq[sel] = scale * (dS @ K)
+        dk_part[a:b] += scale * (dS.T @ Q)
+        dv_part[a:b] += P.T @ dO
+    return dq, dk_part, dv_part
