@@ -1,0 +1,136 @@
+/*
+ * vfm.h -- C ABI of libvfm: packed 3D-RoPE multi-head self-attention for video
+ * diffusion transformers on AMD MI355X (gfx950), forward and backward.
+ *
+ * The operations are the hot path of the paper's video foundation model runs
+ * (arxiv 2503.12964):
+ *   - Section 3.1: clips of different shapes are concatenated along the
+ *     sequence dimension with micro-batch 1 (sequence packing).  Every tensor
+ *     here is therefore packed as [total_tokens, n_heads, head_dim] and the
+ *     clip boundaries are the prefix sums cu_seqlens[0..n_seqs].
+ *   - Sections 4.2 and 4.6: a clip's 3D latent grid (T, H, W) is flattened to
+ *     one token sequence, t slowest and w fastest.
+ *   - Sections 4.4 and 4.6: full attention -- every query token is computed
+ *     against the keys and values of all tokens of its own clip, bidirectional,
+ *     never across clips.
+ *   - Section 5.2, Table 1: multi-head attention, head_dim 128.
+ * The rotary embedding, the softmax scale and the log-sum-exp units are not
+ * given by the paper; the definitions used are stated at each entry point.
+ *
+ * Conventions common to all entry points
+ *   - Tensor arguments are DEVICE pointers to contiguous memory, 16-byte
+ *     aligned, owned by the caller.  The library never allocates, frees or
+ *     synchronises; it only enqueues kernels on `hip_stream` (a hipStream_t
+ *     passed as void*, NULL = the default stream).  Buffers must stay alive
+ *     until that work has completed.
+ *   - cu_seqlens and thw are HOST int32 arrays, read before the call returns
+ *     (they fix the launch geometry and travel to the kernels by value).
+ *   - Element type is bf16 (VFM_BF16).  Accumulation is fp32.
+ *   - head_dim is 64 or 128.  n_seqs is at most VFM_MAX_SEQS.  Empty clips
+ *     (cu_seqlens[s] == cu_seqlens[s+1]) are legal and do no work.
+ *   - Every function returns a vfm_status; 0 is success.  Argument errors are
+ *     detected before anything is launched and leave all outputs untouched.
+ *   - Re-entrant: no global mutable state.
+ */
+#ifndef VFM_H
+#define VFM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VFM_MAX_SEQS 256
+
+#define VFM_API __attribute__((visibility("default")))
+
+typedef enum {
+  VFM_OK = 0,
+  VFM_ERR_NULL = 1,        /* a required pointer is NULL */
+  VFM_ERR_SHAPE = 2,       /* total_tokens/n_heads/head_dim/n_seqs out of range */
+  VFM_ERR_CU_SEQLENS = 3,  /* not starting at 0, decreasing, or not ending at total_tokens */
+  VFM_ERR_THW = 4,         /* T*H*W differs from the clip length, or a non-positive extent */
+  VFM_ERR_SPLIT = 5,       /* dim_t+dim_h+dim_w != head_dim, or an odd/negative part */
+  VFM_ERR_DTYPE = 6,       /* unsupported element type */
+  VFM_ERR_WORKSPACE = 7,   /* workspace NULL, misaligned or too small */
+  VFM_ERR_LAUNCH = 8,      /* the HIP runtime refused a launch */
+  VFM_ERR_ALIGN = 9        /* a tensor pointer is not 16-byte aligned */
+} vfm_status;
+
+typedef enum { VFM_BF16 = 0, VFM_F32 = 1 /* not implemented: VFM_ERR_DTYPE */ } vfm_dtype;
+
+/*
+ * 3D rotary position embedding, in place, on x[total_tokens, n_heads, head_dim]
+ * (applied to q and to k before attention).
+ *
+ * Token n of clip s has local index r = n - cu_seqlens[s] and grid position
+ * t = r / (H*W), h = (r / W) % H, w = r % W with (T,H,W) = thw[3s..3s+2]
+ * (flatten order of Sections 4.2/4.6).  The head vector is cut into three
+ * contiguous slices of widths dim_t, dim_h, dim_w.  In the slice of axis A
+ * (width d_A, position p_A) the adjacent pair (x[2i], x[2i+1]), i < d_A/2, is
+ * rotated by phi = p_A * theta^(-2i/d_A):
+ *     x[2i]'   = x[2i] cos(phi) - x[2i+1] sin(phi)
+ *     x[2i+1]' = x[2i] sin(phi) + x[2i+1] cos(phi)
+ * inverse != 0 rotates by -phi (the transpose; carries gradients back).
+ * Angles and products are fp32; the result is rounded to bf16 (nearest even).
+ *
+ * thw: host [n_seqs,3]; cu_seqlens: host [n_seqs+1].
+ * Errors: NULL, SHAPE, CU_SEQLENS, THW, SPLIT, DTYPE, ALIGN, LAUNCH.
+ */
+VFM_API int vfm_rope3d(void* x, const int32_t* thw, const int32_t* cu_seqlens, int n_seqs,
+               int total_tokens, int n_heads, int head_dim,
+               int dim_t, int dim_h, int dim_w, float theta, int inverse,
+               vfm_dtype dt, void* hip_stream);
+
+/*
+ * Attention forward.  For every clip [a,b) and head h:
+ *     S_ij  = scale * sum_d q[i,h,d] k[j,h,d]          i, j in [a,b)
+ *     out_i = sum_j softmax_j(S_ij) v[j,h,:]
+ *     lse_i = ln sum_j exp(S_ij)                        (natural log)
+ * q, k, v, out: bf16 [total_tokens, n_heads, head_dim]; lse: fp32
+ * [n_heads, total_tokens].  out and lse are fully overwritten for every token
+ * of a non-empty clip.  The result is bitwise reproducible from run to run.
+ * Errors: NULL, SHAPE, CU_SEQLENS, DTYPE, ALIGN, LAUNCH.
+ */
+VFM_API int vfm_attn_fwd(const void* q, const void* k, const void* v,
+                 const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                 int n_heads, int head_dim, float scale,
+                 void* out, float* lse, vfm_dtype dt, void* hip_stream);
+
+/*
+ * Bytes of device workspace vfm_attn_bwd needs for these sizes (0 if the sizes
+ * are invalid).  The workspace holds the fp32 dq accumulator and
+ * Delta_i = sum_d dout[i,h,d] out[i,h,d]; its contents need not be initialised
+ * and are garbage afterwards.
+ */
+VFM_API size_t vfm_attn_bwd_workspace_size(int total_tokens, int n_heads, int head_dim);
+
+/*
+ * Attention backward: gradients of sum(out * dout) with respect to q, k, v,
+ * given the forward's out and lse (no gradient flows into lse):
+ *     P_ij   = exp(S_ij - lse_i)
+ *     dv_j   = sum_i P_ij dout_i
+ *     dS_ij  = P_ij (sum_d dout[i,d] v[j,d] - Delta_i)
+ *     dq_i   = scale * sum_j dS_ij k_j
+ *     dk_j   = scale * sum_i dS_ij q_i
+ * dq, dk, dv: bf16 [total_tokens, n_heads, head_dim], fully overwritten (not
+ * accumulated into).  workspace: device, 256-byte aligned, at least
+ * vfm_attn_bwd_workspace_size() bytes.  dq is summed with fp32 atomics, so its
+ * last bits may differ from run to run; dk and dv are reproducible.
+ * Errors: NULL, SHAPE, CU_SEQLENS, DTYPE, ALIGN, WORKSPACE, LAUNCH.
+ */
+VFM_API int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out,
+                 const float* lse, const void* dout, const int32_t* cu_seqlens,
+                 int n_seqs, int total_tokens, int n_heads, int head_dim, float scale,
+                 void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                 vfm_dtype dt, void* hip_stream);
+
+/* Static, human-readable text for a vfm_status. */
+VFM_API const char* vfm_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VFM_H */

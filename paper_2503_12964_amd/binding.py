@@ -1,0 +1,155 @@
+"""Thin ctypes binding over libvfm.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels of the library; this module
+turns torch tensors (device memory) and host int32 arrays into the pointers and
+sizes the C ABI takes (include/vfm.h).  There is no fallback: if the library
+is not built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvfm.so")
+
+VFM_BF16 = 0
+VFM_F32 = 1
+VFM_MAX_SEQS = 256
+
+EXPORTS = ("vfm_rope3d", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_strerror")
+
+_lib = None
+
+
+class VfmError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"libvfm status {status}: {message}")
+        self.status = status
+
+
+def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
+    """dlopen libvfm.so and declare the C signatures.  Raises if it is missing."""
+    global _lib
+    if _lib is not None and path == LIB_PATH:
+        return _lib
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            f"{path} not found: build it first (python -m paper_2503_12964_amd.build); "
+            "there is no CPU fallback")
+    lib = ctypes.CDLL(path)
+    c_int, c_float, c_void_p, c_size_t = ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
+    p_i32 = ctypes.POINTER(ctypes.c_int32)
+    lib.vfm_rope3d.restype = c_int
+    lib.vfm_rope3d.argtypes = [c_void_p, p_i32, p_i32, c_int, c_int, c_int, c_int, c_int, c_int, c_int,
+                               c_float, c_int, c_int, c_void_p]
+    lib.vfm_attn_fwd.restype = c_int
+    lib.vfm_attn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, p_i32, c_int, c_int, c_int, c_int, c_float,
+                                 c_void_p, c_void_p, c_int, c_void_p]
+    lib.vfm_attn_bwd_workspace_size.restype = c_size_t
+    lib.vfm_attn_bwd_workspace_size.argtypes = [c_int, c_int, c_int]
+    lib.vfm_attn_bwd.restype = c_int
+    lib.vfm_attn_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, p_i32, c_int,
+                                 c_int, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p, c_void_p,
+                                 c_size_t, c_int, c_void_p]
+    lib.vfm_strerror.restype = ctypes.c_char_p
+    lib.vfm_strerror.argtypes = [c_int]
+    if path == LIB_PATH:
+        _lib = lib
+    return lib
+
+
+def strerror(status: int) -> str:
+    return load_library().vfm_strerror(int(status)).decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise VfmError(status, strerror(status))
+
+
+def _host_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def _i32_ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(int(getattr(stream, "cuda_stream", stream)))
+
+
+def _dev(t, name: str) -> ctypes.c_void_p:
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return VFM_BF16
+    if t.dtype == torch.float32:
+        return VFM_F32
+    raise ValueError(f"unsupported dtype {t.dtype}")
+
+
+def vfm_rope3d(x, thw, cu_seqlens, dims: Sequence[int], theta: float = 10000.0,
+               inverse: bool = False, stream=None):
+    """In-place 3D RoPE on x[total, heads, head_dim] (device, bf16).  Returns x."""
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    g = _host_i32(thw).reshape(-1)
+    total, heads, hd = x.shape
+    _check(lib.vfm_rope3d(_dev(x, "x"), _i32_ptr(g), _i32_ptr(cu), int(cu.size - 1), int(total), int(heads),
+                          int(hd), int(dims[0]), int(dims[1]), int(dims[2]), float(theta), int(bool(inverse)),
+                          _dtype_code(x), _stream_ptr(stream)))
+    return x
+
+
+def vfm_attn_fwd(q, k, v, cu_seqlens, scale: float, out=None, lse=None, stream=None) -> Tuple:
+    """out[total, heads, head_dim] (bf16) and lse[heads, total] (fp32) for packed q, k, v."""
+    import torch
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    total, heads, hd = q.shape
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((heads, total), dtype=torch.float32, device=q.device)
+    _check(lib.vfm_attn_fwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _i32_ptr(cu), int(cu.size - 1), int(total),
+                            int(heads), int(hd), float(scale), _dev(out, "out"), _dev(lse, "lse"),
+                            _dtype_code(q), _stream_ptr(stream)))
+    return out, lse
+
+
+def vfm_attn_bwd_workspace_size(total_tokens: int, n_heads: int, head_dim: int) -> int:
+    return int(load_library().vfm_attn_bwd_workspace_size(int(total_tokens), int(n_heads), int(head_dim)))
+
+
+def vfm_attn_bwd(q, k, v, out, lse, dout, cu_seqlens, scale: float, dq=None, dk=None, dv=None,
+                 workspace=None, stream=None) -> Tuple:
+    """dq, dk, dv (bf16, shape of q) given the forward's out and lse."""
+    import torch
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    total, heads, hd = q.shape
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    need = vfm_attn_bwd_workspace_size(total, heads, hd)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    _check(lib.vfm_attn_bwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"), _dev(lse, "lse"),
+                            _dev(dout, "dout"), _i32_ptr(cu), int(cu.size - 1), int(total), int(heads), int(hd),
+                            float(scale), _dev(dq, "dq"), _dev(dk, "dk"), _dev(dv, "dv"),
+                            _dev(workspace, "workspace"), int(workspace.numel() * workspace.element_size()),
+                            _dtype_code(q), _stream_ptr(stream)))
+    return dq, dk, dv

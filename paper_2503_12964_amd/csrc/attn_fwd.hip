@@ -1,0 +1,290 @@
+// Packed variable-length attention forward for gfx950 (bf16 MFMA, fp32 accumulate).
+//
+// One workgroup owns one (head, query tile) of one clip and streams that clip's
+// K/V tiles (kBC rows) through LDS, double buffered.  Each wavefront owns
+// NI blocks of 32 query rows.  Scores are produced transposed,
+//     S^T[j, i] = sum_d K[j, d] Q[i, d]         (32x32x16 MFMA, A = K rows, B = Q rows)
+// so that a lane holds 16 key positions of ONE query row per block: the row max
+// and row sum are in-lane reductions plus one exchange with lane^32, the O
+// rescale is a per-lane scalar, and the bf16 P registers are already the B
+// operand of
+//     O^T[d, i] += sum_j V[j, d] P^T[j, i]      (A = V^T via transposing LDS reads).
+// The contraction slots of that second MFMA are bound to key rows in the order the
+// first MFMA's accumulator registers hold them (runs of 4 rows), which is also what
+// a transposing LDS read returns, so P never leaves registers.
+#include "vfm_common.h"
+
+namespace vfm {
+
+constexpr int kFwdWaves = 4;
+constexpr int kFwdBC = 64;       // key/value rows per LDS tile
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kRescaleThreshold = 8.0f;  // in log2 units: lazily keep a stale row max up to 2^8
+
+template <int D, int NI>
+struct FwdCfg {
+  static constexpr int kBR = kFwdWaves * NI * 32;          // query rows per workgroup
+  static constexpr int kTileBytes = kFwdBC * D * 2;        // one K or V tile
+  static constexpr int kLdsBytes = 4 * kTileBytes;         // K,V x 2 stages
+  static constexpr int kChunksPerRow = D / 8;
+  static constexpr int kChunksPerThread = kFwdBC * kChunksPerRow / (kFwdWaves * 64);
+};
+
+template <int D, int NI>
+__global__ __launch_bounds__(kFwdWaves * 64, (NI == 1 ? 2 : 1))
+void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                     const __bf16* __restrict__ v, __bf16* __restrict__ out,
+                     float* __restrict__ lse, const SegTable segs, const UnitMap um,
+                     int total, int n_heads, float scale_log2) {
+  using Cfg = FwdCfg<D, NI>;
+  constexpr int KS = D / 16;   // k-steps of the QK^T contraction
+  constexpr int DB = D / 32;   // 32-wide blocks of the head dimension
+  constexpr int JB = kFwdBC / 32;
+  constexpr int CPT = Cfg::kChunksPerThread;
+
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  int head, tile;
+  if (!map_unit(um, blockIdx.x, head, tile)) return;
+  int seg_a, seg_b, q0;
+  find_tile(segs, Cfg::kBR, tile, seg_a, seg_b, q0);
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
+  const int lane = tid & 63;
+  const int c = lane & 31;
+  const int g = lane >> 5;
+  const size_t row_stride = (size_t)n_heads * D;   // elements between consecutive tokens
+  const __bf16* kbase = k + (size_t)head * D;
+  const __bf16* vbase = v + (size_t)head * D;
+
+  // ---- Q operands (B operand of S^T): lane holds row i = c, columns ks*16 + 8g..+7
+  bf16x8 qreg[NI][KS];
+  int qrow[NI];
+#pragma unroll
+  for (int ib = 0; ib < NI; ++ib) {
+    qrow[ib] = q0 + (wave * NI + ib) * 32 + c;
+    const int r = min(qrow[ib], seg_b - 1);
+    const __bf16* qp = q + (size_t)r * row_stride + (size_t)head * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qreg[ib][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+  }
+
+  // ---- K/V staging: thread t moves chunks t, t+256, ... of the tile
+  int st_row[CPT], st_chunk[CPT], st_lds[CPT];
+#pragma unroll
+  for (int x = 0; x < CPT; ++x) {
+    const int idx = tid + x * (kFwdWaves * 64);
+    st_row[x] = idx / Cfg::kChunksPerRow;
+    st_chunk[x] = idx % Cfg::kChunksPerRow;
+    st_lds[x] = tile_off<D>(st_row[x], st_chunk[x] * 8);
+  }
+  u32x4 kst[CPT], vst[CPT];
+  auto load_tile = [&](int j0) {
+#pragma unroll
+    for (int x = 0; x < CPT; ++x) {
+      const int r = min(j0 + st_row[x], seg_b - 1);
+      const size_t off = (size_t)r * row_stride + st_chunk[x] * 8;
+      kst[x] = *reinterpret_cast<const u32x4*>(kbase + off);
+      vst[x] = *reinterpret_cast<const u32x4*>(vbase + off);
+    }
+  };
+  auto store_tile = [&](int stage) {
+    char* kt = smem + stage * 2 * Cfg::kTileBytes;
+    char* vt = kt + Cfg::kTileBytes;
+#pragma unroll
+    for (int x = 0; x < CPT; ++x) {
+      *reinterpret_cast<u32x4*>(kt + st_lds[x]) = kst[x];
+      *reinterpret_cast<u32x4*>(vt + st_lds[x]) = vst[x];
+    }
+  };
+
+  // ---- per-lane LDS read offsets (within a tile).  The swizzle XORs bits 4..7 of the
+  // byte offset with a function of (row & 15) only, so the offsets of the other
+  // k-steps / head-dim blocks / row blocks follow from one base per lane:
+  //   K rows as A operand: row jb*32 + c, columns ks*16 + 8g
+  //       off = (kbase ^ (ks << 5)) + jb*32*rowbytes
+  //   V^T as A operand via transposing reads.  For k-step s2 of key block jb the 8
+  //   contraction slots of lane group g are key rows jb*32 + 16*s2 + {4g..4g+3} (t=0)
+  //   and {8+4g..8+4g+3} (t=1); the lane addresses row +((lane&15)>>2), columns
+  //   db*32 + 16*((lane>>4)&1) + 4*(lane&3):
+  //       off = (vbase[t] ^ (db << 6)) + (jb*32 + 16*s2)*rowbytes
+  constexpr int RB = D * 2;
+  const int kbase_off = tile_off<D>(c, 8 * g);
+  int vbase_off[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+    vbase_off[t] = tile_off<D>(8 * t + 4 * g + ((lane & 15) >> 2),
+                               16 * ((lane >> 4) & 1) + 4 * (lane & 3));
+
+  f32x16 oacc[NI][DB];
+  float m_run[NI], l_run[NI];
+#pragma unroll
+  for (int ib = 0; ib < NI; ++ib) {
+    m_run[ib] = -INFINITY;
+    l_run[ib] = 0.f;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[ib][db][r] = 0.f;
+  }
+
+  const int n_kv = seg_b - seg_a;
+  const int n_tiles = (n_kv + kFwdBC - 1) / kFwdBC;
+
+  load_tile(seg_a);
+  store_tile(0);
+  __syncthreads();
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const int j0 = seg_a + t * kFwdBC;
+    const bool more = (t + 1 < n_tiles);
+    if (more) load_tile(j0 + kFwdBC);
+
+    const char* kt = smem + (t & 1) * 2 * Cfg::kTileBytes;
+    const char* vt = kt + Cfg::kTileBytes;
+
+    // ---- S^T = K Q^T
+    f32x16 sacc[JB][NI];
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+      for (int ib = 0; ib < NI; ++ib)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[jb][ib][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int jb = 0; jb < JB; ++jb) {
+        const bf16x8 ka = lds_read_b128(kt, (kbase_off ^ (ks << 5)) + jb * 32 * RB);
+#pragma unroll
+        for (int ib = 0; ib < NI; ++ib) sacc[jb][ib] = mfma32(ka, qreg[ib][ks], sacc[jb][ib]);
+      }
+    }
+
+    // ---- mask keys past the end of the clip (last tile only)
+    if (j0 + kFwdBC > seg_b) {
+#pragma unroll
+      for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int j = j0 + jb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (j >= seg_b) {
+#pragma unroll
+            for (int ib = 0; ib < NI; ++ib) sacc[jb][ib][r] = -INFINITY;
+          }
+        }
+    }
+
+    // ---- online softmax (log2 domain), P -> bf16
+    bf16x8 pb[NI][JB][2];
+#pragma unroll
+    for (int ib = 0; ib < NI; ++ib) {
+      float mx = sacc[0][ib][0];
+#pragma unroll
+      for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[jb][ib][r]);
+      mx = pair_max(mx) * scale_log2;
+      const float m_new = fmaxf(m_run[ib], mx);
+      // The reference point only moves when some row's max grew by more than the
+      // threshold; otherwise exponentials are taken against the stale max (exact
+      // after the final normalisation, and bounded by 2^threshold).
+      if (__builtin_amdgcn_ballot_w64(m_new - m_run[ib] > kRescaleThreshold) != 0) {
+        const float alpha = fast_exp2(m_run[ib] - m_new);
+        l_run[ib] *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[ib][db][r] *= alpha;
+        m_run[ib] = m_new;
+      }
+      const float mref = m_run[ib];
+      float lsum = 0.f;
+#pragma unroll
+      for (int jb = 0; jb < JB; ++jb) {
+        f32x8 p0, p1;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+          p0[r] = fast_exp2(sacc[jb][ib][r] * scale_log2 - mref);
+          p1[r] = fast_exp2(sacc[jb][ib][8 + r] * scale_log2 - mref);
+          lsum += p0[r] + p1[r];
+        }
+        pb[ib][jb][0] = to_bf16x8(p0);
+        pb[ib][jb][1] = to_bf16x8(p1);
+      }
+      l_run[ib] += lsum;
+    }
+
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 va = join_tr(
+              lds_read_tr(vt, (vbase_off[0] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB),
+              lds_read_tr(vt, (vbase_off[1] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB));
+#pragma unroll
+          for (int ib = 0; ib < NI; ++ib) oacc[ib][db] = mfma32(va, pb[ib][jb][s2], oacc[ib][db]);
+        }
+
+    if (more) store_tile((t + 1) & 1);
+    __syncthreads();
+  }
+
+  // ---- epilogue: normalise, write out (bf16) and lse (natural log)
+#pragma unroll
+  for (int ib = 0; ib < NI; ++ib) {
+    const float l_tot = pair_sum(l_run[ib]);
+    const float inv = 1.0f / l_tot;
+    const int i = qrow[ib];
+    if (i < seg_b) {
+      __bf16* op = out + (size_t)i * row_stride + (size_t)head * D + 4 * g;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          f32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = oacc[ib][db][q4 * 4 + e] * inv;
+          *reinterpret_cast<bf16x4*>(op + db * 32 + q4 * 8) = to_bf16x4(o);
+        }
+      if (g == 0) lse[(size_t)head * total + i] = (m_run[ib] + __log2f(l_tot)) * kLn2;
+    }
+  }
+}
+
+template <int D, int NI>
+static hipError_t launch_fwd_cfg(const void* q, const void* k, const void* v, const SegTable& segs,
+                                 int total, int n_heads, float scale, void* out, float* lse,
+                                 hipStream_t stream) {
+  using Cfg = FwdCfg<D, NI>;
+  int tiles = 0;
+  for (int s = 0; s < segs.n; ++s) tiles += (segs.len[s] + Cfg::kBR - 1) / Cfg::kBR;
+  if (tiles == 0) return hipSuccess;
+  UnitMap um;
+  um.tiles_per_head = tiles;
+  um.n_units = tiles * n_heads;
+  um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
+  const int grid = um.chunk * kNumXcd;
+  auto kern = attn_fwd_kernel<D, NI>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+  if (e != hipSuccess) return e;
+  kern<<<grid, kFwdWaves * 64, Cfg::kLdsBytes, stream>>>(
+      (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (__bf16*)out, lse, segs, um, total,
+      n_heads, scale * kLog2e);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, const SegTable& segs,
+                           int total, int n_heads, int head_dim, float scale, void* out,
+                           float* lse, hipStream_t stream) {
+  if (head_dim == 128) return launch_fwd_cfg<128, 2>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
+  return launch_fwd_cfg<64, 2>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
+}
+
+}  // namespace vfm

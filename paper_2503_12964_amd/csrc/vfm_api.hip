@@ -1,0 +1,166 @@
+// C ABI of libvfm: argument validation, clip tables, launches.  No allocation, no sync.
+#include <math.h>
+#include <stdlib.h>
+
+#include <algorithm>
+
+#include "vfm_common.h"
+
+namespace {
+
+using vfm::RopeTable;
+using vfm::SegTable;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(int n_seqs, int total_tokens, int n_heads, int head_dim) {
+  if (n_seqs < 0 || n_seqs > VFM_MAX_SEQS || total_tokens < 0 || n_heads < 1 || n_heads > 65535)
+    return VFM_ERR_SHAPE;
+  if (head_dim != 64 && head_dim != 128) return VFM_ERR_SHAPE;
+  // element offsets are 64-bit in the kernels; token*heads must still fit an int
+  if ((long long)total_tokens * n_heads > 0x7fffffffLL) return VFM_ERR_SHAPE;
+  return VFM_OK;
+}
+
+int check_cu(const int32_t* cu, int n_seqs, int total_tokens) {
+  if (cu[0] != 0) return VFM_ERR_CU_SEQLENS;
+  for (int s = 0; s < n_seqs; ++s)
+    if (cu[s + 1] < cu[s]) return VFM_ERR_CU_SEQLENS;
+  if (cu[n_seqs] != total_tokens) return VFM_ERR_CU_SEQLENS;
+  return VFM_OK;
+}
+
+// Non-empty clips, longest first (ties keep packed order): the tile scheduler
+// hands out the most expensive tiles first.
+void build_seg_table(const int32_t* cu, int n_seqs, SegTable* t) {
+  int order[VFM_MAX_SEQS];
+  int n = 0;
+  for (int s = 0; s < n_seqs; ++s)
+    if (cu[s + 1] > cu[s]) order[n++] = s;
+  std::stable_sort(order, order + n, [&](int a, int b) {
+    return (cu[a + 1] - cu[a]) > (cu[b + 1] - cu[b]);
+  });
+  t->n = n;
+  for (int i = 0; i < n; ++i) {
+    t->start[i] = cu[order[i]];
+    t->len[i] = cu[order[i] + 1] - cu[order[i]];
+  }
+  for (int i = n; i < VFM_MAX_SEQS; ++i) { t->start[i] = 0; t->len[i] = 0; }
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+
+const char* vfm_strerror(int status) {
+  switch (status) {
+    case VFM_OK: return "ok";
+    case VFM_ERR_NULL: return "a required pointer is NULL";
+    case VFM_ERR_SHAPE: return "total_tokens, n_heads, head_dim (64 or 128), n_seqs (<= 256) or scale (> 0, finite) out of range";
+    case VFM_ERR_CU_SEQLENS: return "cu_seqlens must start at 0, be non-decreasing and end at total_tokens";
+    case VFM_ERR_THW: return "each clip needs positive T, H, W with T*H*W equal to its length";
+    case VFM_ERR_SPLIT: return "dim_t + dim_h + dim_w must equal head_dim, each part even and >= 0";
+    case VFM_ERR_DTYPE: return "unsupported element type (only bf16)";
+    case VFM_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or smaller than vfm_attn_bwd_workspace_size()";
+    case VFM_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
+    case VFM_ERR_ALIGN: return "tensor pointers must be 16-byte aligned";
+    default: return "unknown status";
+  }
+}
+
+int vfm_rope3d(void* x, const int32_t* thw, const int32_t* cu_seqlens, int n_seqs,
+               int total_tokens, int n_heads, int head_dim, int dim_t, int dim_h, int dim_w,
+               float theta, int inverse, vfm_dtype dt, void* hip_stream) {
+  if (!x || !thw || !cu_seqlens) return VFM_ERR_NULL;
+  if (dt != VFM_BF16) return VFM_ERR_DTYPE;
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  if (st) return st;
+  if (!(theta > 0.f) || !isfinite(theta)) return VFM_ERR_SHAPE;
+  if (dim_t < 0 || dim_h < 0 || dim_w < 0 || (dim_t | dim_h | dim_w) & 1 ||
+      dim_t + dim_h + dim_w != head_dim)
+    return VFM_ERR_SPLIT;
+  st = check_cu(cu_seqlens, n_seqs, total_tokens);
+  if (st) return st;
+  RopeTable tab;
+  tab.n = n_seqs;
+  for (int s = 0; s < n_seqs; ++s) {
+    const long long T = thw[3 * s], H = thw[3 * s + 1], W = thw[3 * s + 2];
+    const int len = cu_seqlens[s + 1] - cu_seqlens[s];
+    if (len == 0 && T * H * W == 0 && T >= 0 && H >= 0 && W >= 0) {  // empty clip
+      tab.cu[s] = cu_seqlens[s]; tab.hw[s] = 1; tab.w[s] = 1;
+      continue;
+    }
+    if (T <= 0 || H <= 0 || W <= 0 || T * H * W != len) return VFM_ERR_THW;
+    tab.cu[s] = cu_seqlens[s];
+    tab.hw[s] = (int)(H * W);
+    tab.w[s] = (int)W;
+  }
+  tab.cu[n_seqs] = total_tokens;
+  for (int s = n_seqs; s < VFM_MAX_SEQS; ++s) { tab.cu[s + 1] = total_tokens; tab.hw[s] = 1; tab.w[s] = 1; }
+  if (!aligned16(x)) return VFM_ERR_ALIGN;
+  if (total_tokens == 0) return VFM_OK;
+  hipError_t e = vfm::launch_rope3d(x, tab, total_tokens, n_heads, head_dim, dim_t, dim_h, dim_w,
+                                    theta, inverse, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+}
+
+int vfm_attn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
+                 int n_seqs, int total_tokens, int n_heads, int head_dim, float scale, void* out,
+                 float* lse, vfm_dtype dt, void* hip_stream) {
+  if (!q || !k || !v || !cu_seqlens || !out || !lse) return VFM_ERR_NULL;
+  if (dt != VFM_BF16) return VFM_ERR_DTYPE;
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  if (st) return st;
+  if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
+  st = check_cu(cu_seqlens, n_seqs, total_tokens);
+  if (st) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
+    return VFM_ERR_ALIGN;
+  if (total_tokens == 0) return VFM_OK;
+  SegTable segs;
+  build_seg_table(cu_seqlens, n_seqs, &segs);
+  hipError_t e = vfm::launch_attn_fwd(q, k, v, segs, total_tokens, n_heads, head_dim, scale, out,
+                                      lse, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+}
+
+size_t vfm_attn_bwd_workspace_size(int total_tokens, int n_heads, int head_dim) {
+  if (check_shape(0, total_tokens, n_heads, head_dim)) return 0;
+  const size_t rows = (size_t)total_tokens * n_heads;
+  return align_up(rows * head_dim * sizeof(float), 256) + align_up(rows * sizeof(float), 256);
+}
+
+int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                 const void* dout, const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                 int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
+                 void* workspace, size_t workspace_bytes, vfm_dtype dt, void* hip_stream) {
+  if (!q || !k || !v || !out || !lse || !dout || !cu_seqlens || !dq || !dk || !dv)
+    return VFM_ERR_NULL;
+  if (dt != VFM_BF16) return VFM_ERR_DTYPE;
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  if (st) return st;
+  if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
+  st = check_cu(cu_seqlens, n_seqs, total_tokens);
+  if (st) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse) ||
+      !aligned16(dout) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
+    return VFM_ERR_ALIGN;
+  if (total_tokens == 0) return VFM_OK;
+  const size_t need = vfm_attn_bwd_workspace_size(total_tokens, n_heads, head_dim);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
+    return VFM_ERR_WORKSPACE;
+  const size_t rows = (size_t)total_tokens * n_heads;
+  float* dq_acc = static_cast<float*>(workspace);
+  float* delta = reinterpret_cast<float*>(static_cast<char*>(workspace) +
+                                          align_up(rows * head_dim * sizeof(float), 256));
+  SegTable segs;
+  build_seg_table(cu_seqlens, n_seqs, &segs);
+  hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_tokens, n_heads,
+                                      head_dim, scale, dq, dk, dv, dq_acc, delta,
+                                      static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+}
+
+}  // extern "C"

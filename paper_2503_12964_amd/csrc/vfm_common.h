@@ -1,0 +1,161 @@
+// Shared device helpers and launcher declarations for libvfm (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/vfm.h"
+
+namespace vfm {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kNumXcd = 8;  // MI355X: 8 XCDs, workgroups are dealt to them round-robin
+
+// Non-empty clips, longest first.  Passed to kernels by value (kernel argument
+// memory), so no device allocation or copy is needed for the schedule.
+struct SegTable {
+  int n;
+  int start[VFM_MAX_SEQS];
+  int len[VFM_MAX_SEQS];
+};
+
+// Clip table for RoPE: all clips in packed order.
+struct RopeTable {
+  int n;
+  int cu[VFM_MAX_SEQS + 1];
+  int hw[VFM_MAX_SEQS];  // H*W of the clip's latent grid
+  int w[VFM_MAX_SEQS];   // W
+};
+
+// Work unit u = head * tiles_per_head + tile, units split into kNumXcd
+// contiguous chunks so that one XCD (one L2) walks the tiles of one head
+// together.  Returns false if this workgroup has nothing to do.
+struct UnitMap {
+  int tiles_per_head;
+  int n_units;
+  int chunk;  // ceil(n_units / kNumXcd)
+};
+
+__device__ __forceinline__ bool map_unit(const UnitMap& um, int block, int& head, int& tile) {
+  const int xcd = block % kNumXcd;
+  const int local = block / kNumXcd;
+  const int u = xcd * um.chunk + local;
+  if (local >= um.chunk || u >= um.n_units) return false;
+  head = u / um.tiles_per_head;
+  tile = u - head * um.tiles_per_head;
+  return true;
+}
+
+// Tile index (over all clips, longest clip first) -> clip range [a,b) and the
+// tile's first row.  rows_per_tile is the tile height.
+__device__ __forceinline__ void find_tile(const SegTable& segs, int rows_per_tile, int tile,
+                                          int& a, int& b, int& row0) {
+  int s = 0;
+  for (; s < segs.n - 1; ++s) {
+    const int nt = (segs.len[s] + rows_per_tile - 1) / rows_per_tile;
+    if (tile < nt) break;
+    tile -= nt;
+  }
+  a = segs.start[s];
+  b = a + segs.len[s];
+  row0 = a + tile * rows_per_tile;
+}
+
+// LDS tiles hold rows of D bf16 without padding; the 16-byte chunk index within
+// a row is XOR-ed with a function of the row so that both row-wise 16-byte reads
+// (16 consecutive rows, one chunk) and transposing 8-byte reads (4 consecutive
+// rows x 64 bytes) spread over all 64 banks.
+template <int D>
+__device__ __forceinline__ int swz(int row) {
+  if constexpr (D == 128) {
+    return ((row & 3) << 2) | ((row >> 2) & 3);
+  } else {
+    return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);
+  }
+}
+
+// Byte offset of element (row, col) in a swizzled [rows][D] bf16 tile; col is a
+// multiple of 4 and the returned address is valid for an 8-byte access (or a
+// 16-byte one when col is a multiple of 8).
+template <int D>
+__device__ __forceinline__ int tile_off(int row, int col) {
+  const int chunk = (col >> 3) ^ swz<D>(row);
+  return row * (D * 2) + chunk * 16 + (col & 7) * 2;
+}
+
+__device__ __forceinline__ bf16x8 lds_read_b128(const char* base, int off) {
+  return *reinterpret_cast<const bf16x8*>(base + off);
+}
+
+// Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes the
+// addresses name a 4 x 16 block of 16-bit elements (lane i: row i/4, columns
+// 4*(i%4)..+3); lane i receives column i of that block (4 elements, rows 0..3).
+__device__ __forceinline__ s16x4 lds_read_tr(const char* base, int off) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) s16x4*)(base + off));
+}
+
+__device__ __forceinline__ bf16x8 join_tr(s16x4 lo, s16x4 hi) {
+  s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// Value held by the lane 32 away (lane l <-> l^32).
+__device__ __forceinline__ float other_half(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  // r[0] = {low half, low half}, r[1] = {high half, high half}
+  const uint32_t lo = r[0], hi = r[1];
+  const uint32_t o = (threadIdx.x & 32) ? lo : hi;
+  return __builtin_bit_cast(float, o);
+}
+
+// max / sum over the lane pair (l, l^32); every lane gets the result.
+__device__ __forceinline__ float pair_max(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const uint32_t lo = r[0], hi = r[1];
+  return fmaxf(__builtin_bit_cast(float, lo), __builtin_bit_cast(float, hi));
+}
+__device__ __forceinline__ float pair_sum(float x) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  const uint32_t lo = r[0], hi = r[1];
+  return __builtin_bit_cast(float, lo) + __builtin_bit_cast(float, hi);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ bf16x8 to_bf16x8(f32x8 v) { return __builtin_convertvector(v, bf16x8); }
+__device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) { return __builtin_convertvector(v, bf16x4); }
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// ---- launchers (defined next to their kernels) -----------------------------
+hipError_t launch_rope3d(void* x, const RopeTable& tab, int total, int n_heads, int head_dim,
+                         int dim_t, int dim_h, int dim_w, float theta, int inverse,
+                         hipStream_t stream);
+
+hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, const SegTable& segs,
+                           int total, int n_heads, int head_dim, float scale, void* out,
+                           float* lse, hipStream_t stream);
+
+hipError_t launch_attn_bwd(const void* q, const void* k, const void* v, const void* out,
+                           const float* lse, const void* dout, const SegTable& segs, int total,
+                           int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
+                           float* dq_acc, float* delta, hipStream_t stream);
+
+}  // namespace vfm

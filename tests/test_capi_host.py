@@ -1,0 +1,107 @@
+"""Host-side checks of the C ABI: the library loads, exports what include/vfm.h declares,
+and rejects bad arguments before launching anything (so no GPU is needed)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2503_12964_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2503_12964_amd.build import build_lib
+        build_lib(verbose=False)
+    return binding.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "vfm.h")).read()
+    declared = set(re.findall(r"VFM_API\s+[\w\s\*]+?\b(vfm_\w+)\s*\(", text))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_strerror_texts(lib):
+    assert lib.vfm_strerror(0) == b"ok"
+    texts = {lib.vfm_strerror(i) for i in range(10)}
+    assert len(texts) == 10 and b"unknown status" not in texts
+    assert lib.vfm_strerror(99) == b"unknown status"
+
+
+FAKE = ctypes.c_void_p(0x10000)      # never dereferenced: validation precedes any launch
+ODD = ctypes.c_void_p(0x10008)
+
+
+def _i32(a):
+    arr = np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+    return arr, arr.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _fwd(lib, cu, total, heads=2, hd=128, scale=0.1, q=FAKE, out=FAKE, dt=0, n_seqs=None):
+    arr, p = _i32(cu)
+    n = len(cu) - 1 if n_seqs is None else n_seqs
+    return lib.vfm_attn_fwd(q, FAKE, FAKE, p, n, total, heads, hd, scale, out, FAKE, dt, None)
+
+
+def test_fwd_argument_errors(lib):
+    assert _fwd(lib, [0, 8], 8, q=None) == 1
+    assert _fwd(lib, [0, 8], 8, out=None) == 1
+    assert _fwd(lib, [0, 8], 8, hd=96) == 2
+    assert _fwd(lib, [0, 8], 8, heads=0) == 2
+    assert _fwd(lib, [0, 8], 8, scale=0.0) == 2
+    assert _fwd(lib, [0, 8], 8, scale=float("nan")) == 2
+    assert _fwd(lib, [0] * 300, 0, n_seqs=299) == 2            # more clips than VFM_MAX_SEQS
+    assert _fwd(lib, [1, 8], 8) == 3
+    assert _fwd(lib, [0, 5, 4, 8], 8) == 3
+    assert _fwd(lib, [0, 7], 8) == 3
+    assert _fwd(lib, [0, 8], 8, dt=1) == 6
+    assert _fwd(lib, [0, 8], 8, q=ODD) == 9
+    assert _fwd(lib, [0, 0, 0], 0) == 0                         # nothing to do is not an error
+
+
+def test_rope_argument_errors(lib):
+    def rope(thw, cu, total, dims=(32, 48, 48), hd=128, x=FAKE, theta=1e4, dt=0):
+        a, pa = _i32(thw)
+        b, pb = _i32(cu)
+        return lib.vfm_rope3d(x, pa, pb, len(cu) - 1, total, 4, hd, dims[0], dims[1], dims[2], theta, 0, dt, None)
+    assert rope([2, 2, 2], [0, 8], 8, x=None) == 1
+    assert rope([2, 2, 2], [0, 8], 8, dims=(32, 48, 40)) == 5
+    assert rope([2, 2, 2], [0, 8], 8, dims=(31, 49, 48)) == 5
+    assert rope([2, 2, 2], [0, 8], 8, dims=(-2, 82, 48)) == 5
+    assert rope([2, 2, 3], [0, 8], 8) == 4
+    assert rope([2, 0, 4], [0, 8], 8) == 4
+    assert rope([2, 2, 2], [0, 9], 8) == 3
+    assert rope([2, 2, 2], [0, 8], 8, theta=0.0) == 2
+    assert rope([2, 2, 2], [0, 8], 8, dt=1) == 6
+    assert rope([2, 2, 2], [0, 8], 8, x=ODD) == 9
+    assert rope([0, 0, 0], [0, 0], 0) == 0
+
+
+def test_bwd_argument_errors_and_workspace(lib):
+    size = lib.vfm_attn_bwd_workspace_size
+    assert size(0, 2, 128) == 0 or size(0, 2, 128) % 256 == 0
+    assert size(10, 2, 96) == 0
+    n = size(1000, 4, 128)
+    assert n >= 1000 * 4 * 128 * 4 + 1000 * 4 * 4 and n % 256 == 0
+    arr, p = _i32([0, 8])
+
+    def bwd(ws=FAKE, ws_bytes=1 << 30, dq=FAKE, cu=p, total=8):
+        return lib.vfm_attn_bwd(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, cu, 1, total, 2, 128, 0.1, dq, FAKE, FAKE,
+                                ws, ws_bytes, 0, None)
+    assert bwd(dq=None) == 1
+    assert bwd(ws=None) == 7
+    assert bwd(ws_bytes=16) == 7
+    assert bwd(ws=ctypes.c_void_p(0x10010)) == 7                # not 256-byte aligned
+    assert bwd(total=9) == 3
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(FileNotFoundError):
+        binding.load_library(str(tmp_path / "libvfm.so"))
