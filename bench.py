@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed 3D-RoPE attention hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic video-latent
+tokens: vfm_rope3d(q), vfm_rope3d(k), vfm_attn_fwd, vfm_attn_bwd.  The default
+workload is the 720p-class 121-frame latent (T,H,W = 16,44,80 -> 56,320 tokens,
+32 heads, head_dim 128, bf16).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--no-cpu-baseline]
+
+FLOP convention (algorithmic, block-diagonal pairs only): forward 4*D and
+backward 10*D flops per (query, key) pair per head.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak (published)
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel from `rocprofv3 --pmc` (FETCH_SIZE and
+# WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def _device_tensors(wl):
+    import torch
+    from paper_2503_12964_amd import workloads as W
+    t = {}
+    for name in ("q", "k", "v", "dout"):
+        bits = W.make_inputs(wl, tensors=(name,))[name]
+        t[name] = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+        del bits
+    return t
+
+
+def _cpu_baseline(wl, rows: int = 24576):
+    """The fp64 oracle, as it stands, on a bounded sample: `rows` query rows of head 0."""
+    from oracle import vfm_oracle as orc
+    from paper_2503_12964_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max((p.get("num_threads", 1) for p in threadpool_info()), default=1)
+    except Exception:
+        cores = os.cpu_count() or 1
+    one = W.Workload(wl.name, wl.grids, 1, wl.head_dim, wl.rope_dims, wl.seed, wl.backward)
+    inp = W.make_inputs(one)
+    q, k, v, do = (W.bf16_bits_to_f32(inp[n]).astype(np.float64) for n in ("q", "k", "v", "dout"))
+    rows = min(rows, wl.seqlens[0])
+    sel = np.arange(rows)
+    t0 = time.perf_counter()
+    orc.attn_fwd_rows(q, k, v, wl.cu_seqlens, wl.scale, 0, sel)
+    if wl.backward:
+        orc.attn_bwd_rows(q, k, v, do, wl.cu_seqlens, wl.scale, 0, sel)
+    dt = time.perf_counter() - t0
+    per_pair = (4 + (10 if wl.backward else 0)) * wl.head_dim
+    flops = float(per_pair) * rows * wl.seqlens[0]
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"{wl.name} head 0, first {rows} of {wl.seqlens[0]} query rows of clip 0, "
+                  f"{'fwd+bwd' if wl.backward else 'fwd'}, numpy fp64, {dt:.2f} s",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2503_12964_amd import binding as B
+    from paper_2503_12964_amd import workloads as W
+
+    B.load_library()                      # fails loudly if libvfm.so is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    wl = W.WORKLOADS[args.workload]
+    t = _device_tensors(wl)
+    q, k, v, do = t["q"], t["k"], t["v"], t["dout"]
+    out = torch.empty_like(q)
+    lse = torch.empty((wl.n_heads, wl.total_tokens), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    ws = torch.empty(B.vfm_attn_bwd_workspace_size(wl.total_tokens, wl.n_heads, wl.head_dim),
+                     dtype=torch.uint8, device="cuda")
+    cu, thw = wl.cu_seqlens, wl.thw
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        B.vfm_rope3d(q, thw, cu, wl.rope_dims, wl.theta)
+        B.vfm_rope3d(k, thw, cu, wl.rope_dims, wl.theta)
+        if ev: ev[1].record()
+        B.vfm_attn_fwd(q, k, v, cu, wl.scale, out=out, lse=lse)
+        if ev: ev[2].record()
+        if wl.backward:
+            B.vfm_attn_bwd(q, k, v, out, lse, do, cu, wl.scale, dq=dq, dk=dk, dv=dv, workspace=ws)
+        if ev: ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_step = wall * 1e3 / args.steps
+    ms_rope = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    ms_fwd = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    ms_bwd = float(np.mean([e[2].elapsed_time(e[3]) for e in events])) if wl.backward else 0.0
+
+    f_fwd = wl.flops(backward=False)
+    f_all = wl.flops()
+    f_bwd = f_all - f_fwd
+    value = f_all / (ms_step * 1e-3) / 1e12
+    rope_bytes = 2 * 2 * wl.total_tokens * wl.n_heads * wl.head_dim * 2   # q and k, read + write
+    if wl.backward:
+        dom, dom_flops, dom_ms = "attn_bwd_kernel", f_bwd, ms_bwd
+        dom_note = "vfm_attn_bwd call: bwd_prepare + attn_bwd_kernel + bwd_finish; 10*D flops/pair/head"
+    else:
+        dom, dom_flops, dom_ms = "attn_fwd_kernel", f_fwd, ms_fwd
+        dom_note = "vfm_attn_fwd call: attn_fwd_kernel; 4*D flops/pair/head"
+    achieved = dom_flops / (dom_ms * 1e-3) / 1e12
+    result = {
+        "metric": "attention fwd+bwd TFLOP/s at 56K-token video latent" if args.workload == "C4"
+                  else f"attention TFLOP/s, workload {args.workload}",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: grids {list(wl.grids)} -> {wl.total_tokens} tokens, "
+                               f"{wl.n_heads} heads, head_dim {wl.head_dim}, rope split {list(wl.rope_dims)}, "
+                               f"{'rope+fwd+bwd' if wl.backward else 'rope+fwd'}",
+                   "flops_per_step": f_all, "pct_of_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS},
+        "breakdown": {"rope_ms": ms_rope, "fwd_ms": ms_fwd, "bwd_ms": ms_bwd,
+                      "fwd_tflops": f_fwd / (ms_fwd * 1e-3) / 1e12,
+                      "bwd_tflops": (f_bwd / (ms_bwd * 1e-3) / 1e12) if wl.backward else None,
+                      "attn_only_tflops": f_all / ((ms_fwd + ms_bwd) * 1e-3) / 1e12,
+                      "rope_gbs": rope_bytes / (ms_rope * 1e-3) / 1e9,
+                      "rope_frac_hbm_peak": rope_bytes / (ms_rope * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "ms": dom_ms, "note": dom_note},
+    }
+    del q, k, v, do, out, dq, dk, dv, ws, t
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = _cpu_baseline(wl)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
