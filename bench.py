@@ -135,8 +135,9 @@ def main() -> int:
     value = f_all / (ms_step * 1e-3) / 1e12
     rope_bytes = 2 * 2 * wl.total_tokens * wl.n_heads * wl.head_dim * 2   # q and k, read + write
     if wl.backward:
-        dom, dom_flops, dom_ms = "attn_bwd_kernel", f_bwd, ms_bwd
-        dom_note = "vfm_attn_bwd call: bwd_prepare + attn_bwd_kernel + bwd_finish; 10*D flops/pair/head"
+        dom, dom_flops, dom_ms = "attn_bwd_dkdv_kernel + attn_bwd_dq_kernel", f_bwd, ms_bwd
+        dom_note = ("vfm_attn_bwd call: bwd_prepare + attn_bwd_dkdv_kernel + attn_bwd_dq_kernel; "
+                    "10*D algorithmic flops/pair/head (the two kernels execute 14*D)")
     else:
         dom, dom_flops, dom_ms = "attn_fwd_kernel", f_fwd, ms_fwd
         dom_note = "vfm_attn_fwd call: attn_fwd_kernel; 4*D flops/pair/head"

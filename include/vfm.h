@@ -101,9 +101,9 @@ VFM_API int vfm_attn_fwd(const void* q, const void* k, const void* v,
 
 /*
  * Bytes of device workspace vfm_attn_bwd needs for these sizes (0 if the sizes
- * are invalid).  The workspace holds the fp32 dq accumulator and
- * Delta_i = sum_d dout[i,h,d] out[i,h,d]; its contents need not be initialised
- * and are garbage afterwards.
+ * are invalid).  The workspace holds Delta_i = sum_d dout[i,h,d] out[i,h,d]
+ * (fp32 [n_heads, total_tokens]); its contents need not be initialised and are
+ * garbage afterwards.
  */
 VFM_API size_t vfm_attn_bwd_workspace_size(int total_tokens, int n_heads, int head_dim);
 
@@ -117,8 +117,8 @@ VFM_API size_t vfm_attn_bwd_workspace_size(int total_tokens, int n_heads, int he
  *     dk_j   = scale * sum_i dS_ij q_i
  * dq, dk, dv: bf16 [total_tokens, n_heads, head_dim], fully overwritten (not
  * accumulated into).  workspace: device, 256-byte aligned, at least
- * vfm_attn_bwd_workspace_size() bytes.  dq is summed with fp32 atomics, so its
- * last bits may differ from run to run; dk and dv are reproducible.
+ * vfm_attn_bwd_workspace_size() bytes.  No atomics are used: dq, dk and dv are
+ * bitwise reproducible from run to run.
  * Errors: NULL, SHAPE, CU_SEQLENS, DTYPE, ALIGN, WORKSPACE, LAUNCH.
  */
 VFM_API int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out,

@@ -129,7 +129,7 @@ int vfm_attn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_
 size_t vfm_attn_bwd_workspace_size(int total_tokens, int n_heads, int head_dim) {
   if (check_shape(0, total_tokens, n_heads, head_dim)) return 0;
   const size_t rows = (size_t)total_tokens * n_heads;
-  return align_up(rows * head_dim * sizeof(float), 256) + align_up(rows * sizeof(float), 256);
+  return align_up(rows * sizeof(float), 256);
 }
 
 int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
@@ -151,14 +151,11 @@ int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, c
   const size_t need = vfm_attn_bwd_workspace_size(total_tokens, n_heads, head_dim);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
     return VFM_ERR_WORKSPACE;
-  const size_t rows = (size_t)total_tokens * n_heads;
-  float* dq_acc = static_cast<float*>(workspace);
-  float* delta = reinterpret_cast<float*>(static_cast<char*>(workspace) +
-                                          align_up(rows * head_dim * sizeof(float), 256));
+  float* delta = static_cast<float*>(workspace);
   SegTable segs;
   build_seg_table(cu_seqlens, n_seqs, &segs);
   hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_tokens, n_heads,
-                                      head_dim, scale, dq, dk, dv, dq_acc, delta,
+                                      head_dim, scale, dq, dk, dv, delta,
                                       static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
 }
