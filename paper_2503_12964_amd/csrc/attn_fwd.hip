@@ -71,32 +71,32 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     for (int ks = 0; ks < KS; ++ks) qreg[ib][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
   }
 
-  // ---- K/V staging: thread t moves chunks t, t+256, ... of the tile
-  int st_row[CPT], st_chunk[CPT], st_lds[CPT];
+  // ---- K/V staging with direct global->LDS loads (no staging registers, no LDS
+  // writes).  One wave instruction fills 64 consecutive 16-byte chunks of a tile;
+  // lane L of instruction (x, wave) owns LDS chunk P = (x*waves + wave)*64 + L, i.e.
+  // tile row P / chunks_per_row, physical chunk P % chunks_per_row, and fetches the
+  // logical chunk that the swizzle maps there.
+  int st_row[CPT], st_col[CPT];
 #pragma unroll
   for (int x = 0; x < CPT; ++x) {
-    const int idx = tid + x * (kFwdWaves * 64);
-    st_row[x] = idx / Cfg::kChunksPerRow;
-    st_chunk[x] = idx % Cfg::kChunksPerRow;
-    st_lds[x] = tile_off<D>(st_row[x], st_chunk[x] * 8);
+    const int p = (x * kFwdWaves + wave) * 64 + lane;
+    st_row[x] = p / Cfg::kChunksPerRow;
+    st_col[x] = ((p % Cfg::kChunksPerRow) ^ swz<D>(st_row[x])) * 8;
   }
-  u32x4 kst[CPT], vst[CPT];
-  auto load_tile = [&](int j0) {
-#pragma unroll
-    for (int x = 0; x < CPT; ++x) {
-      const int r = min(j0 + st_row[x], seg_b - 1);
-      const size_t off = (size_t)r * row_stride + st_chunk[x] * 8;
-      kst[x] = *reinterpret_cast<const u32x4*>(kbase + off);
-      vst[x] = *reinterpret_cast<const u32x4*>(vbase + off);
-    }
-  };
-  auto store_tile = [&](int stage) {
+  auto issue_tile = [&](int j0, int stage) {
     char* kt = smem + stage * 2 * Cfg::kTileBytes;
     char* vt = kt + Cfg::kTileBytes;
 #pragma unroll
     for (int x = 0; x < CPT; ++x) {
-      *reinterpret_cast<u32x4*>(kt + st_lds[x]) = kst[x];
-      *reinterpret_cast<u32x4*>(vt + st_lds[x]) = vst[x];
+      const int r = min(j0 + st_row[x], seg_b - 1);
+      const size_t off = (size_t)r * row_stride + st_col[x];
+      const int lds_off = (x * kFwdWaves + wave) * 1024;
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(kbase + off),
+          (__attribute__((address_space(3))) void*)(kt + lds_off), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(vbase + off),
+          (__attribute__((address_space(3))) void*)(vt + lds_off), 16, 0, 0);
     }
   };
 
@@ -133,35 +133,54 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   const int n_kv = seg_b - seg_a;
   const int n_tiles = (n_kv + kFwdBC - 1) / kFwdBC;
 
-  load_tile(seg_a);
-  store_tile(0);
+  issue_tile(seg_a, 0);
   __syncthreads();
 
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = seg_a + t * kFwdBC;
     const bool more = (t + 1 < n_tiles);
-    if (more) load_tile(j0 + kFwdBC);
 
     const char* kt = smem + (t & 1) * 2 * Cfg::kTileBytes;
     const char* vt = kt + Cfg::kTileBytes;
 
-    // ---- S^T = K Q^T
-    f32x16 sacc[JB][NI];
+    // ---- all K operand reads of this tile are issued before the first MFMA, so their
+    // LDS latency overlaps; the scheduling barriers keep the compiler from
+    // re-serialising read -> wait -> MFMA.
+    bf16x8 ka[JB][KS];
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb)
 #pragma unroll
-      for (int ib = 0; ib < NI; ++ib)
+      for (int ks = 0; ks < KS; ++ks)
+        ka[jb][ks] = lds_read_b128(kt, (kbase_off ^ (ks << 5)) + jb * 32 * RB);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- S^T = K Q^T (the first k-step starts from a zero accumulator)
+    f32x16 sacc[JB][NI];
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[jb][ib][r] = 0.f;
+    for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
+      for (int jb = 0; jb < JB; ++jb)
 #pragma unroll
-      for (int jb = 0; jb < JB; ++jb) {
-        const bf16x8 ka = lds_read_b128(kt, (kbase_off ^ (ks << 5)) + jb * 32 * RB);
+        for (int ib = 0; ib < NI; ++ib)
+          sacc[jb][ib] = mfma32(ka[jb][ks], qreg[ib][ks], ks == 0 ? zero16 : sacc[jb][ib]);
+
+    // ---- V^T operand reads are issued now, in the shadow of the S MFMAs and the softmax
+    s16x4 vlo[JB][2][DB], vhi[JB][2][DB];
 #pragma unroll
-        for (int ib = 0; ib < NI; ++ib) sacc[jb][ib] = mfma32(ka, qreg[ib][ks], sacc[jb][ib]);
-      }
-    }
+    for (int jb = 0; jb < JB; ++jb)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          vlo[jb][s2][db] = lds_read_tr(vt, (vbase_off[0] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB);
+          vhi[jb][s2][db] = lds_read_tr(vt, (vbase_off[1] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB);
+        }
+    __builtin_amdgcn_sched_barrier(0);
+    // The next tile's loads go out only now, after this iteration's last LDS read: the
+    // compiler orders every LDS read after an LDS-writing load behind a full vmcnt wait.
+    if (more) issue_tile(j0 + kFwdBC, (t + 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- mask keys past the end of the clip (last tile only)
     if (j0 + kFwdBC > seg_b) {
@@ -218,21 +237,20 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     }
 
     // ---- O^T += V^T P^T
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const bf16x8 va = join_tr(
-              lds_read_tr(vt, (vbase_off[0] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB),
-              lds_read_tr(vt, (vbase_off[1] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB));
+          const bf16x8 va = join_tr(vlo[jb][s2][db], vhi[jb][s2][db]);
 #pragma unroll
           for (int ib = 0; ib < NI; ++ib) oacc[ib][db] = mfma32(va, pb[ib][jb][s2], oacc[ib][db]);
         }
+    __builtin_amdgcn_sched_barrier(0);
 
-    if (more) store_tile((t + 1) & 1);
-    __syncthreads();
+    __syncthreads();   // waits for the next tile's loads (vmcnt) and for every wave's LDS reads
   }
 
   // ---- epilogue: normalise, write out (bf16) and lse (natural log)
@@ -283,8 +301,8 @@ static hipError_t launch_fwd_cfg(const void* q, const void* k, const void* v, co
 hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, const SegTable& segs,
                            int total, int n_heads, int head_dim, float scale, void* out,
                            float* lse, hipStream_t stream) {
-  if (head_dim == 128) return launch_fwd_cfg<128, 2>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
-  return launch_fwd_cfg<64, 2>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
+  if (head_dim == 128) return launch_fwd_cfg<128, 1>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
+  return launch_fwd_cfg<64, 1>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
 }
 
 }  // namespace vfm
