@@ -101,9 +101,9 @@ VFM_API int vfm_attn_fwd(const void* q, const void* k, const void* v,
 
 /*
  * Bytes of device workspace vfm_attn_bwd needs for these sizes (0 if the sizes
- * are invalid).  The workspace holds Delta_i = sum_d dout[i,h,d] out[i,h,d]
- * (fp32 [n_heads, total_tokens]); its contents need not be initialised and are
- * garbage afterwards.
+ * are invalid).  The workspace holds Delta_i = sum_d dout[i,h,d] out[i,h,d] and
+ * lse * log2(e) (two fp32 [n_heads, total_tokens] arrays); its contents need not
+ * be initialised and are garbage afterwards.
  */
 VFM_API size_t vfm_attn_bwd_workspace_size(int total_tokens, int n_heads, int head_dim);
 

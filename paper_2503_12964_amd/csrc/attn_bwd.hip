@@ -3,7 +3,7 @@
 // Three kernels, no atomics (device-wide fp32 atomics are executed at the memory side on
 // this chip and were measured to bound the fused variant), so every output is written
 // once and the result is bitwise reproducible:
-//   bwd_prepare : Delta[h,i] = sum_d dO[i,h,d] O[i,h,d]
+//   bwd_prepare : Delta[h,i] = sum_d dO[i,h,d] O[i,h,d]  and  lse2 = lse * log2(e)
 //   bwd_dkdv    : one workgroup owns kBC key/value rows of one (clip, head); its four
 //                 wavefronts own 32 of those rows each and keep their K and V rows, and
 //                 their dK^T / dV^T accumulators, in registers.  The workgroup walks the
@@ -31,7 +31,9 @@ constexpr float kLog2eB = 1.4426950408889634f;
 template <int D>
 __global__ __launch_bounds__(256) void bwd_prepare_kernel(const u32x4* __restrict__ out,
                                                           const u32x4* __restrict__ dout,
-                                                          float* __restrict__ delta, int total,
+                                                          const float* __restrict__ lse,
+                                                          float* __restrict__ delta,
+                                                          float* __restrict__ lse2, int total,
                                                           int n_heads) {
   constexpr int kLanesPerRow = D / 8;
   constexpr int kTokPerBlock = 256 / kLanesPerRow;
@@ -51,7 +53,10 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const u32x4* __restric
     }
 #pragma unroll
     for (int o = kLanesPerRow / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, kLanesPerRow);
-    if (valid && chunk == 0) delta[(size_t)h * total + tok] = s;
+    if (valid && chunk == 0) {
+      delta[(size_t)h * total + tok] = s;
+      lse2[(size_t)h * total + tok] = lse[(size_t)h * total + tok] * kLog2eB;   // log2 units
+    }
   }
 }
 
@@ -69,7 +74,7 @@ template <int D>
 __global__ __launch_bounds__(kBwdWaves * 64, 1)
 void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                      const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
-                     const float* __restrict__ lse, const float* __restrict__ delta,
+                     const float* __restrict__ lse2, const float* __restrict__ delta,
                      __bf16* __restrict__ dk, __bf16* __restrict__ dv,
                      const SegTable segs, const UnitMap um,
                      int total, int n_heads, float scale, float scale_log2) {
@@ -107,45 +112,44 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
       vreg[ks] = *reinterpret_cast<const bf16x8*>(v + off + ks * 16);
     }
   }
-  // ---- staging of Q / dO / lse / Delta tiles
-  int st_row[CPT], st_chunk[CPT], st_lds[CPT];
+  // ---- staging of Q / dO / lse2 / Delta tiles with direct global->LDS loads.
+  // Lane L of wave instruction (x, wave) owns LDS chunk P = (x*waves + wave)*64 + L of
+  // the tile (row P / chunks_per_row, physical chunk P % chunks_per_row) and fetches the
+  // logical chunk the swizzle maps there.  Waves 0 and 1 also fetch the 64 lse2 / Delta
+  // values (4 bytes per lane).
+  int st_row[CPT], st_col[CPT];
 #pragma unroll
   for (int x = 0; x < CPT; ++x) {
-    const int idx = tid + x * (kBwdWaves * 64);
-    st_row[x] = idx / Cfg::kChunksPerRow;
-    st_chunk[x] = idx % Cfg::kChunksPerRow;
-    st_lds[x] = tile_off<D>(st_row[x], st_chunk[x] * 8);
+    const int p = (x * kBwdWaves + wave) * 64 + lane;
+    st_row[x] = p / Cfg::kChunksPerRow;
+    st_col[x] = ((p % Cfg::kChunksPerRow) ^ swz<D>(st_row[x])) * 8;
   }
-  u32x4 qst[CPT], dost[CPT];
-  float stat = 0.f;  // threads 0..63: lse (log2 units), 64..127: Delta
-  const float* lse_h = lse + (size_t)head * total;
-  const float* delta_h = delta + (size_t)head * total;
-  auto load_tile = [&](int q0) {
-#pragma unroll
-    for (int x = 0; x < CPT; ++x) {
-      const int r = min(q0 + st_row[x], seg_b - 1);
-      const size_t off = (size_t)r * row_stride + head_off + st_chunk[x] * 8;
-      qst[x] = *reinterpret_cast<const u32x4*>(q + off);
-      dost[x] = *reinterpret_cast<const u32x4*>(dout + off);
-    }
-    if (tid < 2 * kBwdBQ) {
-      const int r = q0 + (tid & (kBwdBQ - 1));
-      if (tid < kBwdBQ) stat = (r < seg_b) ? lse_h[r] * kLog2eB : INFINITY;  // +inf => P = 0
-      else stat = (r < seg_b) ? delta_h[r] : 0.f;
-    }
-  };
-  auto store_tile = [&](int stage) {
+  const float* stat_src = (wave == 0 ? lse2 : delta) + (size_t)head * total;
+  auto issue_tile = [&](int q0, int stage) {
     char* qt = smem + stage * Cfg::kStageBytes;
     char* dot = qt + Cfg::kTileBytes;
 #pragma unroll
     for (int x = 0; x < CPT; ++x) {
-      *reinterpret_cast<u32x4*>(qt + st_lds[x]) = qst[x];
-      *reinterpret_cast<u32x4*>(dot + st_lds[x]) = dost[x];
+      const int r = min(q0 + st_row[x], seg_b - 1);
+      const size_t off = (size_t)r * row_stride + head_off + st_col[x];
+      const int lds_off = (x * kBwdWaves + wave) * 1024;
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(q + off),
+          (__attribute__((address_space(3))) void*)(qt + lds_off), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(dout + off),
+          (__attribute__((address_space(3))) void*)(dot + lds_off), 16, 0, 0);
     }
-    if (tid < 2 * kBwdBQ) reinterpret_cast<float*>(qt + 2 * Cfg::kTileBytes)[tid] = stat;
+    if (wave < 2) {
+      const int r = min(q0 + lane, seg_b - 1);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(stat_src + r),
+          (__attribute__((address_space(3))) void*)(qt + 2 * Cfg::kTileBytes + wave * (kBwdBQ * 4)),
+          4, 0, 0);
+    }
   };
 
-  // ---- per-lane LDS offsets.  The swizzles XOR low byte-offset bits with a function
+  // ---- per-lane LDS offsets.  The swizzle XORs low byte-offset bits with a function
   // of the low row bits only, so one base per lane serves every k-step / block:
   //   Q/dO rows as A operand (row ib*32 + c, columns ks*16 + 8g):
   //       off = (rbase ^ (ks << 5)) + ib*32*rowbytes
@@ -156,28 +160,27 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   const int rbase = tile_off<D>(c, 8 * g);
   int tbase[2];
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
+  for (int t = 0; t < 2; ++t)
     tbase[t] = tile_off<D>(8 * t + 4 * g + ((lane & 15) >> 2),
                            16 * ((lane >> 4) & 1) + 4 * (lane & 3));
-  }
 
   f32x16 dkacc[DB], dvacc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dkacc[db][r] = 0.f; dvacc[db][r] = 0.f; }
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   const int n_q = seg_b - seg_a;
   const int n_steps = (n_q + kBwdBQ - 1) / kBwdBQ;
 
-  load_tile(seg_a);
-  store_tile(0);
+  issue_tile(seg_a, 0);
   __syncthreads();
 
   for (int t = 0; t < n_steps; ++t) {
     const int q0 = seg_a + t * kBwdBQ;
     const bool more = (t + 1 < n_steps);
-    if (more) load_tile(q0 + kBwdBQ);
+    const bool tail_q = (q0 + kBwdBQ > seg_b);
 
     const char* qt = smem + (t & 1) * Cfg::kStageBytes;
     const char* dot = qt + Cfg::kTileBytes;
@@ -186,29 +189,59 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 
 #pragma unroll
     for (int ib = 0; ib < NIB; ++ib) {
-      f32x16 sacc, dpacc;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { sacc[r] = 0.f; dpacc[r] = 0.f; }
+      // ---- all row operands of this query block are requested before the first MFMA
+      bf16x8 qa[KS], da[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        sacc = mfma32(lds_read_b128(qt, (rbase ^ (ks << 5)) + ib * 32 * RB), kreg[ks], sacc);
-        dpacc = mfma32(lds_read_b128(dot, (rbase ^ (ks << 5)) + ib * 32 * RB), vreg[ks], dpacc);
+        const int off = (rbase ^ (ks << 5)) + ib * 32 * RB;
+        qa[ks] = lds_read_b128(qt, off);
+        da[ks] = lds_read_b128(dot, off);
       }
-      // P and dS for rows i = ib*32 + 8*q4 + 4g + e, column j = this lane's key
-      f32x16 p, ds;
+      __builtin_amdgcn_sched_barrier(0);
+      f32x16 sacc, dpacc;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        sacc = mfma32(qa[ks], kreg[ks], ks == 0 ? zero16 : sacc);
+        dpacc = mfma32(da[ks], vreg[ks], ks == 0 ? zero16 : dpacc);
+      }
+      // ---- transposed operands and row statistics, requested in the MFMAs' shadow
+      s16x4 dlo[2][DB], dhi[2][DB], qlo[2][DB], qhi[2][DB];
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const int o0 = (tbase[0] ^ (db << 6)) + (ib * 32 + 16 * s2) * RB;
+          const int o1 = (tbase[1] ^ (db << 6)) + (ib * 32 + 16 * s2) * RB;
+          dlo[s2][db] = lds_read_tr(dot, o0);
+          dhi[s2][db] = lds_read_tr(dot, o1);
+          qlo[s2][db] = lds_read_tr(qt, o0);
+          qhi[s2][db] = lds_read_tr(qt, o1);
+        }
+      f32x4 l4[4], d4[4];
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + ib * 32 + 8 * q4 + 4 * g);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(delta_s + ib * 32 + 8 * q4 + 4 * g);
+        l4[q4] = *reinterpret_cast<const f32x4*>(lse_s + ib * 32 + 8 * q4 + 4 * g);
+        d4[q4] = *reinterpret_cast<const f32x4*>(delta_s + ib * 32 + 8 * q4 + 4 * g);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      // the next tile's loads go out after this step's last LDS read
+      if (ib == NIB - 1) {
+        if (more) issue_tile(q0 + kBwdBQ, (t + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // ---- P and dS for rows i = ib*32 + 8*q4 + 4g + e, column j = this lane's key
+      f32x16 p, ds;
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = q4 * 4 + e;
-          float pv = fast_exp2(sacc[r] * scale_log2 - l4[e]);
+          float pv = fast_exp2(sacc[r] * scale_log2 - l4[q4][e]);
           if (tail_kv) pv = jvalid ? pv : 0.f;
+          if (tail_q) pv = (q0 + ib * 32 + 8 * q4 + 4 * g + e < seg_b) ? pv : 0.f;
           p[r] = pv;
-          ds[r] = pv * (dpacc[r] - d4[e]);
+          ds[r] = pv * (dpacc[r] - d4[q4][e]);
         }
-      }
       bf16x8 pb[2], dsb8[2];
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
@@ -218,23 +251,19 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
         pb[s2] = to_bf16x8(a);
         dsb8[s2] = to_bf16x8(b);
       }
-      // dV^T += dO^T P ; dK^T += Q^T dS
+      __builtin_amdgcn_sched_barrier(0);
+      // ---- dV^T += dO^T P ; dK^T += Q^T dS
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const int o0 = (tbase[0] ^ (db << 6)) + (ib * 32 + 16 * s2) * RB;
-          const int o1 = (tbase[1] ^ (db << 6)) + (ib * 32 + 16 * s2) * RB;
-          const bf16x8 doa = join_tr(lds_read_tr(dot, o0), lds_read_tr(dot, o1));
-          dvacc[db] = mfma32(doa, pb[s2], dvacc[db]);
-          const bf16x8 qa = join_tr(lds_read_tr(qt, o0), lds_read_tr(qt, o1));
-          dkacc[db] = mfma32(qa, dsb8[s2], dkacc[db]);
+          dvacc[db] = mfma32(join_tr(dlo[s2][db], dhi[s2][db]), pb[s2], dvacc[db]);
+          dkacc[db] = mfma32(join_tr(qlo[s2][db], qhi[s2][db]), dsb8[s2], dkacc[db]);
         }
+      __builtin_amdgcn_sched_barrier(0);
     }
 
-    if (more) store_tile((t + 1) & 1);
-    __syncthreads();
-
+    __syncthreads();   // next tile landed (vmcnt) and every wave is done reading this one
   }
 
   // ---- epilogue: dK (scaled) and dV for this lane's key row
@@ -271,10 +300,10 @@ struct DqCfg {
 };
 
 template <int D, int NI>
-__global__ __launch_bounds__(kDqWaves * 64, 1)
+__global__ __launch_bounds__(kDqWaves * 64, (NI == 1 ? 2 : 1))
 void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                         const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
-                        const float* __restrict__ lse, const float* __restrict__ delta,
+                        const float* __restrict__ lse2g, const float* __restrict__ delta,
                         __bf16* __restrict__ dq, const SegTable segs, const UnitMap um,
                         int total, int n_heads, float scale, float scale_log2) {
   using Cfg = DqCfg<D, NI>;
@@ -315,36 +344,32 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
       qreg[ib][ks] = *reinterpret_cast<const bf16x8*>(q + off + ks * 16);
       doreg[ib][ks] = *reinterpret_cast<const bf16x8*>(dout + off + ks * 16);
     }
-    lse2[ib] = lse[(size_t)head * total + r] * kLog2eB;
+    lse2[ib] = lse2g[(size_t)head * total + r];
     dlt[ib] = delta[(size_t)head * total + r];
   }
 
-  // ---- K/V staging (same scheme as the forward kernel)
-  int st_row[CPT], st_chunk[CPT], st_lds[CPT];
+  // ---- K/V staging with direct global->LDS loads (same scheme as the forward kernel)
+  int st_row[CPT], st_col[CPT];
 #pragma unroll
   for (int x = 0; x < CPT; ++x) {
-    const int idx = tid + x * (kDqWaves * 64);
-    st_row[x] = idx / Cfg::kChunksPerRow;
-    st_chunk[x] = idx % Cfg::kChunksPerRow;
-    st_lds[x] = tile_off<D>(st_row[x], st_chunk[x] * 8);
+    const int p = (x * kDqWaves + wave) * 64 + lane;
+    st_row[x] = p / Cfg::kChunksPerRow;
+    st_col[x] = ((p % Cfg::kChunksPerRow) ^ swz<D>(st_row[x])) * 8;
   }
-  u32x4 kst[CPT], vst[CPT];
-  auto load_tile = [&](int j0) {
-#pragma unroll
-    for (int x = 0; x < CPT; ++x) {
-      const int r = min(j0 + st_row[x], seg_b - 1);
-      const size_t off = (size_t)r * row_stride + st_chunk[x] * 8;
-      kst[x] = *reinterpret_cast<const u32x4*>(kbase + off);
-      vst[x] = *reinterpret_cast<const u32x4*>(vbase + off);
-    }
-  };
-  auto store_tile = [&](int stage) {
+  auto issue_tile = [&](int j0, int stage) {
     char* kt = smem + stage * 2 * Cfg::kTileBytes;
     char* vt = kt + Cfg::kTileBytes;
 #pragma unroll
     for (int x = 0; x < CPT; ++x) {
-      *reinterpret_cast<u32x4*>(kt + st_lds[x]) = kst[x];
-      *reinterpret_cast<u32x4*>(vt + st_lds[x]) = vst[x];
+      const int r = min(j0 + st_row[x], seg_b - 1);
+      const size_t off = (size_t)r * row_stride + st_col[x];
+      const int lds_off = (x * kDqWaves + wave) * 1024;
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(kbase + off),
+          (__attribute__((address_space(3))) void*)(kt + lds_off), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(vbase + off),
+          (__attribute__((address_space(3))) void*)(vt + lds_off), 16, 0, 0);
     }
   };
 
@@ -364,37 +389,52 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int r = 0; r < 16; ++r) dqacc[ib][db][r] = 0.f;
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   const int n_tiles = (seg_b - seg_a + kDqBC - 1) / kDqBC;
-  load_tile(seg_a);
-  store_tile(0);
+  issue_tile(seg_a, 0);
   __syncthreads();
 
   for (int t = 0; t < n_tiles; ++t) {
     const int j0 = seg_a + t * kDqBC;
     const bool more = (t + 1 < n_tiles);
-    if (more) load_tile(j0 + kDqBC);
     const char* kt = smem + (t & 1) * 2 * Cfg::kTileBytes;
     const char* vt = kt + Cfg::kTileBytes;
     const bool tail = (j0 + kDqBC > seg_b);
 
 #pragma unroll
     for (int jb = 0; jb < JB; ++jb) {
-      f32x16 sacc[NI], dpacc[NI];
-#pragma unroll
-      for (int ib = 0; ib < NI; ++ib)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { sacc[ib][r] = 0.f; dpacc[ib][r] = 0.f; }
+      // all row operands of this key block are requested before the first MFMA
+      bf16x8 ka[KS], va[KS];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         const int off = (rbase ^ (ks << 5)) + jb * 32 * RB;
-        const bf16x8 ka = lds_read_b128(kt, off);
-        const bf16x8 va = lds_read_b128(vt, off);
+        ka[ks] = lds_read_b128(kt, off);
+        va[ks] = lds_read_b128(vt, off);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      f32x16 sacc[NI], dpacc[NI];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
         for (int ib = 0; ib < NI; ++ib) {
-          sacc[ib] = mfma32(ka, qreg[ib][ks], sacc[ib]);
-          dpacc[ib] = mfma32(va, doreg[ib][ks], dpacc[ib]);
+          sacc[ib] = mfma32(ka[ks], qreg[ib][ks], ks == 0 ? zero16 : sacc[ib]);
+          dpacc[ib] = mfma32(va[ks], doreg[ib][ks], ks == 0 ? zero16 : dpacc[ib]);
         }
+      // K^T operands for the dQ MFMAs, requested in the shadow of the MFMAs above
+      s16x4 klo[2][DB], khi[2][DB];
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          klo[s2][db] = lds_read_tr(kt, (tbase[0] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB);
+          khi[s2][db] = lds_read_tr(kt, (tbase[1] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB);
+        }
+      __builtin_amdgcn_sched_barrier(0);
+      // the next tile's loads go out after this iteration's last LDS read
+      if (jb == JB - 1) {
+        if (more) issue_tile(j0 + kDqBC, (t + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
       }
       bf16x8 dsb[NI][2];
 #pragma unroll
@@ -417,20 +457,19 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
           dsb[ib][s2] = to_bf16x8(a);
         }
       }
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const int o0 = (tbase[0] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB;
-          const int o1 = (tbase[1] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB;
-          const bf16x8 kta = join_tr(lds_read_tr(kt, o0), lds_read_tr(kt, o1));
+          const bf16x8 kta = join_tr(klo[s2][db], khi[s2][db]);
 #pragma unroll
           for (int ib = 0; ib < NI; ++ib) dqacc[ib][db] = mfma32(kta, dsb[ib][s2], dqacc[ib][db]);
         }
+      __builtin_amdgcn_sched_barrier(0);
     }
 
-    if (more) store_tile((t + 1) & 1);
-    __syncthreads();
+    __syncthreads();   // next tile landed (vmcnt) and every wave is done reading this one
   }
 
   // ---- epilogue: dq = bf16(scale * dQ^T)
@@ -456,13 +495,13 @@ template <int D>
 static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, const void* out,
                                const float* lse, const void* dout, const SegTable& segs, int total,
                                int n_heads, float scale, void* dq, void* dk, void* dv,
-                               float* delta, hipStream_t stream) {
+                               float* delta, float* lse2, hipStream_t stream) {
   if (total == 0) return hipSuccess;
   {
     constexpr int kTokPerBlock = 256 / (D / 8);
     const int grid = (total + kTokPerBlock - 1) / kTokPerBlock;
-    bwd_prepare_kernel<D><<<grid, 256, 0, stream>>>((const u32x4*)out, (const u32x4*)dout, delta,
-                                                    total, n_heads);
+    bwd_prepare_kernel<D><<<grid, 256, 0, stream>>>((const u32x4*)out, (const u32x4*)dout, lse,
+                                                    delta, lse2, total, n_heads);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -480,13 +519,13 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
     kern<<<um.chunk * kNumXcd, kBwdWaves * 64, Cfg::kLdsBytes, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse, delta,
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse2, delta,
         (__bf16*)dk, (__bf16*)dv, segs, um, total, n_heads, scale, scale * kLog2eB);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
   {
-    constexpr int NI = 2;
+    constexpr int NI = 1;
     using Cfg = DqCfg<D, NI>;
     int tiles = 0;
     for (int s = 0; s < segs.n; ++s) tiles += (segs.len[s] + Cfg::kBR - 1) / Cfg::kBR;
@@ -499,7 +538,7 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
     kern<<<um.chunk * kNumXcd, kDqWaves * 64, Cfg::kLdsBytes, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse, delta,
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse2, delta,
         (__bf16*)dq, segs, um, total, n_heads, scale, scale * kLog2eB);
     return hipGetLastError();
   }
@@ -508,10 +547,10 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
 hipError_t launch_attn_bwd(const void* q, const void* k, const void* v, const void* out,
                            const float* lse, const void* dout, const SegTable& segs, int total,
                            int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
-                           float* delta, hipStream_t stream) {
+                           float* delta, float* lse2, hipStream_t stream) {
   if (head_dim == 128)
-    return launch_bwd_d<128>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, stream);
-  return launch_bwd_d<64>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, stream);
+    return launch_bwd_d<128>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, stream);
+  return launch_bwd_d<64>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, stream);
 }
 
 }  // namespace vfm
