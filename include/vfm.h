@@ -74,7 +74,8 @@ typedef enum { VFM_BF16 = 0, VFM_F32 = 1 /* not implemented: VFM_ERR_DTYPE */ } 
  *     x[2i]'   = x[2i] cos(phi) - x[2i+1] sin(phi)
  *     x[2i+1]' = x[2i] sin(phi) + x[2i+1] cos(phi)
  * inverse != 0 rotates by -phi (the transpose; carries gradients back).
- * Angles and products are fp32; the result is rounded to bf16 (nearest even).
+ * The angle is formed and range-reduced in fp64, sin/cos and the products are
+ * fp32, and the result is rounded to bf16 (nearest even).
  *
  * thw: host [n_seqs,3]; cu_seqlens: host [n_seqs+1].
  * Errors: NULL, SHAPE, CU_SEQLENS, THW, SPLIT, DTYPE, ALIGN, LAUNCH.

@@ -52,6 +52,7 @@ __all__ = [
     "attn_bwd",
     "attn_fwd_rows",
     "attn_bwd_rows",
+    "attn_bwd_cols",
 ]
 
 
@@ -268,3 +269,40 @@ def attn_bwd_rows(q, k, v, dout, cu_seqlens, scale: float, head: int, rows):
         dk_part[a:b] += scale * (dS.T @ Q)
         dv_part[a:b] += P.T @ dO
     return dq, dk_part, dv_part
+
+
+def attn_bwd_cols(q, k, v, dout, cu_seqlens, scale: float, head: int, cols, row_chunk: int = 4096):
+    """dK and dV for selected packed key/value rows of one head (all in one segment).
+
+    dK_j and dV_j are sums over every query row i of the segment, and each term
+    needs that row's softmax normaliser and Delta_i, so the forward definition
+    is evaluated for all rows of the segment first (rows are independent; they
+    are visited `row_chunk` at a time only to bound memory).  Then, for j in
+    `cols`:  P_ij = exp(S_ij - LSE_i), dV_j = sum_i P_ij dO_i,
+    dS_ij = P_ij (dO_i . V_j - Delta_i), dK_j = scale * sum_i dS_ij Q_i.
+    Returns dk [len(cols), D], dv [len(cols), D].
+    """
+    total, _, D = q.shape
+    cu = _check_cu(cu_seqlens, total)
+    cols = np.asarray(cols, dtype=np.int64)
+    a, b = _segment_of(cu, int(cols[0]))
+    if np.any(cols < a) or np.any(cols >= b):
+        raise ValueError("all columns must lie in one segment")
+    K = _as_f64(k[a:b, head, :])
+    V = _as_f64(v[a:b, head, :])
+    Kc = _as_f64(k[cols, head, :])
+    Vc = _as_f64(v[cols, head, :])
+    dk = np.zeros((cols.size, D))
+    dv = np.zeros((cols.size, D))
+    for r0 in range(a, b, row_chunk):
+        r1 = min(b, r0 + row_chunk)
+        Q = _as_f64(q[r0:r1, head, :])
+        dO = _as_f64(dout[r0:r1, head, :])
+        P, L = _softmax_rows(scale * (Q @ K.T))
+        delta = (dO * (P @ V)).sum(axis=1, keepdims=True)
+        del P
+        Pc = np.exp(scale * (Q @ Kc.T) - L[:, None])
+        dv += Pc.T @ dO
+        dS = Pc * (dO @ Vc.T - delta)
+        dk += scale * (dS.T @ Q)
+    return dk, dv

@@ -3,7 +3,7 @@
 // One group of D/8 lanes owns one token; lane c of the group owns the 16-byte
 // chunk c of every head vector of that token (four adjacent pairs).  The four
 // (cos, sin) values a lane needs depend on the token and on c only, so they are
-// computed once (accurate sincosf: angles reach ~120 rad) and reused for all
+// computed once (angle reduced in fp64, then sincosf) and reused for all
 // heads.  A wavefront therefore moves 256-byte contiguous head rows; every byte
 // of x is read once and written once.
 #include "vfm_common.h"
@@ -11,8 +11,8 @@
 namespace vfm {
 
 struct RopeFreq {
-  float inv_freq[64];  // per pair index p = element/2: theta^(-2i/d_axis), fp64-computed on the host
-  int axis[64];        // 0 = t, 1 = h, 2 = w
+  double inv_freq[64];    // per pair index p = element/2: theta^(-2i/d_axis)
+  unsigned char axis[64]; // 0 = t, 1 = h, 2 = w
 };
 
 template <int D>
@@ -44,10 +44,14 @@ __global__ __launch_bounds__(256) void rope3d_kernel(u32x4* __restrict__ x, cons
   for (int e = 0; e < 4; ++e) {
     const int p = chunk * 4 + e;
     const int ax = fr.axis[p];
-    const float pa = (float)(ax == 0 ? pos[0] : (ax == 1 ? pos[1] : pos[2]));
-    const float ang = pa * fr.inv_freq[p];
+    // The angle is formed and reduced to [-pi, pi] in fp64 (a handful of operations per
+    // token, reused for every head), so the rotation stays accurate to fp32 rounding
+    // however large the grid position is.
+    const double pa = (double)(ax == 0 ? pos[0] : (ax == 1 ? pos[1] : pos[2]));
+    double ang = pa * fr.inv_freq[p];
+    ang -= 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
     float s, c;
-    sincosf(ang, &s, &c);
+    sincosf((float)ang, &s, &c);
     cs[e] = c;
     sn[e] = inverse ? -s : s;
   }
@@ -98,11 +102,11 @@ hipError_t launch_rope3d(void* x, const RopeTable& tab, int total, int n_heads, 
   int p = 0;
   for (int ax = 0; ax < 3; ++ax) {
     for (int i = 0; i < dims[ax] / 2; ++i, ++p) {
-      fr.inv_freq[p] = (float)pow((double)theta, -2.0 * (double)i / (double)dims[ax]);
-      fr.axis[p] = ax;
+      fr.inv_freq[p] = pow((double)theta, -2.0 * (double)i / (double)dims[ax]);
+      fr.axis[p] = (unsigned char)ax;
     }
   }
-  for (; p < 64; ++p) { fr.inv_freq[p] = 0.f; fr.axis[p] = 0; }
+  for (; p < 64; ++p) { fr.inv_freq[p] = 0.0; fr.axis[p] = 0; }
   if (total == 0) return hipSuccess;
   if (head_dim == 128) {
     const int grid = (total + 15) / 16;

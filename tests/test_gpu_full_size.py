@@ -1,0 +1,151 @@
+"""GPU parity at the paper-shaped workload sizes, in the launch configuration bench.py times.
+
+Where the whole tensor is too large for the CPU oracle, heads are subsampled (heads are
+independent, identical work) and, at the 56K/130K-token sizes, outputs are checked on sampled
+query rows (out, lse, dq) and sampled key rows (dk, dv) that the oracle computes one by one.
+Sampled rows straddle tile boundaries and include the first and last token of a clip.
+"""
+import numpy as np
+import pytest
+
+from oracle import vfm_oracle as orc
+from paper_2503_12964_amd import workloads as W
+from tests import parity_utils as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _binding():
+    from paper_2503_12964_amd import binding
+    binding.load_library()
+    return binding
+
+
+def _f32(t):
+    import torch
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+def _upload(wl, names=("q", "k", "v", "dout")):
+    dev = {}
+    for n in names:
+        bits = W.make_inputs(wl, tensors=(n,))[n]
+        dev[n] = U.to_device(bits)
+        del bits
+    return dev
+
+
+def _rope_check(b, wl, x, heads):
+    """RoPE x in place on the GPU; check the listed heads (all tokens) against the oracle."""
+    before = _f32(x[:, heads, :]).astype(np.float64)
+    b.vfm_rope3d(x, wl.thw, wl.cu_seqlens, wl.rope_dims, wl.theta)
+    got = _f32(x[:, heads, :]).astype(np.float64)
+    want = orc.rope3d(before, wl.thw, wl.cu_seqlens, wl.rope_dims, wl.theta)
+    tol = 2.0 ** -8 * np.abs(want) + 1e-6 * np.abs(before).max()
+    assert np.all(np.abs(got - want) <= tol)
+    assert U.rel_rms(got, want) <= U.TOL_ROPE_RELRMS
+
+
+def _sample_rows(wl, per_clip, seed):
+    rng = np.random.default_rng(seed)
+    rows = []
+    for a, n in zip(wl.cu_seqlens[:-1], wl.seqlens):
+        if n == 0:
+            continue
+        fixed = [0, n - 1, min(n - 1, 127), min(n - 1, 128), min(n - 1, 255), min(n - 1, 256)]
+        extra = rng.integers(0, n, size=max(0, per_clip - len(fixed))).tolist()
+        rows += [int(a) + r for r in sorted(set(fixed + extra))[:max(per_clip, 2)]]
+    return np.array(sorted(set(rows)), dtype=np.int64)
+
+
+@pytest.mark.parametrize("name,heads", [("C2", (0, 5, 15)), ("C3", (0, 23))])
+def test_head_subset_full_oracle(name, heads):
+    """Whole clips, all tokens, on a subset of heads: every tile shape and ragged tail of the
+    configuration is covered; rope -> fwd -> bwd run on all heads on the GPU."""
+    b = _binding()
+    wl = W.WORKLOADS[name]
+    dev = _upload(wl)
+    heads = list(heads)
+    _rope_check(b, wl, dev["q"], heads)
+    _rope_check(b, wl, dev["k"], heads)
+    out, lse = b.vfm_attn_fwd(dev["q"], dev["k"], dev["v"], wl.cu_seqlens, wl.scale)
+    dq, dk, dv = b.vfm_attn_bwd(dev["q"], dev["k"], dev["v"], out, lse, dev["dout"], wl.cu_seqlens, wl.scale)
+    host = {n: _f32(dev[n][:, heads, :]).astype(np.float64) for n in dev}
+    o_ref, l_ref = orc.attn_fwd(host["q"], host["k"], host["v"], wl.cu_seqlens, wl.scale)
+    g_ref = orc.attn_bwd(host["q"], host["k"], host["v"], host["dout"], wl.cu_seqlens, wl.scale)
+    o = _f32(out[:, heads, :]).astype(np.float64)
+    assert U.max_abs(o, o_ref) <= U.TOL_OUT_MAXABS
+    assert U.rel_rms(o, o_ref) <= U.TOL_OUT_RELRMS
+    assert U.max_abs(_f32(lse[heads, :]), l_ref) <= U.TOL_LSE_MAXABS
+    for nm, g, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), g_ref):
+        r = U.rel_rms(_f32(g[:, heads, :]).astype(np.float64), ref)
+        assert r <= U.TOL_GRAD_RELRMS, (nm, r)
+
+
+def test_headline_56k_sampled_rows_and_columns():
+    """The 56,320-token, 32-head latent exactly as bench.py runs it."""
+    import torch
+    b = _binding()
+    wl = W.WORKLOADS["C4"]
+    dev = _upload(wl)
+    _rope_check(b, wl, dev["q"], [0, 1, 2, 3, 31])
+    _rope_check(b, wl, dev["k"], [0, 31])
+    out, lse = b.vfm_attn_fwd(dev["q"], dev["k"], dev["v"], wl.cu_seqlens, wl.scale)
+    dq, dk, dv = b.vfm_attn_bwd(dev["q"], dev["k"], dev["v"], out, lse, dev["dout"], wl.cu_seqlens, wl.scale)
+    torch.cuda.synchronize()
+    rows = _sample_rows(wl, 10, seed=5)
+    err_o, ref_o, err_q, ref_q, max_o, max_l = 0.0, 0.0, 0.0, 0.0, 0.0, 0.0
+    for h in range(wl.n_heads):
+        host = {n: _f32(dev[n][:, h:h + 1, :]) for n in dev}
+        o_ref, l_ref = orc.attn_fwd_rows(host["q"], host["k"], host["v"], wl.cu_seqlens, wl.scale, 0, rows)
+        dq_ref, _, _ = orc.attn_bwd_rows(host["q"], host["k"], host["v"], host["dout"], wl.cu_seqlens,
+                                         wl.scale, 0, rows)
+        o = _f32(out[rows, h, :]).astype(np.float64)
+        g = _f32(dq[rows, h, :]).astype(np.float64)
+        max_o = max(max_o, U.max_abs(o, o_ref))
+        max_l = max(max_l, U.max_abs(_f32(lse[h, rows]), l_ref))
+        err_o += np.sum((o - o_ref) ** 2); ref_o += np.sum(o_ref ** 2)
+        err_q += np.sum((g - dq_ref) ** 2); ref_q += np.sum(dq_ref ** 2)
+    assert max_o <= U.TOL_OUT_MAXABS
+    assert np.sqrt(err_o / ref_o) <= U.TOL_OUT_RELRMS
+    assert max_l <= U.TOL_LSE_MAXABS
+    assert np.sqrt(err_q / ref_q) <= U.TOL_GRAD_RELRMS
+    # dk, dv need every query row: one head, sampled key rows
+    h = 17
+    cols = _sample_rows(wl, 24, seed=6)
+    host = {n: _f32(dev[n][:, h:h + 1, :]) for n in dev}
+    dk_ref, dv_ref = orc.attn_bwd_cols(host["q"], host["k"], host["v"], host["dout"], wl.cu_seqlens,
+                                       wl.scale, 0, cols)
+    assert U.rel_rms(_f32(dk[cols, h, :]), dk_ref) <= U.TOL_GRAD_RELRMS
+    assert U.rel_rms(_f32(dv[cols, h, :]), dv_ref) <= U.TOL_GRAD_RELRMS
+
+
+def test_inference_130k_four_steps_one_stream():
+    """1080p-class latent, forward only: rope(q), rope(k), attention, four times back to back on
+    one stream with no host synchronisation in between; the last step is checked."""
+    import torch
+    b = _binding()
+    wl = W.WORKLOADS["C5"]
+    dev = _upload(wl, names=("q", "k", "v"))
+    _rope_check(b, wl, dev["q"], [0, 39])            # first of the four rope applications
+    b.vfm_rope3d(dev["k"], wl.thw, wl.cu_seqlens, wl.rope_dims, wl.theta)
+    out = torch.empty_like(dev["q"])
+    lse = torch.empty((wl.n_heads, wl.total_tokens), dtype=torch.float32, device="cuda")
+    for step in range(4):
+        if step:
+            b.vfm_rope3d(dev["q"], wl.thw, wl.cu_seqlens, wl.rope_dims, wl.theta)
+            b.vfm_rope3d(dev["k"], wl.thw, wl.cu_seqlens, wl.rope_dims, wl.theta)
+        b.vfm_attn_fwd(dev["q"], dev["k"], dev["v"], wl.cu_seqlens, wl.scale, out=out, lse=lse)
+    torch.cuda.synchronize()
+    rows = _sample_rows(wl, 8, seed=7)
+    err, ref, mx, ml = 0.0, 0.0, 0.0, 0.0
+    for h in (0, 7, 13, 21, 26, 39):
+        host = {n: _f32(dev[n][:, h:h + 1, :]) for n in dev}
+        o_ref, l_ref = orc.attn_fwd_rows(host["q"], host["k"], host["v"], wl.cu_seqlens, wl.scale, 0, rows)
+        o = _f32(out[rows, h, :]).astype(np.float64)
+        mx = max(mx, U.max_abs(o, o_ref))
+        ml = max(ml, U.max_abs(_f32(lse[h, rows]), l_ref))
+        err += np.sum((o - o_ref) ** 2); ref += np.sum(o_ref ** 2)
+    assert mx <= U.TOL_OUT_MAXABS
+    assert np.sqrt(err / ref) <= U.TOL_OUT_RELRMS
+    assert ml <= U.TOL_LSE_MAXABS

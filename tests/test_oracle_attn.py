@@ -259,6 +259,19 @@ def test_row_helpers_match_full_functions():
     np.testing.assert_allclose(dv_sum, dv[:, 1], atol=1e-13)
 
 
+def test_column_helper_matches_full_function():
+    lens = [9, 30, 4]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    q, k, v, do = _inputs(cu, 2, 8, 130)
+    _, dk, dv = orc.attn_bwd(q, k, v, do, cu, 0.3)
+    cols = np.array([9, 17, 38, 22])
+    dk_c, dv_c = orc.attn_bwd_cols(q, k, v, do, cu, 0.3, 1, cols, row_chunk=7)
+    np.testing.assert_allclose(dk_c, dk[cols, 1], atol=1e-13)
+    np.testing.assert_allclose(dv_c, dv[cols, 1], atol=1e-13)
+    with pytest.raises(ValueError):
+        orc.attn_bwd_cols(q, k, v, do, cu, 0.3, 1, [3, 20])
+
+
 def test_bad_cu_seqlens_rejected():
     q = np.zeros((4, 1, 2))
     for cu in ([1, 4], [0, 3], [0, 3, 2, 4]):
