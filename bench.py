@@ -29,8 +29,8 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak (published)
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel from `rocprofv3 --pmc` (FETCH_SIZE and
-# WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+# WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None where not measured.
+MEASURED_TRAFFIC_BYTES = {"C4": 32.97e9}
 
 
 def _device_tensors(wl):
@@ -79,6 +79,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB device copy (the known-size kernel that scales "
+                         "the FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); "
@@ -93,6 +96,14 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")       # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": dst.numel() * 4}))
+        return 0
     wl = W.WORKLOADS[args.workload]
     t = _device_tensors(wl)
     q, k, v, do = t["q"], t["k"], t["v"], t["dout"]
