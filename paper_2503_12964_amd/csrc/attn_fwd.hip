@@ -75,28 +75,29 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   // writes).  One wave instruction fills 64 consecutive 16-byte chunks of a tile;
   // lane L of instruction (x, wave) owns LDS chunk P = (x*waves + wave)*64 + L, i.e.
   // tile row P / chunks_per_row, physical chunk P % chunks_per_row, and fetches the
-  // logical chunk that the swizzle maps there.
-  int st_row[CPT], st_col[CPT];
+  // logical chunk that the swizzle maps there.  Global byte offsets are 32-bit and are
+  // advanced by one tile per iteration; rows past the clip end clamp to its last row.
+  const uint32_t row_bytes = (uint32_t)row_stride * 2u;
+  const uint32_t last_row_off = (uint32_t)(seg_b - 1) * row_bytes;
+  uint32_t st_rowoff[CPT], st_colb[CPT];
 #pragma unroll
   for (int x = 0; x < CPT; ++x) {
     const int p = (x * kFwdWaves + wave) * 64 + lane;
-    st_row[x] = p / Cfg::kChunksPerRow;
-    st_col[x] = ((p % Cfg::kChunksPerRow) ^ swz<D>(st_row[x])) * 8;
+    const int r = p / Cfg::kChunksPerRow;
+    st_rowoff[x] = (uint32_t)(seg_a + r) * row_bytes;
+    st_colb[x] = (uint32_t)(((p % Cfg::kChunksPerRow) ^ swz<D>(r)) * 16);
   }
-  auto issue_tile = [&](int j0, int stage) {
-    char* kt = smem + stage * 2 * Cfg::kTileBytes;
-    char* vt = kt + Cfg::kTileBytes;
+  const uint32_t smem_addr = lds_addr_of(smem);
+  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(smem_addr + wave * 1024);
+  // issues the next tile in row order (tiles are always requested in sequence)
+  auto issue_tile = [&](int stage) {
 #pragma unroll
     for (int x = 0; x < CPT; ++x) {
-      const int r = min(j0 + st_row[x], seg_b - 1);
-      const size_t off = (size_t)r * row_stride + st_col[x];
-      const int lds_off = (x * kFwdWaves + wave) * 1024;
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(kbase + off),
-          (__attribute__((address_space(3))) void*)(kt + lds_off), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(vbase + off),
-          (__attribute__((address_space(3))) void*)(vt + lds_off), 16, 0, 0);
+      const uint32_t off = min(st_rowoff[x], last_row_off) + st_colb[x];
+      const uint32_t dst = wave_lds + stage * 2 * Cfg::kTileBytes + x * kFwdWaves * 1024;
+      lds_dma16(kbase, off, dst);
+      lds_dma16(vbase, off, dst + Cfg::kTileBytes);
+      st_rowoff[x] += kFwdBC * row_bytes;
     }
   };
 
@@ -133,14 +134,18 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   const int n_kv = seg_b - seg_a;
   const int n_tiles = (n_kv + kFwdBC - 1) / kFwdBC;
 
-  issue_tile(seg_a, 0);
+  issue_tile(0);
+  wait_vmcnt<0>();
   __syncthreads();
 
-  for (int t = 0; t < n_tiles; ++t) {
+  // One tile; STAGE is a compile-time constant so every LDS offset is an immediate.
+  auto tile_body = [&](auto stage_c, int t) {
+    constexpr int STAGE = decltype(stage_c)::value;
     const int j0 = seg_a + t * kFwdBC;
-    const bool more = (t + 1 < n_tiles);
+    // the next tile's loads are issued first and land while this tile is processed
+    if (t + 1 < n_tiles) issue_tile(STAGE ^ 1);
 
-    const char* kt = smem + (t & 1) * 2 * Cfg::kTileBytes;
+    const char* kt = smem + STAGE * 2 * Cfg::kTileBytes;
     const char* vt = kt + Cfg::kTileBytes;
 
     // ---- all K operand reads of this tile are issued before the first MFMA, so their
@@ -176,10 +181,6 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
           vlo[jb][s2][db] = lds_read_tr(vt, (vbase_off[0] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB);
           vhi[jb][s2][db] = lds_read_tr(vt, (vbase_off[1] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB);
         }
-    __builtin_amdgcn_sched_barrier(0);
-    // The next tile's loads go out only now, after this iteration's last LDS read: the
-    // compiler orders every LDS read after an LDS-writing load behind a full vmcnt wait.
-    if (more) issue_tile(j0 + kFwdBC, (t + 1) & 1);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- mask keys past the end of the clip (last tile only)
@@ -250,7 +251,12 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
         }
     __builtin_amdgcn_sched_barrier(0);
 
-    __syncthreads();   // waits for the next tile's loads (vmcnt) and for every wave's LDS reads
+    wait_vmcnt<0>();   // the next tile has landed ...
+    __syncthreads();   // ... for every wave, and every wave is done reading this one
+  };
+  for (int t = 0; t < n_tiles; t += 2) {
+    tile_body(IntC<0>{}, t);
+    if (t + 1 < n_tiles) tile_body(IntC<1>{}, t + 1);
   }
 
   // ---- epilogue: normalise, write out (bf16) and lse (natural log)

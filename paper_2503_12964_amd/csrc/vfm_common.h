@@ -140,6 +140,32 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ bf16x8 to_bf16x8(f32x8 v) { return __builtin_convertvector(v, bf16x8); }
 __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) { return __builtin_convertvector(v, bf16x4); }
 
+// ---- direct global -> LDS loads, issued as inline assembly ------------------
+// The compiler orders every LDS read that follows a compiler-visible LDS-writing load
+// behind a full vmcnt(0) wait, which would expose the whole global latency each tile.
+// Issued as assembly the loads stay in flight across the tile's LDS reads; the kernels
+// wait for them explicitly (wait_vmcnt) before the barrier that publishes the tile.
+// Lane L's bytes land at lds_addr + L*size; lds_addr and base are wave-uniform, the
+// global address is base + byte_off (32-bit unsigned, per lane).  Extra outstanding
+// loads the compiler does not know of can only make its own vmcnt waits stricter.
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+__device__ __forceinline__ void lds_dma16(const void* base, uint32_t byte_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory");
+}
+__device__ __forceinline__ void lds_dma4(const void* base, uint32_t byte_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+               :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+template <int V>
+struct IntC { static constexpr int value = V; };
+
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
