@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const u32x4* __restric
 template <int D>
 struct BwdCfg {
   static constexpr int kTileBytes = kBwdBQ * D * 2;               // one Q or dO tile
-  static constexpr int kStageBytes = 2 * kTileBytes + 2 * kBwdBQ * 4;  // Q, dO, lse, Delta
+  static constexpr int kStageBytes = 2 * kTileBytes + 4 * kBwdBQ * 4;  // Q, dO, lse2, Delta (+ spare)
   static constexpr int kLdsBytes = 2 * kStageBytes;
   static constexpr int kChunksPerRow = D / 8;
   static constexpr int kChunksPerThread = kBwdBQ * kChunksPerRow / (kBwdWaves * 64);
@@ -115,38 +115,38 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   // ---- staging of Q / dO / lse2 / Delta tiles with direct global->LDS loads.
   // Lane L of wave instruction (x, wave) owns LDS chunk P = (x*waves + wave)*64 + L of
   // the tile (row P / chunks_per_row, physical chunk P % chunks_per_row) and fetches the
-  // logical chunk the swizzle maps there.  Waves 0 and 1 also fetch the 64 lse2 / Delta
-  // values (4 bytes per lane).
-  int st_row[CPT], st_col[CPT];
+  // logical chunk the swizzle maps there.  Every wave also fetches 64 row statistics
+  // (4 bytes per lane): wave 0 lse2, wave 1 Delta, waves 2 and 3 the same again into
+  // spare LDS, so that all waves have the same number of loads in flight.
+  const uint32_t row_bytes = (uint32_t)row_stride * 2u;
+  const uint32_t last_row_off = (uint32_t)(seg_b - 1) * row_bytes;
+  const __bf16* qbase = q + head_off;
+  const __bf16* dobase = dout + head_off;
+  uint32_t st_rowoff[CPT], st_colb[CPT];
 #pragma unroll
   for (int x = 0; x < CPT; ++x) {
     const int p = (x * kBwdWaves + wave) * 64 + lane;
-    st_row[x] = p / Cfg::kChunksPerRow;
-    st_col[x] = ((p % Cfg::kChunksPerRow) ^ swz<D>(st_row[x])) * 8;
+    const int r = p / Cfg::kChunksPerRow;
+    st_rowoff[x] = (uint32_t)(seg_a + r) * row_bytes;
+    st_colb[x] = (uint32_t)(((p % Cfg::kChunksPerRow) ^ swz<D>(r)) * 16);
   }
-  const float* stat_src = (wave == 0 ? lse2 : delta) + (size_t)head * total;
-  auto issue_tile = [&](int q0, int stage) {
-    char* qt = smem + stage * Cfg::kStageBytes;
-    char* dot = qt + Cfg::kTileBytes;
+  const float* stat_src = uniform_ptr(((wave & 1) == 0 ? lse2 : delta) + (size_t)head * total);
+  uint32_t stat_off = (uint32_t)(seg_a + lane) * 4u;
+  const uint32_t stat_last = (uint32_t)(seg_b - 1) * 4u;
+  const uint32_t smem_addr = lds_addr_of(smem);
+  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(smem_addr + wave * 1024);
+  const uint32_t stat_lds = __builtin_amdgcn_readfirstlane(smem_addr + 2 * Cfg::kTileBytes + wave * (kBwdBQ * 4));
+  auto issue_tile = [&](int stage) {   // tiles are requested in sequence
 #pragma unroll
     for (int x = 0; x < CPT; ++x) {
-      const int r = min(q0 + st_row[x], seg_b - 1);
-      const size_t off = (size_t)r * row_stride + head_off + st_col[x];
-      const int lds_off = (x * kBwdWaves + wave) * 1024;
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(q + off),
-          (__attribute__((address_space(3))) void*)(qt + lds_off), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(dout + off),
-          (__attribute__((address_space(3))) void*)(dot + lds_off), 16, 0, 0);
+      const uint32_t off = min(st_rowoff[x], last_row_off) + st_colb[x];
+      const uint32_t dst = wave_lds + stage * Cfg::kStageBytes + x * kBwdWaves * 1024;
+      lds_dma16(qbase, off, dst);
+      lds_dma16(dobase, off, dst + Cfg::kTileBytes);
+      st_rowoff[x] += kBwdBQ * row_bytes;
     }
-    if (wave < 2) {
-      const int r = min(q0 + lane, seg_b - 1);
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(stat_src + r),
-          (__attribute__((address_space(3))) void*)(qt + 2 * Cfg::kTileBytes + wave * (kBwdBQ * 4)),
-          4, 0, 0);
-    }
+    lds_dma4(stat_src, min(stat_off, stat_last), stat_lds + stage * Cfg::kStageBytes);
+    stat_off += kBwdBQ * 4u;
   };
 
   // ---- per-lane LDS offsets.  The swizzle XORs low byte-offset bits with a function
@@ -174,18 +174,20 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   const int n_q = seg_b - seg_a;
   const int n_steps = (n_q + kBwdBQ - 1) / kBwdBQ;
 
-  issue_tile(seg_a, 0);
+  issue_tile(0);
+  wait_vmcnt<0>();
   __syncthreads();
 
-  for (int t = 0; t < n_steps; ++t) {
+  auto step_body = [&](auto stage_c, int t) {
+    constexpr int STAGE = decltype(stage_c)::value;
     const int q0 = seg_a + t * kBwdBQ;
-    const bool more = (t + 1 < n_steps);
-    const bool tail_q = (q0 + kBwdBQ > seg_b);
+    if (t + 1 < n_steps) issue_tile(STAGE ^ 1);   // lands while this tile is processed
+    const bool masked = tail_kv || (q0 + kBwdBQ > seg_b);
 
-    const char* qt = smem + (t & 1) * Cfg::kStageBytes;
+    const char* qt = smem + STAGE * Cfg::kStageBytes;
     const char* dot = qt + Cfg::kTileBytes;
     const float* lse_s = reinterpret_cast<const float*>(qt + 2 * Cfg::kTileBytes);
-    const float* delta_s = lse_s + kBwdBQ;
+    const float* delta_s = lse_s + kBwdBQ;   // (wave 1's statistics follow wave 0's)
 
 #pragma unroll
     for (int ib = 0; ib < NIB; ++ib) {
@@ -224,24 +226,30 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
         d4[q4] = *reinterpret_cast<const f32x4*>(delta_s + ib * 32 + 8 * q4 + 4 * g);
       }
       __builtin_amdgcn_sched_barrier(0);
-      // the next tile's loads go out after this step's last LDS read
-      if (ib == NIB - 1) {
-        if (more) issue_tile(q0 + kBwdBQ, (t + 1) & 1);
-        __builtin_amdgcn_sched_barrier(0);
-      }
       // ---- P and dS for rows i = ib*32 + 8*q4 + 4g + e, column j = this lane's key
       f32x16 p, ds;
+      if (masked) {   // wave-uniform: only tiles touching the end of the clip pay for masks
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4)
+        for (int q4 = 0; q4 < 4; ++q4)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = q4 * 4 + e;
-          float pv = fast_exp2(sacc[r] * scale_log2 - l4[q4][e]);
-          if (tail_kv) pv = jvalid ? pv : 0.f;
-          if (tail_q) pv = (q0 + ib * 32 + 8 * q4 + 4 * g + e < seg_b) ? pv : 0.f;
-          p[r] = pv;
-          ds[r] = pv * (dpacc[r] - d4[q4][e]);
-        }
+          for (int e = 0; e < 4; ++e) {
+            const int r = q4 * 4 + e;
+            const bool ok = jvalid && (q0 + ib * 32 + 8 * q4 + 4 * g + e < seg_b);
+            const float pv = ok ? fast_exp2(sacc[r] * scale_log2 - l4[q4][e]) : 0.f;
+            p[r] = pv;
+            ds[r] = pv * (dpacc[r] - d4[q4][e]);
+          }
+      } else {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int r = q4 * 4 + e;
+            const float pv = fast_exp2(sacc[r] * scale_log2 - l4[q4][e]);
+            p[r] = pv;
+            ds[r] = pv * (dpacc[r] - d4[q4][e]);
+          }
+      }
       bf16x8 pb[2], dsb8[2];
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
@@ -263,7 +271,12 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
       __builtin_amdgcn_sched_barrier(0);
     }
 
-    __syncthreads();   // next tile landed (vmcnt) and every wave is done reading this one
+    wait_vmcnt<0>();   // the next tile has landed ...
+    __syncthreads();   // ... for every wave, and every wave is done reading this one
+  };
+  for (int t = 0; t < n_steps; t += 2) {
+    step_body(IntC<0>{}, t);
+    if (t + 1 < n_steps) step_body(IntC<1>{}, t + 1);
   }
 
   // ---- epilogue: dK (scaled) and dV for this lane's key row
@@ -349,27 +362,25 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
   }
 
   // ---- K/V staging with direct global->LDS loads (same scheme as the forward kernel)
-  int st_row[CPT], st_col[CPT];
+  const uint32_t row_bytes = (uint32_t)row_stride * 2u;
+  const uint32_t last_row_off = (uint32_t)(seg_b - 1) * row_bytes;
+  uint32_t st_rowoff[CPT], st_colb[CPT];
 #pragma unroll
   for (int x = 0; x < CPT; ++x) {
     const int p = (x * kDqWaves + wave) * 64 + lane;
-    st_row[x] = p / Cfg::kChunksPerRow;
-    st_col[x] = ((p % Cfg::kChunksPerRow) ^ swz<D>(st_row[x])) * 8;
+    const int r = p / Cfg::kChunksPerRow;
+    st_rowoff[x] = (uint32_t)(seg_a + r) * row_bytes;
+    st_colb[x] = (uint32_t)(((p % Cfg::kChunksPerRow) ^ swz<D>(r)) * 16);
   }
-  auto issue_tile = [&](int j0, int stage) {
-    char* kt = smem + stage * 2 * Cfg::kTileBytes;
-    char* vt = kt + Cfg::kTileBytes;
+  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_addr_of(smem) + wave * 1024);
+  auto issue_tile = [&](int stage) {   // tiles are requested in sequence
 #pragma unroll
     for (int x = 0; x < CPT; ++x) {
-      const int r = min(j0 + st_row[x], seg_b - 1);
-      const size_t off = (size_t)r * row_stride + st_col[x];
-      const int lds_off = (x * kDqWaves + wave) * 1024;
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(kbase + off),
-          (__attribute__((address_space(3))) void*)(kt + lds_off), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(
-          (const __attribute__((address_space(1))) void*)(vbase + off),
-          (__attribute__((address_space(3))) void*)(vt + lds_off), 16, 0, 0);
+      const uint32_t off = min(st_rowoff[x], last_row_off) + st_colb[x];
+      const uint32_t dst = wave_lds + stage * 2 * Cfg::kTileBytes + x * kDqWaves * 1024;
+      lds_dma16(kbase, off, dst);
+      lds_dma16(vbase, off, dst + Cfg::kTileBytes);
+      st_rowoff[x] += kDqBC * row_bytes;
     }
   };
 
@@ -392,13 +403,15 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   const int n_tiles = (seg_b - seg_a + kDqBC - 1) / kDqBC;
-  issue_tile(seg_a, 0);
+  issue_tile(0);
+  wait_vmcnt<0>();
   __syncthreads();
 
-  for (int t = 0; t < n_tiles; ++t) {
+  auto tile_body = [&](auto stage_c, int t) {
+    constexpr int STAGE = decltype(stage_c)::value;
     const int j0 = seg_a + t * kDqBC;
-    const bool more = (t + 1 < n_tiles);
-    const char* kt = smem + (t & 1) * 2 * Cfg::kTileBytes;
+    if (t + 1 < n_tiles) issue_tile(STAGE ^ 1);   // lands while this tile is processed
+    const char* kt = smem + STAGE * 2 * Cfg::kTileBytes;
     const char* vt = kt + Cfg::kTileBytes;
     const bool tail = (j0 + kDqBC > seg_b);
 
@@ -431,23 +444,23 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
           khi[s2][db] = lds_read_tr(kt, (tbase[1] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB);
         }
       __builtin_amdgcn_sched_barrier(0);
-      // the next tile's loads go out after this iteration's last LDS read
-      if (jb == JB - 1) {
-        if (more) issue_tile(j0 + kDqBC, (t + 1) & 1);
-        __builtin_amdgcn_sched_barrier(0);
-      }
       bf16x8 dsb[NI][2];
 #pragma unroll
       for (int ib = 0; ib < NI; ++ib) {
         f32x16 ds;
+        if (tail) {   // wave-uniform: only the clip's last tile pays for the key mask
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float pv = fast_exp2(sacc[ib][r] * scale_log2 - lse2[ib]);
-          if (tail) {
+          for (int r = 0; r < 16; ++r) {
             const int j = j0 + jb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-            pv = (j < seg_b) ? pv : 0.f;
+            const float pv = (j < seg_b) ? fast_exp2(sacc[ib][r] * scale_log2 - lse2[ib]) : 0.f;
+            ds[r] = pv * (dpacc[ib][r] - dlt[ib]);
           }
-          ds[r] = pv * (dpacc[ib][r] - dlt[ib]);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float pv = fast_exp2(sacc[ib][r] * scale_log2 - lse2[ib]);
+            ds[r] = pv * (dpacc[ib][r] - dlt[ib]);
+          }
         }
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
@@ -469,7 +482,12 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
       __builtin_amdgcn_sched_barrier(0);
     }
 
-    __syncthreads();   // next tile landed (vmcnt) and every wave is done reading this one
+    wait_vmcnt<0>();   // the next tile has landed ...
+    __syncthreads();   // ... for every wave, and every wave is done reading this one
+  };
+  for (int t = 0; t < n_tiles; t += 2) {
+    tile_body(IntC<0>{}, t);
+    if (t + 1 < n_tiles) tile_body(IntC<1>{}, t + 1);
   }
 
   // ---- epilogue: dq = bf16(scale * dQ^T)
