@@ -174,6 +174,8 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   const int n_q = seg_b - seg_a;
   const int n_steps = (n_q + kBwdBQ - 1) / kBwdBQ;
 
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) { settle(kreg[ks]); settle(vreg[ks]); }
   issue_tile(0);
   wait_vmcnt<0>();
   __syncthreads();
@@ -403,6 +405,12 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   const int n_tiles = (seg_b - seg_a + kDqBC - 1) / kDqBC;
+#pragma unroll
+  for (int ib = 0; ib < NI; ++ib)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) { settle(qreg[ib][ks]); settle(doreg[ib][ks]); }
+#pragma unroll
+  for (int ib = 0; ib < NI; ++ib) asm volatile("" :: "v"(lse2[ib]), "v"(dlt[ib]));
   issue_tile(0);
   wait_vmcnt<0>();
   __syncthreads();

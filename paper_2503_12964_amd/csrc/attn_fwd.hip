@@ -134,6 +134,10 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   const int n_kv = seg_b - seg_a;
   const int n_tiles = (n_kv + kFwdBC - 1) / kFwdBC;
 
+#pragma unroll
+  for (int ib = 0; ib < NI; ++ib)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) settle(qreg[ib][ks]);
   issue_tile(0);
   wait_vmcnt<0>();
   __syncthreads();

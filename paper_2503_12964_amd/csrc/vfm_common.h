@@ -174,6 +174,10 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 template <int V>
 struct IntC { static constexpr int value = V; };
+// Marks a loaded operand as used here, so that the compiler waits for its global load at
+// this point (before the main loop) instead of keeping conservative vmcnt waits inside
+// the loop, where they would also wait for the direct-to-LDS loads in flight.
+__device__ __forceinline__ void settle(const bf16x8& x) { asm volatile("" :: "v"(x)); }
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
