@@ -14,7 +14,8 @@ from typing import Optional, Sequence, Tuple
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libvfm.so")
+# VFM_LIB may point at another build of the library (same C ABI).
+LIB_PATH = os.environ.get("VFM_LIB") or os.path.join(_HERE, "libvfm.so")
 
 VFM_BF16 = 0
 VFM_F32 = 1

@@ -20,9 +20,9 @@ FLAGS = [
 ]
 
 
-def _compile(src: str, obj_dir: str) -> str:
+def _compile(src: str, obj_dir: str, csrc: str = CSRC) -> str:
     obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, "-c", os.path.join(csrc, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
@@ -33,18 +33,19 @@ def _compile(src: str, obj_dir: str) -> str:
     return obj
 
 
-def build_lib(verbose: bool = True) -> str:
-    obj_dir = os.path.join(HERE, "_build")
+def build_lib(verbose: bool = True, csrc: str = CSRC, out: str = LIB_PATH) -> str:
+    """Compile every source under `csrc` and link them into `out` (defaults: the in-tree library)."""
+    obj_dir = os.path.join(HERE, "_build") if out == LIB_PATH else out + ".obj"
     os.makedirs(obj_dir, exist_ok=True)
     with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
-        objs = list(ex.map(lambda s: _compile(s, obj_dir), SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH, *objs]
+        objs = list(ex.map(lambda s: _compile(s, obj_dir, csrc), SOURCES))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed:\n" + res.stderr)
     if verbose:
-        print(f"built {LIB_PATH}")
-    return LIB_PATH
+        print(f"built {out}")
+    return out
 
 
 if __name__ == "__main__":

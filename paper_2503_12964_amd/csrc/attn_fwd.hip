@@ -1,54 +1,68 @@
 // Packed variable-length attention forward for gfx950 (bf16 MFMA, fp32 accumulate).
 //
-// One workgroup owns one (head, query tile) of one clip and streams that clip's
-// K/V tiles (kBC rows) through LDS, double buffered.  Each wavefront owns
-// NI blocks of 32 query rows.  Scores are produced transposed,
+// One workgroup (4 wavefronts x 32 query rows) owns one (head, query tile) of one clip
+// and streams that clip's keys and values through LDS in units of 32 rows.
+//
+// Scores are produced transposed,
 //     S^T[j, i] = sum_d K[j, d] Q[i, d]         (32x32x16 MFMA, A = K rows, B = Q rows)
-// so that a lane holds 16 key positions of ONE query row per block: the row max
-// and row sum are in-lane reductions plus one exchange with lane^32, the O
-// rescale is a per-lane scalar, and the bf16 P registers are already the B
-// operand of
+// so that a lane holds 16 key positions of ONE query row: the row max and row sum are
+// in-lane reductions plus one exchange with lane^32, the O rescale is a per-lane scalar,
+// and the bf16 P registers are already the B operand of
 //     O^T[d, i] += sum_j V[j, d] P^T[j, i]      (A = V^T via transposing LDS reads).
-// The contraction slots of that second MFMA are bound to key rows in the order the
-// first MFMA's accumulator registers hold them (runs of 4 rows), which is also what
-// a transposing LDS read returns, so P never leaves registers.
+// The contraction slots of that second MFMA are bound to key rows in the order the first
+// MFMA's accumulator registers hold them (runs of 4 rows), which is also what a
+// transposing LDS read returns, so P never leaves registers.
+//
+// The loop is software pipelined over units so that one wavefront always has independent
+// MFMA and VALU work in flight: iteration u issues the MFMAs of S(u+1) and of
+// O += V(u-1) P(u-1) while the VALU computes the softmax of unit u.  A VALU instruction
+// costs 4 issue cycles (exp2: ~12) against 32 for an MFMA, so about five VALU
+// instructions fit under each MFMA; scheduling-group barriers ask the compiler for that
+// interleave.  K and V units live in two LDS rings of four slots, filled by direct
+// global->LDS loads issued three units ahead.
 #include "vfm_common.h"
 
 namespace vfm {
 
 constexpr int kFwdWaves = 4;
-constexpr int kFwdBC = 64;       // key/value rows per LDS tile
+constexpr int kFwdBR = kFwdWaves * 32;  // query rows per workgroup
+constexpr int kFwdU = 32;               // key/value rows per pipeline unit
+constexpr int kFwdRing = 4;             // LDS ring slots for K and for V
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kRescaleThreshold = 8.0f;  // in log2 units: lazily keep a stale row max up to 2^8
+constexpr float kRescaleThreshold = 8.0f;  // log2 units: a stale row max is kept up to 2^8
 
-template <int D, int NI>
+template <int D>
 struct FwdCfg {
-  static constexpr int kBR = kFwdWaves * NI * 32;          // query rows per workgroup
-  static constexpr int kTileBytes = kFwdBC * D * 2;        // one K or V tile
-  static constexpr int kLdsBytes = 4 * kTileBytes;         // K,V x 2 stages
+  static constexpr int kUnitBytes = kFwdU * D * 2;                  // one K or V unit
+  static constexpr int kLdsBytes = 2 * kFwdRing * kUnitBytes;       // K ring + V ring
   static constexpr int kChunksPerRow = D / 8;
-  static constexpr int kChunksPerThread = kFwdBC * kChunksPerRow / (kFwdWaves * 64);
+  static constexpr int kLoadsPerWave = kFwdU * kChunksPerRow / (kFwdWaves * 64);  // per unit, per tensor
 };
 
-template <int D, int NI>
-__global__ __launch_bounds__(kFwdWaves * 64, (NI == 1 ? 2 : 1))
+// scheduling-group masks
+constexpr int kSgValu = 0x002, kSgMfma = 0x008, kSgDsRead = 0x100;
+
+template <int D>
+__global__ __launch_bounds__(kFwdWaves * 64, 2)
 void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                      const __bf16* __restrict__ v, __bf16* __restrict__ out,
                      float* __restrict__ lse, const SegTable segs, const UnitMap um,
                      int total, int n_heads, float scale_log2) {
-  using Cfg = FwdCfg<D, NI>;
+  using Cfg = FwdCfg<D>;
   constexpr int KS = D / 16;   // k-steps of the QK^T contraction
   constexpr int DB = D / 32;   // 32-wide blocks of the head dimension
-  constexpr int JB = kFwdBC / 32;
-  constexpr int CPT = Cfg::kChunksPerThread;
+  constexpr int LPW = Cfg::kLoadsPerWave;
+  constexpr int UB = Cfg::kUnitBytes;
+  constexpr int RB = D * 2;
+  constexpr int kInFlight = 2 * 2 * LPW;   // loads of the two youngest batches (K and V each)
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   int head, tile;
   if (!map_unit(um, blockIdx.x, head, tile)) return;
   int seg_a, seg_b, q0;
-  find_tile(segs, Cfg::kBR, tile, seg_a, seg_b, q0);
+  find_tile(segs, kFwdBR, tile, seg_a, seg_b, q0);
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -60,58 +74,57 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   const __bf16* vbase = v + (size_t)head * D;
 
   // ---- Q operands (B operand of S^T): lane holds row i = c, columns ks*16 + 8g..+7
-  bf16x8 qreg[NI][KS];
-  int qrow[NI];
-#pragma unroll
-  for (int ib = 0; ib < NI; ++ib) {
-    qrow[ib] = q0 + (wave * NI + ib) * 32 + c;
-    const int r = min(qrow[ib], seg_b - 1);
+  bf16x8 qreg[KS];
+  const int qrow = q0 + wave * 32 + c;
+  {
+    const int r = min(qrow, seg_b - 1);
     const __bf16* qp = q + (size_t)r * row_stride + (size_t)head * D + 8 * g;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) qreg[ib][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    for (int ks = 0; ks < KS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
   }
 
-  // ---- K/V staging with direct global->LDS loads (no staging registers, no LDS
-  // writes).  One wave instruction fills 64 consecutive 16-byte chunks of a tile;
-  // lane L of instruction (x, wave) owns LDS chunk P = (x*waves + wave)*64 + L, i.e.
-  // tile row P / chunks_per_row, physical chunk P % chunks_per_row, and fetches the
-  // logical chunk that the swizzle maps there.  Global byte offsets are 32-bit and are
-  // advanced by one tile per iteration; rows past the clip end clamp to its last row.
+  // ---- K/V staging with direct global->LDS loads.  One wave instruction fills 64
+  // consecutive 16-byte chunks of a unit; lane L of instruction (x, wave) owns chunk
+  // P = (x*waves + wave)*64 + L, i.e. unit row P / chunks_per_row, physical chunk
+  // P % chunks_per_row, and fetches the logical chunk the swizzle maps there.  Global
+  // byte offsets are 32-bit, advanced one unit per request; rows past the clip end clamp
+  // to its last row (their scores are masked).  Units are requested strictly in order.
   const uint32_t row_bytes = (uint32_t)row_stride * 2u;
   const uint32_t last_row_off = (uint32_t)(seg_b - 1) * row_bytes;
-  uint32_t st_rowoff[CPT], st_colb[CPT];
+  uint32_t st_colb[LPW], k_rowoff[LPW], v_rowoff[LPW];
 #pragma unroll
-  for (int x = 0; x < CPT; ++x) {
+  for (int x = 0; x < LPW; ++x) {
     const int p = (x * kFwdWaves + wave) * 64 + lane;
     const int r = p / Cfg::kChunksPerRow;
-    st_rowoff[x] = (uint32_t)(seg_a + r) * row_bytes;
+    k_rowoff[x] = v_rowoff[x] = (uint32_t)(seg_a + r) * row_bytes;
     st_colb[x] = (uint32_t)(((p % Cfg::kChunksPerRow) ^ swz<D>(r)) * 16);
   }
-  const uint32_t smem_addr = lds_addr_of(smem);
-  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(smem_addr + wave * 1024);
-  // issues the next tile in row order (tiles are always requested in sequence)
-  auto issue_tile = [&](int stage) {
+  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_addr_of(smem) + wave * 1024);
+  auto issue_k = [&](int slot) {
 #pragma unroll
-    for (int x = 0; x < CPT; ++x) {
-      const uint32_t off = min(st_rowoff[x], last_row_off) + st_colb[x];
-      const uint32_t dst = wave_lds + stage * 2 * Cfg::kTileBytes + x * kFwdWaves * 1024;
-      lds_dma16(kbase, off, dst);
-      lds_dma16(vbase, off, dst + Cfg::kTileBytes);
-      st_rowoff[x] += kFwdBC * row_bytes;
+    for (int x = 0; x < LPW; ++x) {
+      lds_dma16(kbase, min(k_rowoff[x], last_row_off) + st_colb[x],
+                wave_lds + slot * UB + x * kFwdWaves * 1024);
+      k_rowoff[x] += kFwdU * row_bytes;
+    }
+  };
+  auto issue_v = [&](int slot) {
+#pragma unroll
+    for (int x = 0; x < LPW; ++x) {
+      lds_dma16(vbase, min(v_rowoff[x], last_row_off) + st_colb[x],
+                wave_lds + (kFwdRing + slot) * UB + x * kFwdWaves * 1024);
+      v_rowoff[x] += kFwdU * row_bytes;
     }
   };
 
-  // ---- per-lane LDS read offsets (within a tile).  The swizzle XORs bits 4..7 of the
-  // byte offset with a function of (row & 15) only, so the offsets of the other
-  // k-steps / head-dim blocks / row blocks follow from one base per lane:
-  //   K rows as A operand: row jb*32 + c, columns ks*16 + 8g
-  //       off = (kbase ^ (ks << 5)) + jb*32*rowbytes
-  //   V^T as A operand via transposing reads.  For k-step s2 of key block jb the 8
-  //   contraction slots of lane group g are key rows jb*32 + 16*s2 + {4g..4g+3} (t=0)
-  //   and {8+4g..8+4g+3} (t=1); the lane addresses row +((lane&15)>>2), columns
-  //   db*32 + 16*((lane>>4)&1) + 4*(lane&3):
-  //       off = (vbase[t] ^ (db << 6)) + (jb*32 + 16*s2)*rowbytes
-  constexpr int RB = D * 2;
+  // ---- per-lane LDS read offsets within a unit.  The swizzle XORs bits 4..7 of the byte
+  // offset with a function of (row & 15) only, so one base per lane serves every k-step
+  // and head-dim block:
+  //   K rows as A operand (row c, columns ks*16 + 8g):   off = kbase_off ^ (ks << 5)
+  //   V^T as A operand via transposing reads.  For k-step s2 the 8 contraction slots of
+  //   lane group g are key rows 16*s2 + {4g..4g+3} (t=0) and {8+4g..8+4g+3} (t=1); the
+  //   lane addresses row +((lane&15)>>2), columns db*32 + 16*((lane>>4)&1) + 4*(lane&3):
+  //                                                      off = (vbase_off[t] ^ (db << 6)) + 16*s2*RB
   const int kbase_off = tile_off<D>(c, 8 * g);
   int vbase_off[2];
 #pragma unroll
@@ -119,186 +132,213 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     vbase_off[t] = tile_off<D>(8 * t + 4 * g + ((lane & 15) >> 2),
                                16 * ((lane >> 4) & 1) + 4 * (lane & 3));
 
-  f32x16 oacc[NI][DB];
-  float m_run[NI], l_run[NI];
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  f32x16 oacc[DB];
 #pragma unroll
-  for (int ib = 0; ib < NI; ++ib) {
-    m_run[ib] = -INFINITY;
-    l_run[ib] = 0.f;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[ib][db][r] = 0.f;
-  }
+  for (int db = 0; db < DB; ++db) oacc[db] = zero16;
 
-  const int n_kv = seg_b - seg_a;
-  const int n_tiles = (n_kv + kFwdBC - 1) / kFwdBC;
+  const int n_units = (seg_b - seg_a + kFwdU - 1) / kFwdU;
 
+  auto read_k = [&](int slot, bf16x8 (&ka)[KS]) {
+    const char* kt = smem + slot * UB;
 #pragma unroll
-  for (int ib = 0; ib < NI; ++ib)
+    for (int ks = 0; ks < KS; ++ks) ka[ks] = lds_read_b128(kt, kbase_off ^ (ks << 5));
+  };
+  auto mask_tail = [&](int u, f32x16& s) {   // keys past the clip end (last unit only)
+    const int j0 = seg_a + u * kFwdU;
+    if (j0 + kFwdU > seg_b) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) settle(qreg[ib][ks]);
-  issue_tile(0);
+      for (int r = 0; r < 16; ++r)
+        if (j0 + 8 * (r >> 2) + 4 * g + (r & 3) >= seg_b) s[r] = -INFINITY;
+    }
+  };
+
+  // ---- prologue: K units 0..3 and V units 0..1 requested; S(0); operands of K(1)
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) settle(qreg[ks]);
+  issue_k(0); issue_k(1); issue_k(2); issue_k(3);
+  issue_v(0); issue_v(1);
   wait_vmcnt<0>();
   __syncthreads();
 
-  // One tile; STAGE is a compile-time constant so every LDS offset is an immediate.
-  auto tile_body = [&](auto stage_c, int t) {
-    constexpr int STAGE = decltype(stage_c)::value;
-    const int j0 = seg_a + t * kFwdBC;
-    // the next tile's loads are issued first and land while this tile is processed
-    if (t + 1 < n_tiles) issue_tile(STAGE ^ 1);
+  bf16x8 ka[KS];
+  f32x16 s_cur;
+  {
+    bf16x8 k0[KS];
+    read_k(0, k0);
+    read_k(1, ka);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) s_cur = mfma32(k0[ks], qreg[ks], ks == 0 ? zero16 : s_cur);
+    mask_tail(0, s_cur);
+  }
+  // the first reference point is the exact row max of unit 0, so nothing needs rescaling
+  float m_run, l_run = 0.f;
+  {
+    float mx = s_cur[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_cur[r]);
+    m_run = pair_max(mx) * scale_log2;
+  }
+  __syncthreads();            // every wave holds K(0), K(1) in registers: slots 0, 1 are free
+  issue_k(0);                 // K unit 4
 
-    const char* kt = smem + STAGE * 2 * Cfg::kTileBytes;
-    const char* vt = kt + Cfg::kTileBytes;
+  bf16x8 pb_prev[2];          // P(u-1), set by the first iteration before any use
+  pb_prev[0] = pb_prev[1] = bf16x8{};
 
-    // ---- all K operand reads of this tile are issued before the first MFMA, so their
-    // LDS latency overlaps; the scheduling barriers keep the compiler from
-    // re-serialising read -> wait -> MFMA.
-    bf16x8 ka[JB][KS];
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb)
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-        ka[jb][ks] = lds_read_b128(kt, (kbase_off ^ (ks << 5)) + jb * 32 * RB);
-    __builtin_amdgcn_sched_barrier(0);
+  // One pipeline iteration.  SLOT = u % 4 is a compile-time constant so every LDS offset
+  // is an immediate.  With PV = false (u = 0) there is no previous unit to accumulate.
+  auto iteration = [&](auto slot_c, auto pv_c, int u) {
+    constexpr int SLOT = decltype(slot_c)::value;
+    constexpr bool PV = decltype(pv_c)::value != 0;
+    // requests: K(u+5) into the slot of K(u+1), V(u+2) into the slot of V(u-2)
+    issue_k((SLOT + 1) % kFwdRing);
+    issue_v((SLOT + 2) % kFwdRing);
 
-    // ---- S^T = K Q^T (the first k-step starts from a zero accumulator)
-    f32x16 sacc[JB][NI];
-    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-      for (int jb = 0; jb < JB; ++jb)
-#pragma unroll
-        for (int ib = 0; ib < NI; ++ib)
-          sacc[jb][ib] = mfma32(ka[jb][ks], qreg[ib][ks], ks == 0 ? zero16 : sacc[jb][ib]);
-
-    // ---- V^T operand reads are issued now, in the shadow of the S MFMAs and the softmax
-    s16x4 vlo[JB][2][DB], vhi[JB][2][DB];
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb)
+    // ---- region 1: S(u+1) MFMAs | V(u-1) operand reads | first half of softmax(u)
+    s16x4 vlo[2][DB], vhi[2][DB];
+    if constexpr (PV) {
+      const char* vt = smem + (kFwdRing + (SLOT + 3) % kFwdRing) * UB;
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          vlo[jb][s2][db] = lds_read_tr(vt, (vbase_off[0] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB);
-          vhi[jb][s2][db] = lds_read_tr(vt, (vbase_off[1] ^ (db << 6)) + (jb * 32 + 16 * s2) * RB);
-        }
-    __builtin_amdgcn_sched_barrier(0);
-
-    // ---- mask keys past the end of the clip (last tile only)
-    if (j0 + kFwdBC > seg_b) {
-#pragma unroll
-      for (int jb = 0; jb < JB; ++jb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = j0 + jb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-          if (j >= seg_b) {
-#pragma unroll
-            for (int ib = 0; ib < NI; ++ib) sacc[jb][ib][r] = -INFINITY;
-          }
+          vlo[s2][db] = lds_read_tr(vt, (vbase_off[0] ^ (db << 6)) + 16 * s2 * RB);
+          vhi[s2][db] = lds_read_tr(vt, (vbase_off[1] ^ (db << 6)) + 16 * s2 * RB);
         }
     }
+    f32x16 s_next;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) s_next = mfma32(ka[ks], qreg[ks], ks == 0 ? zero16 : s_next);
 
-    // ---- online softmax (log2 domain), P -> bf16
-    bf16x8 pb[NI][JB][2];
+    // softmax of unit u (log2 domain).  The reference point m_run only moves when some
+    // row's max grew by more than the threshold (wave-uniform decision); otherwise the
+    // exponentials are taken against the stale max, which is exact after the final
+    // normalisation and bounded by 2^threshold.
+    float mx = s_cur[0];
 #pragma unroll
-    for (int ib = 0; ib < NI; ++ib) {
-      float mx = sacc[0][ib][0];
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s_cur[r]);
+    mx = pair_max(mx) * scale_log2;
+    const bool move = __builtin_amdgcn_ballot_w64(mx - m_run > kRescaleThreshold) != 0;
+    const float m_new = move ? fmaxf(m_run, mx) : m_run;
+    const float alpha = fast_exp2(m_run - m_new);      // 1 unless the reference moved
+    m_run = m_new;
+    f32x8 p0, p1;
+    float lsum = 0.f;
 #pragma unroll
-      for (int jb = 0; jb < JB; ++jb)
+    for (int r = 0; r < 8; ++r) {
+      p0[r] = fast_exp2(s_cur[r] * scale_log2 - m_new);
+      lsum += p0[r];
+    }
+    bf16x8 pb_cur[2];
+    pb_cur[0] = to_bf16x8(p0);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[jb][ib][r]);
-      mx = pair_max(mx) * scale_log2;
-      const float m_new = fmaxf(m_run[ib], mx);
-      // The reference point only moves when some row's max grew by more than the
-      // threshold; otherwise exponentials are taken against the stale max (exact
-      // after the final normalisation, and bounded by 2^threshold).
-      if (__builtin_amdgcn_ballot_w64(m_new - m_run[ib] > kRescaleThreshold) != 0) {
-        const float alpha = fast_exp2(m_run[ib] - m_new);
-        l_run[ib] *= alpha;
+    for (int i = 0; i < KS; ++i) {
+      __builtin_amdgcn_sched_group_barrier(kSgMfma, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(kSgDsRead, PV ? 2 : 0, 0);
+      __builtin_amdgcn_sched_group_barrier(kSgValu, 5, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- region 2: O += V(u-1) P(u-1) MFMAs | K(u+2) operand reads | second half of softmax(u)
+    if constexpr (PV) {
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
         for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[ib][db][r] *= alpha;
-        m_run[ib] = m_new;
-      }
-      const float mref = m_run[ib];
-      float lsum = 0.f;
-#pragma unroll
-      for (int jb = 0; jb < JB; ++jb) {
-        f32x8 p0, p1;
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-          p0[r] = fast_exp2(sacc[jb][ib][r] * scale_log2 - mref);
-          p1[r] = fast_exp2(sacc[jb][ib][8 + r] * scale_log2 - mref);
-          lsum += p0[r] + p1[r];
-        }
-        pb[ib][jb][0] = to_bf16x8(p0);
-        pb[ib][jb][1] = to_bf16x8(p1);
-      }
-      l_run[ib] += lsum;
+          oacc[db] = mfma32(join_tr(vlo[s2][db], vhi[s2][db]), pb_prev[s2], oacc[db]);
     }
-
-    // ---- O^T += V^T P^T
+    bf16x8 ka_next[KS];
+    read_k((SLOT + 2) % kFwdRing, ka_next);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      p1[r] = fast_exp2(s_cur[8 + r] * scale_log2 - m_new);
+      lsum += p1[r];
+    }
+    l_run = l_run * alpha + lsum;
+    pb_cur[1] = to_bf16x8(p1);
+#pragma unroll
+    for (int i = 0; i < 2 * DB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(kSgMfma, PV ? 1 : 0, 0);
+      __builtin_amdgcn_sched_group_barrier(kSgDsRead, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(kSgValu, 4, 0);
+    }
+    // keep the softmax in this block: later branches must not pull it below them
+    asm volatile("" : "+v"(pb_cur[0]), "+v"(pb_cur[1]), "+v"(l_run));
     __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int jb = 0; jb < JB; ++jb)
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x8 va = join_tr(vlo[jb][s2][db], vhi[jb][s2][db]);
-#pragma unroll
-          for (int ib = 0; ib < NI; ++ib) oacc[ib][db] = mfma32(va, pb[ib][jb][s2], oacc[ib][db]);
-        }
-    __builtin_amdgcn_sched_barrier(0);
 
-    wait_vmcnt<0>();   // the next tile has landed ...
-    __syncthreads();   // ... for every wave, and every wave is done reading this one
-  };
-  for (int t = 0; t < n_tiles; t += 2) {
-    tile_body(IntC<0>{}, t);
-    if (t + 1 < n_tiles) tile_body(IntC<1>{}, t + 1);
-  }
-
-  // ---- epilogue: normalise, write out (bf16) and lse (natural log)
-#pragma unroll
-  for (int ib = 0; ib < NI; ++ib) {
-    const float l_tot = pair_sum(l_run[ib]);
-    const float inv = 1.0f / l_tot;
-    const int i = qrow[ib];
-    if (i < seg_b) {
-      __bf16* op = out + (size_t)i * row_stride + (size_t)head * D + 4 * g;
+    // rare: the reference point moved, bring the accumulator (which now includes unit
+    // u-1, taken against the old reference) to the new one
+    if (move) {
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = oacc[ib][db][q4 * 4 + e] * inv;
-          *reinterpret_cast<bf16x4*>(op + db * 32 + q4 * 8) = to_bf16x4(o);
-        }
-      if (g == 0) lse[(size_t)head * total + i] = (m_run[ib] + __log2f(l_tot)) * kLn2;
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
     }
+
+    mask_tail(u + 1, s_next);
+    s_cur = s_next;
+    pb_prev[0] = pb_cur[0];
+    pb_prev[1] = pb_cur[1];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) ka[ks] = ka_next[ks];
+
+    wait_vmcnt<kInFlight>();   // everything but the two youngest batches has landed ...
+    __syncthreads();           // ... for every wave, and every wave is done with this unit's slots
+  };
+
+  iteration(IntC<0>{}, IntC<0>{}, 0);
+  for (int u = 1; u < n_units; u += 4) {
+    iteration(IntC<1>{}, IntC<1>{}, u);
+    if (u + 1 < n_units) iteration(IntC<2>{}, IntC<1>{}, u + 1);
+    if (u + 2 < n_units) iteration(IntC<3>{}, IntC<1>{}, u + 2);
+    if (u + 3 < n_units) iteration(IntC<0>{}, IntC<1>{}, u + 3);
+  }
+  // ---- drain: accumulate the last unit
+  {
+    const char* vt = smem + (kFwdRing + (n_units - 1) % kFwdRing) * UB;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const bf16x8 va = join_tr(lds_read_tr(vt, (vbase_off[0] ^ (db << 6)) + 16 * s2 * RB),
+                                  lds_read_tr(vt, (vbase_off[1] ^ (db << 6)) + 16 * s2 * RB));
+        oacc[db] = mfma32(va, pb_prev[s2], oacc[db]);
+      }
+  }
+  wait_vmcnt<0>();   // no load may still be writing LDS when the workgroup ends
+
+  // ---- epilogue: normalise, write out (bf16) and lse (natural log)
+  const float l_tot = pair_sum(l_run);
+  const float inv = 1.0f / l_tot;
+  if (qrow < seg_b) {
+    __bf16* op = out + (size_t)qrow * row_stride + (size_t)head * D + 4 * g;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        f32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = oacc[db][q4 * 4 + e] * inv;
+        *reinterpret_cast<bf16x4*>(op + db * 32 + q4 * 8) = to_bf16x4(o);
+      }
+    if (g == 0) lse[(size_t)head * total + qrow] = (m_run + __log2f(l_tot)) * kLn2;
   }
 }
 
-template <int D, int NI>
+template <int D>
 static hipError_t launch_fwd_cfg(const void* q, const void* k, const void* v, const SegTable& segs,
                                  int total, int n_heads, float scale, void* out, float* lse,
                                  hipStream_t stream) {
-  using Cfg = FwdCfg<D, NI>;
+  using Cfg = FwdCfg<D>;
   int tiles = 0;
-  for (int s = 0; s < segs.n; ++s) tiles += (segs.len[s] + Cfg::kBR - 1) / Cfg::kBR;
+  for (int s = 0; s < segs.n; ++s) tiles += (segs.len[s] + kFwdBR - 1) / kFwdBR;
   if (tiles == 0) return hipSuccess;
   UnitMap um;
   um.tiles_per_head = tiles;
   um.n_units = tiles * n_heads;
   um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
   const int grid = um.chunk * kNumXcd;
-  auto kern = attn_fwd_kernel<D, NI>;
+  auto kern = attn_fwd_kernel<D>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
   if (e != hipSuccess) return e;
@@ -311,8 +351,8 @@ static hipError_t launch_fwd_cfg(const void* q, const void* k, const void* v, co
 hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, const SegTable& segs,
                            int total, int n_heads, int head_dim, float scale, void* out,
                            float* lse, hipStream_t stream) {
-  if (head_dim == 128) return launch_fwd_cfg<128, 1>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
-  return launch_fwd_cfg<64, 1>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
+  if (head_dim == 128) return launch_fwd_cfg<128>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
+  return launch_fwd_cfg<64>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
 }
 
 }  // namespace vfm
