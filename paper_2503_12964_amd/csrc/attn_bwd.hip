@@ -3,7 +3,8 @@
 // Three kernels, no atomics (device-wide fp32 atomics are executed at the memory side on
 // this chip and were measured to bound the fused variant), so every output is written
 // once and the result is bitwise reproducible:
-//   bwd_prepare : Delta[h,i] = sum_d dO[i,h,d] O[i,h,d]  and  lse2 = lse * log2(e)
+//   bwd_prepare : Delta[h,i] = sum_d dO[i,h,d] O[i,h,d],  lse2 = lse * log2(e), and two
+//                 sentinel statistics (+inf, 0) used for rows past a clip's end
 //   bwd_dkdv    : one workgroup owns kBC key/value rows of one (clip, head); its four
 //                 wavefronts own 32 of those rows each and keep their K and V rows, and
 //                 their dK^T / dV^T accumulators, in registers.  The workgroup walks the
@@ -33,7 +34,8 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const u32x4* __restric
                                                           const u32x4* __restrict__ dout,
                                                           const float* __restrict__ lse,
                                                           float* __restrict__ delta,
-                                                          float* __restrict__ lse2, int total,
+                                                          float* __restrict__ lse2,
+                                                          float* __restrict__ sentinel, int total,
                                                           int n_heads) {
   constexpr int kLanesPerRow = D / 8;
   constexpr int kTokPerBlock = 256 / kLanesPerRow;
@@ -41,6 +43,10 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const u32x4* __restric
   const int chunk = threadIdx.x % kLanesPerRow;
   const bool valid = tok < total;
   const int tk = valid ? tok : total - 1;
+  if (blockIdx.x == 0 && threadIdx.x == 0) {   // statistics fetched for rows past a clip's end
+    sentinel[0] = INFINITY;                    // lse2: P = exp2(s - inf) = 0
+    sentinel[1] = 0.f;                         // Delta
+  }
   for (int h = 0; h < n_heads; ++h) {
     const size_t row = (size_t)tk * n_heads + h;
     const u32x4 a = out[row * kLanesPerRow + chunk];
@@ -61,28 +67,45 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const u32x4* __restric
 }
 
 // ---------------------------------------------------------------- dK, dV
+// Software pipelined over query blocks of 32 rows so that a single wavefront per SIMD
+// always has independent MFMA and VALU work: iteration b runs
+//   phase A:  S(b+1), dP(b+1) MFMAs        |  P(b)  = exp2(S(b)*scale - lse2)        (VALU)
+//   phase B:  dV^T += dO(b)^T P(b) MFMAs   |  dS(b) = P(b) o (dP(b) - Delta)         (VALU)
+//   phase C:  dK^T += Q(b)^T dS(b) MFMAs   |  row-operand reads of block b+2, tile requests
+// Q/dO tiles of 64 rows (two blocks) live in a ring of four LDS stages filled by direct
+// global->LDS loads three tiles ahead; there is one workgroup barrier per tile.
+// Query rows past the clip end need no mask: their lse2 is fetched from a +inf sentinel
+// (so P = 0) and their Delta from a 0 sentinel.  Key rows past the clip end need none
+// either: a lane's key only feeds that lane's own dK/dV row, which is never stored.
+constexpr int kBwdRing = 4;
+constexpr int kSgValuB = 0x002, kSgMfmaB = 0x008, kSgDsReadB = 0x100;
+
 template <int D>
 struct BwdCfg {
-  static constexpr int kTileBytes = kBwdBQ * D * 2;               // one Q or dO tile
-  static constexpr int kStageBytes = 2 * kTileBytes + 4 * kBwdBQ * 4;  // Q, dO, lse2, Delta (+ spare)
-  static constexpr int kLdsBytes = 2 * kStageBytes;
+  static constexpr int kTileBytes = kBwdBQ * D * 2;                      // one Q or dO tile
+  static constexpr int kStageBytes = 2 * kTileBytes + 4 * kBwdBQ * 4;    // Q, dO, lse2, Delta (+ spare)
+  static constexpr int kLdsBytes = kBwdRing * kStageBytes;
   static constexpr int kChunksPerRow = D / 8;
-  static constexpr int kChunksPerThread = kBwdBQ * kChunksPerRow / (kBwdWaves * 64);
+  static constexpr int kLoadsPerWave = kBwdBQ * kChunksPerRow / (kBwdWaves * 64);  // per tile, per tensor
+  static constexpr int kBatch = 2 * kLoadsPerWave + 1;                   // loads per wave per tile
 };
 
 template <int D>
 __global__ __launch_bounds__(kBwdWaves * 64, 1)
 void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                     const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
-                     const float* __restrict__ lse2, const float* __restrict__ delta,
-                     __bf16* __restrict__ dk, __bf16* __restrict__ dv,
-                     const SegTable segs, const UnitMap um,
-                     int total, int n_heads, float scale, float scale_log2) {
+                          const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
+                          const float* __restrict__ lse2, const float* __restrict__ delta,
+                          const float* __restrict__ sentinel,   // [+inf, 0]
+                          __bf16* __restrict__ dk, __bf16* __restrict__ dv,
+                          const SegTable segs, const UnitMap um,
+                          int total, int n_heads, float scale, float scale_log2) {
   using Cfg = BwdCfg<D>;
   constexpr int KS = D / 16;
   constexpr int DB = D / 32;
-  constexpr int NIB = kBwdBQ / 32;              // query blocks per step (2)
-  constexpr int CPT = Cfg::kChunksPerThread;
+  constexpr int LPW = Cfg::kLoadsPerWave;
+  constexpr int SB = Cfg::kStageBytes;
+  constexpr int TB = Cfg::kTileBytes;
+  constexpr int RB = D * 2;
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -102,7 +125,6 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   // ---- this wavefront's key/value rows as B operands (lane: row c, columns ks*16+8g..)
   const int jrow = j0 + wave * 32 + c;
   const bool jvalid = jrow < seg_b;
-  const bool tail_kv = (j0 + kBwdBC > seg_b);
   bf16x8 kreg[KS], vreg[KS];
   {
     const size_t off = (size_t)min(jrow, seg_b - 1) * row_stride + head_off + 8 * g;
@@ -112,51 +134,53 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
       vreg[ks] = *reinterpret_cast<const bf16x8*>(v + off + ks * 16);
     }
   }
-  // ---- staging of Q / dO / lse2 / Delta tiles with direct global->LDS loads.
-  // Lane L of wave instruction (x, wave) owns LDS chunk P = (x*waves + wave)*64 + L of
-  // the tile (row P / chunks_per_row, physical chunk P % chunks_per_row) and fetches the
-  // logical chunk the swizzle maps there.  Every wave also fetches 64 row statistics
-  // (4 bytes per lane): wave 0 lse2, wave 1 Delta, waves 2 and 3 the same again into
-  // spare LDS, so that all waves have the same number of loads in flight.
+
+  // ---- tile requests (direct global->LDS).  Lane L of wave instruction (x, wave) owns
+  // LDS chunk P = (x*waves + wave)*64 + L of the tile (row P / chunks_per_row, physical
+  // chunk P % chunks_per_row) and fetches the logical chunk the swizzle maps there.
+  // Every wave also fetches 64 row statistics (4 bytes per lane): waves 0/2 lse2, waves
+  // 1/3 Delta (2 and 3 into spare LDS, so that all waves have equally many loads in
+  // flight).  Tiles are requested strictly in order; offsets advance by one tile.
   const uint32_t row_bytes = (uint32_t)row_stride * 2u;
   const uint32_t last_row_off = (uint32_t)(seg_b - 1) * row_bytes;
   const __bf16* qbase = q + head_off;
   const __bf16* dobase = dout + head_off;
-  uint32_t st_rowoff[CPT], st_colb[CPT];
+  uint32_t st_rowoff[LPW], st_colb[LPW];
 #pragma unroll
-  for (int x = 0; x < CPT; ++x) {
+  for (int x = 0; x < LPW; ++x) {
     const int p = (x * kBwdWaves + wave) * 64 + lane;
     const int r = p / Cfg::kChunksPerRow;
     st_rowoff[x] = (uint32_t)(seg_a + r) * row_bytes;
     st_colb[x] = (uint32_t)(((p % Cfg::kChunksPerRow) ^ swz<D>(r)) * 16);
   }
-  const float* stat_src = uniform_ptr(((wave & 1) == 0 ? lse2 : delta) + (size_t)head * total);
-  uint32_t stat_off = (uint32_t)(seg_a + lane) * 4u;
-  const uint32_t stat_last = (uint32_t)(seg_b - 1) * 4u;
+  const bool is_lse = (wave & 1) == 0;
+  const float* stat_src = uniform_ptr(is_lse ? lse2 : delta);
+  const uint32_t stat_sentinel = (uint32_t)((const char*)(sentinel + (is_lse ? 0 : 1)) - (const char*)stat_src);
+  int stat_row = seg_a + lane;                         // packed row this lane fetches next
+  const uint32_t stat_head = (uint32_t)((size_t)head * total * 4u);
   const uint32_t smem_addr = lds_addr_of(smem);
   const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(smem_addr + wave * 1024);
-  const uint32_t stat_lds = __builtin_amdgcn_readfirstlane(smem_addr + 2 * Cfg::kTileBytes + wave * (kBwdBQ * 4));
-  auto issue_tile = [&](int stage) {   // tiles are requested in sequence
+  const uint32_t stat_lds = __builtin_amdgcn_readfirstlane(smem_addr + 2 * TB + wave * (kBwdBQ * 4));
+  auto issue_tile = [&](int stage) {
 #pragma unroll
-    for (int x = 0; x < CPT; ++x) {
+    for (int x = 0; x < LPW; ++x) {
       const uint32_t off = min(st_rowoff[x], last_row_off) + st_colb[x];
-      const uint32_t dst = wave_lds + stage * Cfg::kStageBytes + x * kBwdWaves * 1024;
+      const uint32_t dst = wave_lds + stage * SB + x * kBwdWaves * 1024;
       lds_dma16(qbase, off, dst);
-      lds_dma16(dobase, off, dst + Cfg::kTileBytes);
+      lds_dma16(dobase, off, dst + TB);
       st_rowoff[x] += kBwdBQ * row_bytes;
     }
-    lds_dma4(stat_src, min(stat_off, stat_last), stat_lds + stage * Cfg::kStageBytes);
-    stat_off += kBwdBQ * 4u;
+    const uint32_t soff = stat_row < seg_b ? stat_head + (uint32_t)stat_row * 4u : stat_sentinel;
+    lds_dma4(stat_src, soff, stat_lds + stage * SB);
+    stat_row += kBwdBQ;
   };
 
-  // ---- per-lane LDS offsets.  The swizzle XORs low byte-offset bits with a function
-  // of the low row bits only, so one base per lane serves every k-step / block:
+  // ---- per-lane LDS offsets within a tile.  The swizzle XORs low byte-offset bits with a
+  // function of the low row bits only, so one base per lane serves every k-step / block:
   //   Q/dO rows as A operand (row ib*32 + c, columns ks*16 + 8g):
   //       off = (rbase ^ (ks << 5)) + ib*32*rowbytes
-  //   Q^T/dO^T as A operand through transposing reads (same slot binding as the
-  //   forward kernel's V^T operand):
-  //       off = (tbase[t] ^ (db << 6)) + (ib*32 + 16*s2)*rowbytes
-  constexpr int RB = D * 2;
+  //   Q^T/dO^T as A operand through transposing reads (same slot binding as the forward
+  //   kernel's V^T operand):  off = (tbase[t] ^ (db << 6)) + (ib*32 + 16*s2)*rowbytes
   const int rbase = tile_off<D>(c, 8 * g);
   int tbase[2];
 #pragma unroll
@@ -164,122 +188,162 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     tbase[t] = tile_off<D>(8 * t + 4 * g + ((lane & 15) >> 2),
                            16 * ((lane >> 4) & 1) + 4 * (lane & 3));
 
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   f32x16 dkacc[DB], dvacc[DB];
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int db = 0; db < DB; ++db) { dkacc[db] = zero16; dvacc[db] = zero16; }
+
+  const int n_tiles = (seg_b - seg_a + kBwdBQ - 1) / kBwdBQ;
+  const int n_blocks = 2 * n_tiles;
+
+  auto read_rows = [&](int stage, int ib, bf16x8 (&qa)[KS], bf16x8 (&da)[KS]) {
+    const char* qt = smem + stage * SB;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { dkacc[db][r] = 0.f; dvacc[db][r] = 0.f; }
-  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int ks = 0; ks < KS; ++ks) {
+      const int off = (rbase ^ (ks << 5)) + ib * 32 * RB;
+      qa[ks] = lds_read_b128(qt, off);
+      da[ks] = lds_read_b128(qt + TB, off);
+    }
+  };
 
-  const int n_q = seg_b - seg_a;
-  const int n_steps = (n_q + kBwdBQ - 1) / kBwdBQ;
-
+  // ---- prologue: tiles 0..2 requested; S(0), dP(0); row operands of block 1
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) { settle(kreg[ks]); settle(vreg[ks]); }
-  issue_tile(0);
+  issue_tile(0); issue_tile(1); issue_tile(2);
   wait_vmcnt<0>();
   __syncthreads();
 
-  auto step_body = [&](auto stage_c, int t) {
-    constexpr int STAGE = decltype(stage_c)::value;
-    const int q0 = seg_a + t * kBwdBQ;
-    if (t + 1 < n_steps) issue_tile(STAGE ^ 1);   // lands while this tile is processed
-    const bool masked = tail_kv || (q0 + kBwdBQ > seg_b);
-
-    const char* qt = smem + STAGE * Cfg::kStageBytes;
-    const char* dot = qt + Cfg::kTileBytes;
-    const float* lse_s = reinterpret_cast<const float*>(qt + 2 * Cfg::kTileBytes);
-    const float* delta_s = lse_s + kBwdBQ;   // (wave 1's statistics follow wave 0's)
-
+  bf16x8 qa_n[KS], da_n[KS];      // row operands of block b+1
+  f32x16 s_cur, dp_cur;           // S(b), dP(b)
+  {
+    bf16x8 q0r[KS], d0r[KS];
+    read_rows(0, 0, q0r, d0r);
+    read_rows(0, 1, qa_n, da_n);
 #pragma unroll
-    for (int ib = 0; ib < NIB; ++ib) {
-      // ---- all row operands of this query block are requested before the first MFMA
-      bf16x8 qa[KS], da[KS];
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const int off = (rbase ^ (ks << 5)) + ib * 32 * RB;
-        qa[ks] = lds_read_b128(qt, off);
-        da[ks] = lds_read_b128(dot, off);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      f32x16 sacc, dpacc;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        sacc = mfma32(qa[ks], kreg[ks], ks == 0 ? zero16 : sacc);
-        dpacc = mfma32(da[ks], vreg[ks], ks == 0 ? zero16 : dpacc);
-      }
-      // ---- transposed operands and row statistics, requested in the MFMAs' shadow
-      s16x4 dlo[2][DB], dhi[2][DB], qlo[2][DB], qhi[2][DB];
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const int o0 = (tbase[0] ^ (db << 6)) + (ib * 32 + 16 * s2) * RB;
-          const int o1 = (tbase[1] ^ (db << 6)) + (ib * 32 + 16 * s2) * RB;
-          dlo[s2][db] = lds_read_tr(dot, o0);
-          dhi[s2][db] = lds_read_tr(dot, o1);
-          qlo[s2][db] = lds_read_tr(qt, o0);
-          qhi[s2][db] = lds_read_tr(qt, o1);
-        }
-      f32x4 l4[4], d4[4];
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        l4[q4] = *reinterpret_cast<const f32x4*>(lse_s + ib * 32 + 8 * q4 + 4 * g);
-        d4[q4] = *reinterpret_cast<const f32x4*>(delta_s + ib * 32 + 8 * q4 + 4 * g);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      // ---- P and dS for rows i = ib*32 + 8*q4 + 4g + e, column j = this lane's key
-      f32x16 p, ds;
-      if (masked) {   // wave-uniform: only tiles touching the end of the clip pay for masks
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = q4 * 4 + e;
-            const bool ok = jvalid && (q0 + ib * 32 + 8 * q4 + 4 * g + e < seg_b);
-            const float pv = ok ? fast_exp2(sacc[r] * scale_log2 - l4[q4][e]) : 0.f;
-            p[r] = pv;
-            ds[r] = pv * (dpacc[r] - d4[q4][e]);
-          }
-      } else {
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int r = q4 * 4 + e;
-            const float pv = fast_exp2(sacc[r] * scale_log2 - l4[q4][e]);
-            p[r] = pv;
-            ds[r] = pv * (dpacc[r] - d4[q4][e]);
-          }
-      }
-      bf16x8 pb[2], dsb8[2];
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        f32x8 a, b;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { a[e] = p[8 * s2 + e]; b[e] = ds[8 * s2 + e]; }
-        pb[s2] = to_bf16x8(a);
-        dsb8[s2] = to_bf16x8(b);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      // ---- dV^T += dO^T P ; dK^T += Q^T dS
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          dvacc[db] = mfma32(join_tr(dlo[s2][db], dhi[s2][db]), pb[s2], dvacc[db]);
-          dkacc[db] = mfma32(join_tr(qlo[s2][db], qhi[s2][db]), dsb8[s2], dkacc[db]);
-        }
-      __builtin_amdgcn_sched_barrier(0);
+    for (int ks = 0; ks < KS; ++ks) {
+      s_cur = mfma32(q0r[ks], kreg[ks], ks == 0 ? zero16 : s_cur);
+      dp_cur = mfma32(d0r[ks], vreg[ks], ks == 0 ? zero16 : dp_cur);
     }
-
-    wait_vmcnt<0>();   // the next tile has landed ...
-    __syncthreads();   // ... for every wave, and every wave is done reading this one
-  };
-  for (int t = 0; t < n_steps; t += 2) {
-    step_body(IntC<0>{}, t);
-    if (t + 1 < n_steps) step_body(IntC<1>{}, t + 1);
   }
+
+  // One pipeline iteration; POS = b % 8 fixes every LDS stage at compile time.
+  auto iteration = [&](auto pos_c) {
+    constexpr int POS = decltype(pos_c)::value;
+    constexpr int IB = POS & 1;                          // block b within its tile
+    constexpr int ST_CUR = (POS / 2) % kBwdRing;         // stage of block b's tile
+    constexpr int ST_ROW = ((POS + 2) / 2) % kBwdRing;   // stage of block b+2's tile
+    if constexpr (IB == 0) {
+      // Start of tile t = b/2: tile t+1 must have landed for every wave before anyone reads
+      // block b+2's rows, and every wave is past tile t-1, whose stage takes tile t+3.
+      wait_vmcnt<Cfg::kBatch>();
+      __syncthreads();
+      issue_tile((ST_CUR + 3) % kBwdRing);
+    }
+    const char* qt = smem + ST_CUR * SB;
+    const char* dot = qt + TB;
+    const float* lse_s = reinterpret_cast<const float*>(qt + 2 * TB);
+    const float* delta_s = lse_s + kBwdBQ;               // wave 1's statistics follow wave 0's
+
+    // ---- phase A: S(b+1), dP(b+1) | P(b) | statistics and transposed-operand reads of block b
+    f32x4 l4[4], d4[4];
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) l4[q4] = *reinterpret_cast<const f32x4*>(lse_s + IB * 32 + 8 * q4 + 4 * g);
+    s16x4 dlo[2][DB], dhi[2][DB], qlo[2][DB], qhi[2][DB];
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const int o0 = (tbase[0] ^ (db << 6)) + (IB * 32 + 16 * s2) * RB;
+        const int o1 = (tbase[1] ^ (db << 6)) + (IB * 32 + 16 * s2) * RB;
+        dlo[s2][db] = lds_read_tr(dot, o0);
+        dhi[s2][db] = lds_read_tr(dot, o1);
+        qlo[s2][db] = lds_read_tr(qt, o0);
+        qhi[s2][db] = lds_read_tr(qt, o1);
+      }
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) d4[q4] = *reinterpret_cast<const f32x4*>(delta_s + IB * 32 + 8 * q4 + 4 * g);
+    f32x16 s_next, dp_next;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      s_next = mfma32(qa_n[ks], kreg[ks], ks == 0 ? zero16 : s_next);
+      dp_next = mfma32(da_n[ks], vreg[ks], ks == 0 ? zero16 : dp_next);
+    }
+    // P for rows i = 8*q4 + 4g + e of the block, column j = this lane's key
+    f32x16 p;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) p[q4 * 4 + e] = fast_exp2(s_cur[q4 * 4 + e] * scale_log2 - l4[q4][e]);
+    bf16x8 pb[2];
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      f32x8 a;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) a[e] = p[8 * s2 + e];
+      pb[s2] = to_bf16x8(a);
+    }
+    __builtin_amdgcn_sched_group_barrier(kSgDsReadB, 4, 0);
+#pragma unroll
+    for (int i = 0; i < 2 * KS; ++i) {
+      __builtin_amdgcn_sched_group_barrier(kSgMfmaB, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(kSgDsReadB, (8 * DB + 4 + 2 * KS - 1) / (2 * KS), 0);
+      __builtin_amdgcn_sched_group_barrier(kSgValuB, 3, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- phase B: dV^T += dO(b)^T P(b) | dS(b) = P(b) o (dP(b) - Delta)
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        dvacc[db] = mfma32(join_tr(dlo[s2][db], dhi[s2][db]), pb[s2], dvacc[db]);
+    bf16x8 dsb[2];
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      f32x8 a;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int r = 8 * s2 + e;
+        a[e] = p[r] * (dp_cur[r] - d4[r >> 2][r & 3]);
+      }
+      dsb[s2] = to_bf16x8(a);
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * DB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(kSgMfmaB, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(kSgValuB, 5, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- phase C: dK^T += Q(b)^T dS(b) | row operands of block b+2
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+        dkacc[db] = mfma32(join_tr(qlo[s2][db], qhi[s2][db]), dsb[s2], dkacc[db]);
+    bf16x8 qa_2[KS], da_2[KS];
+    read_rows(ST_ROW, IB, qa_2, da_2);
+#pragma unroll
+    for (int i = 0; i < 2 * DB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(kSgMfmaB, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(kSgDsReadB, (2 * KS + 2 * DB - 1) / (2 * DB), 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    s_cur = s_next;
+    dp_cur = dp_next;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) { qa_n[ks] = qa_2[ks]; da_n[ks] = da_2[ks]; }
+  };
+
+  for (int b = 0; b < n_blocks; b += 8) {
+    iteration(IntC<0>{});
+    iteration(IntC<1>{});
+    if (b + 2 < n_blocks) { iteration(IntC<2>{}); iteration(IntC<3>{}); }
+    if (b + 4 < n_blocks) { iteration(IntC<4>{}); iteration(IntC<5>{}); }
+    if (b + 6 < n_blocks) { iteration(IntC<6>{}); iteration(IntC<7>{}); }
+  }
+  wait_vmcnt<0>();   // no load may still be writing LDS when the workgroup ends
 
   // ---- epilogue: dK (scaled) and dV for this lane's key row
   if (jvalid) {
@@ -521,13 +585,13 @@ template <int D>
 static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, const void* out,
                                const float* lse, const void* dout, const SegTable& segs, int total,
                                int n_heads, float scale, void* dq, void* dk, void* dv,
-                               float* delta, float* lse2, hipStream_t stream) {
+                               float* delta, float* lse2, float* sentinel, hipStream_t stream) {
   if (total == 0) return hipSuccess;
   {
     constexpr int kTokPerBlock = 256 / (D / 8);
     const int grid = (total + kTokPerBlock - 1) / kTokPerBlock;
     bwd_prepare_kernel<D><<<grid, 256, 0, stream>>>((const u32x4*)out, (const u32x4*)dout, lse,
-                                                    delta, lse2, total, n_heads);
+                                                    delta, lse2, sentinel, total, n_heads);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -546,7 +610,7 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
     if (e != hipSuccess) return e;
     kern<<<um.chunk * kNumXcd, kBwdWaves * 64, Cfg::kLdsBytes, stream>>>(
         (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse2, delta,
-        (__bf16*)dk, (__bf16*)dv, segs, um, total, n_heads, scale, scale * kLog2eB);
+        sentinel, (__bf16*)dk, (__bf16*)dv, segs, um, total, n_heads, scale, scale * kLog2eB);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
@@ -573,10 +637,10 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
 hipError_t launch_attn_bwd(const void* q, const void* k, const void* v, const void* out,
                            const float* lse, const void* dout, const SegTable& segs, int total,
                            int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
-                           float* delta, float* lse2, hipStream_t stream) {
+                           float* delta, float* lse2, float* sentinel, hipStream_t stream) {
   if (head_dim == 128)
-    return launch_bwd_d<128>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, stream);
-  return launch_bwd_d<64>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, stream);
+    return launch_bwd_d<128>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, sentinel, stream);
+  return launch_bwd_d<64>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, sentinel, stream);
 }
 
 }  // namespace vfm

@@ -129,7 +129,7 @@ int vfm_attn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_
 size_t vfm_attn_bwd_workspace_size(int total_tokens, int n_heads, int head_dim) {
   if (check_shape(0, total_tokens, n_heads, head_dim)) return 0;
   const size_t rows = (size_t)total_tokens * n_heads;
-  return 2 * align_up(rows * sizeof(float), 256);   // Delta and lse in log2 units
+  return 2 * align_up(rows * sizeof(float), 256) + 256;   // Delta, lse in log2 units, sentinels
 }
 
 int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
@@ -152,11 +152,13 @@ int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, c
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
     return VFM_ERR_WORKSPACE;
   float* delta = static_cast<float*>(workspace);
-  float* lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + need / 2);
+  const size_t part = (need - 256) / 2;
+  float* lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + part);
+  float* sentinel = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * part);
   SegTable segs;
   build_seg_table(cu_seqlens, n_seqs, &segs);
   hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_tokens, n_heads,
-                                      head_dim, scale, dq, dk, dv, delta, lse2,
+                                      head_dim, scale, dq, dk, dv, delta, lse2, sentinel,
                                       static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
 }

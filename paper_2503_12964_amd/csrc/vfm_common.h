@@ -195,6 +195,6 @@ hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, const Se
 hipError_t launch_attn_bwd(const void* q, const void* k, const void* v, const void* out,
                            const float* lse, const void* dout, const SegTable& segs, int total,
                            int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
-                           float* delta, float* lse2, hipStream_t stream);
+                           float* delta, float* lse2, float* sentinel, hipStream_t stream);
 
 }  // namespace vfm
