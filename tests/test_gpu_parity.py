@@ -116,6 +116,24 @@ def test_peaky_softmax_running_max():
     _assert_parity(wl, gpu, host, relative_maxabs=True)
 
 
+@pytest.mark.parametrize("ramp_to", [8.0, 40.0])
+def test_softmax_reference_moves_with_growing_scores(ramp_to):
+    # key magnitude grows along each clip, so later key units keep exceeding the forward
+    # kernel's softmax reference point: with ramp_to = 8 it has to move several times, with
+    # 40 the exponentials taken against the stale reference overflow to inf before it moves
+    import torch
+    wl = SMALL["ragged128"]
+    b = _binding()
+    inp = W.make_inputs(wl)
+    q, k, v, do = (U.to_device(inp[n]) for n in ("q", "k", "v", "dout"))
+    ramp = torch.linspace(1.0, ramp_to, wl.total_tokens, device=k.device)
+    k = (k.float() * ramp[:, None, None]).to(torch.bfloat16)
+    out, lse = b.vfm_attn_fwd(q, k, v, wl.cu_seqlens, wl.scale)
+    dq, dk, dv = b.vfm_attn_bwd(q, k, v, out, lse, do, wl.cu_seqlens, wl.scale)
+    host = tuple(U.to_f64(t) for t in (q, k, v, do))
+    _assert_parity(wl, (out, lse, dq, dk, dv), host, relative_maxabs=True)
+
+
 def test_forward_is_bitwise_reproducible():
     wl = SMALL["ragged128"]
     b = _binding()
