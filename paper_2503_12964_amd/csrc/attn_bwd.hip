@@ -366,26 +366,25 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 }
 
 // ---------------------------------------------------------------- dQ
-constexpr int kDqWaves = 4;
 constexpr int kDqBC = 64;   // key/value rows per LDS tile
 
-template <int D, int NI>
+template <int D, int NI, int W>
 struct DqCfg {
-  static constexpr int kBR = kDqWaves * NI * 32;        // query rows per workgroup
+  static constexpr int kBR = W * NI * 32;        // query rows per workgroup
   static constexpr int kTileBytes = kDqBC * D * 2;      // one K or V tile
   static constexpr int kLdsBytes = 4 * kTileBytes;      // K, V x 2 stages
   static constexpr int kChunksPerRow = D / 8;
-  static constexpr int kChunksPerThread = kDqBC * kChunksPerRow / (kDqWaves * 64);
+  static constexpr int kChunksPerThread = kDqBC * kChunksPerRow / (W * 64);
 };
 
-template <int D, int NI>
-__global__ __launch_bounds__(kDqWaves * 64, (NI == 1 ? 2 : 1))
+template <int D, int NI, int W>
+__global__ __launch_bounds__(W * 64, (NI == 1 ? 2 : 1))
 void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                         const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
                         const float* __restrict__ lse2g, const float* __restrict__ delta,
                         __bf16* __restrict__ dq, const SegTable segs, const UnitMap um,
                         int total, int n_heads, float scale, float scale_log2) {
-  using Cfg = DqCfg<D, NI>;
+  using Cfg = DqCfg<D, NI, W>;
   constexpr int KS = D / 16;
   constexpr int DB = D / 32;
   constexpr int JB = kDqBC / 32;
@@ -433,7 +432,7 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
   uint32_t st_rowoff[CPT], st_colb[CPT];
 #pragma unroll
   for (int x = 0; x < CPT; ++x) {
-    const int p = (x * kDqWaves + wave) * 64 + lane;
+    const int p = (x * W + wave) * 64 + lane;
     const int r = p / Cfg::kChunksPerRow;
     st_rowoff[x] = (uint32_t)(seg_a + r) * row_bytes;
     st_colb[x] = (uint32_t)(((p % Cfg::kChunksPerRow) ^ swz<D>(r)) * 16);
@@ -443,7 +442,7 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
 #pragma unroll
     for (int x = 0; x < CPT; ++x) {
       const uint32_t off = min(st_rowoff[x], last_row_off) + st_colb[x];
-      const uint32_t dst = wave_lds + stage * 2 * Cfg::kTileBytes + x * kDqWaves * 1024;
+      const uint32_t dst = wave_lds + stage * 2 * Cfg::kTileBytes + x * W * 1024;
       lds_dma16(kbase, off, dst);
       lds_dma16(vbase, off, dst + Cfg::kTileBytes);
       st_rowoff[x] += kDqBC * row_bytes;
@@ -616,18 +615,19 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
   }
   {
     constexpr int NI = 1;
-    using Cfg = DqCfg<D, NI>;
+    constexpr int W = 8;   // 256 query rows share each staged K/V tile
+    using Cfg = DqCfg<D, NI, W>;
     int tiles = 0;
     for (int s = 0; s < segs.n; ++s) tiles += (segs.len[s] + Cfg::kBR - 1) / Cfg::kBR;
     UnitMap um;
     um.tiles_per_head = tiles;
     um.n_units = tiles * n_heads;
     um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
-    auto kern = attn_bwd_dq_kernel<D, NI>;
+    auto kern = attn_bwd_dq_kernel<D, NI, W>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
-    kern<<<um.chunk * kNumXcd, kDqWaves * 64, Cfg::kLdsBytes, stream>>>(
+    kern<<<um.chunk * kNumXcd, W * 64, Cfg::kLdsBytes, stream>>>(
         (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse2, delta,
         (__bf16*)dq, segs, um, total, n_heads, scale, scale * kLog2eB);
     return hipGetLastError();
