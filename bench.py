@@ -10,12 +10,19 @@ workload is the 720p-class 121-frame latent (T,H,W = 16,44,80 -> 56,320 tokens,
 
 FLOP convention (algorithmic, block-diagonal pairs only): forward 4*D and
 backward 10*D flops per (query, key) pair per head.
+
+Besides the published matrix peak the line carries a ceiling measured in the same run: a
+loop of nothing but bf16 MFMA instructions, sustained for seconds, with constant and with
+random operands (paper_2503_12964_amd/mfma_ceiling, a child process started before this
+process touches the GPU).  With random operands the chip lowers its clock to stay inside
+its power limit, so that figure is what a kernel working on real data can approach.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -30,7 +37,21 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel from `rocprofv3 --pmc` (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"C4": 32.97e9}
+MEASURED_TRAFFIC_BYTES = {"C4": 27.17e9}
+
+
+def _mfma_ceiling(seconds: float = 1.5):
+    """Run the standalone MFMA-only loop; None if it has not been built or fails."""
+    exe = os.path.join(ROOT, "paper_2503_12964_amd", "mfma_ceiling")
+    if not os.path.exists(exe):
+        return None
+    if any(name.startswith("ROCPROF") for name in os.environ):
+        return None       # under the profiler this process already holds the GPU: start no child
+    try:
+        res = subprocess.run([exe, str(seconds)], capture_output=True, text=True, timeout=60)
+        return json.loads(res.stdout.strip().splitlines()[-1]) if res.returncode == 0 else None
+    except Exception:
+        return None
 
 
 def _device_tensors(wl):
@@ -79,6 +100,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-mfma-ceiling", action="store_true",
+                    help="skip the MFMA-only ceiling measurement (about 3 s of GPU time)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy (the known-size kernel that scales "
                          "the FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -87,6 +110,9 @@ def main() -> int:
         print("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); "
               "use --gpus 1", file=sys.stderr)
         return 2
+
+    # child process, run to completion before this process initialises the GPU
+    ceiling = None if (args.no_mfma_ceiling or args.calibrate_copy) else _mfma_ceiling()
 
     import torch
     from paper_2503_12964_amd import binding as B
@@ -139,6 +165,7 @@ def main() -> int:
     ms_rope = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
     ms_fwd = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
     ms_bwd = float(np.mean([e[2].elapsed_time(e[3]) for e in events])) if wl.backward else 0.0
+    ms_each = [e[0].elapsed_time(e[3]) for e in events]
 
     f_fwd = wl.flops(backward=False)
     f_all = wl.flops()
@@ -167,12 +194,23 @@ def main() -> int:
                       "fwd_tflops": f_fwd / (ms_fwd * 1e-3) / 1e12,
                       "bwd_tflops": (f_bwd / (ms_bwd * 1e-3) / 1e12) if wl.backward else None,
                       "attn_only_tflops": f_all / ((ms_fwd + ms_bwd) * 1e-3) / 1e12,
+                      # recompute not credited: 4*D forward + 8*D backward flops per pair per head
+                      "attn_only_model_tflops": (f_fwd + 0.8 * f_bwd) / ((ms_fwd + ms_bwd) * 1e-3) / 1e12
+                                                if wl.backward else None,
+                      "step_ms_median": float(np.median(ms_each)), "step_ms_min": float(np.min(ms_each)),
                       "rope_gbs": rope_bytes / (ms_rope * 1e-3) / 1e9,
                       "rope_frac_hbm_peak": rope_bytes / (ms_rope * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "ms": dom_ms, "note": dom_note},
     }
+    if ceiling:
+        rnd = ceiling["random_operands_tflops"]
+        result["roofline"]["mfma_only_measured"] = {
+            **ceiling, "unit": "TFLOP/s",
+            "frac_of_random_operand_ceiling": achieved / rnd if rnd > 0 else None,
+            "note": "loop of MFMA instructions only, sustained; with random operands the clock drops "
+                    "under the power limit, which also bounds kernels working on real data"}
     del q, k, v, do, out, dq, dk, dv, ws, t
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:

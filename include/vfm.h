@@ -103,8 +103,9 @@ VFM_API int vfm_attn_fwd(const void* q, const void* k, const void* v,
 /*
  * Bytes of device workspace vfm_attn_bwd needs for these sizes (0 if the sizes
  * are invalid).  The workspace holds Delta_i = sum_d dout[i,h,d] out[i,h,d] and
- * lse * log2(e) (two fp32 [n_heads, total_tokens] arrays); its contents need not
- * be initialised and are garbage afterwards.
+ * lse * log2(e) (two fp32 [n_heads, total_tokens] arrays, each padded to 256
+ * bytes) followed by 256 bytes of constants the kernels read for rows past a
+ * clip's end; its contents need not be initialised and are garbage afterwards.
  */
 VFM_API size_t vfm_attn_bwd_workspace_size(int total_tokens, int n_heads, int head_dim);
 

@@ -9,6 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libvfm.so")
+CEILING_PATH = os.path.join(HERE, "mfma_ceiling")   # standalone matrix-pipe ceiling measurement
 SOURCES = ["vfm_api.hip", "rope3d.hip", "attn_fwd.hip", "attn_bwd.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -48,5 +49,19 @@ def build_lib(verbose: bool = True, csrc: str = CSRC, out: str = LIB_PATH) -> st
     return out
 
 
+def build_ceiling_tool(verbose: bool = True, out: str = CEILING_PATH) -> str:
+    """Compile the standalone MFMA-only ceiling measurement (csrc/mfma_ceiling.hip)."""
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Wno-unused-command-line-argument",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           os.path.join(CSRC, "mfma_ceiling.hip"), "-o", out]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed on mfma_ceiling.hip:\n" + res.stderr)
+    if verbose:
+        print(f"built {out}")
+    return out
+
+
 if __name__ == "__main__":
     build_lib()
+    build_ceiling_tool()
