@@ -27,11 +27,17 @@ What the paper fixes, and where:
   * Section 5.2 and Table 1: multi-head attention, one K/V head per Q head,
     head_dim = hidden / heads = 128.
 
+  * Section 4.5.1 (paragraph on QK normalisation): Q and K are normalised
+    per attention head (not over the whole hidden dimension) right before
+    the dot-product attention.
+
 What the paper does not fix (readings taken; all are restated in the design
 notes of the repository): the rotary embedding itself (theta, per-axis
 split, adjacent-pair convention, per-axis frequency exponent, integer grid
-positions starting at 0), the softmax scale (an argument), and natural-log
-units for the log-sum-exp.
+positions starting at 0), the softmax scale (an argument), natural-log
+units for the log-sum-exp, and the kind of per-head normalisation (taken as
+root-mean-square normalisation with a learned gain of head_dim entries shared
+by all heads, and an epsilon inside the square root).
 
 Pins (tests/test_oracle_*.py): single-token segment returns V; Q = 0 returns
 the segment mean of V and lse = ln N; packed equals per-clip; RoPE keeps
@@ -48,6 +54,8 @@ import numpy as np
 __all__ = [
     "token_coords",
     "rope3d",
+    "qknorm_rope3d",
+    "qknorm_rope3d_bwd",
     "attn_fwd",
     "attn_bwd",
     "attn_fwd_rows",
@@ -134,6 +142,51 @@ def rope3d(x, thw, cu_seqlens, dims, theta: float = 10000.0,
         y[:, :, start + 1:start + d_a:2] = x0 * s + x1 * c
         start += d_a
     return y
+
+
+def _rstd(x: np.ndarray, eps: float) -> np.ndarray:
+    """1 / sqrt(mean_d x_d^2 + eps) per (token, head), shape [total, heads, 1]."""
+    return 1.0 / np.sqrt(np.mean(x * x, axis=2, keepdims=True) + float(eps))
+
+
+def qknorm_rope3d(x, gain, eps: float, thw, cu_seqlens, dims, theta: float = 10000.0) -> np.ndarray:
+    """Per-head normalisation of x[total, heads, head_dim] followed by 3D RoPE.
+
+    Section 4.5.1 normalises Q and K per head before attention; the reading
+    taken is RMS normalisation with a learned gain g[head_dim]:
+        r   = 1 / sqrt(mean_d x_d^2 + eps)          per (token, head)
+        z_d = x_d * r * g_d
+        y   = rope3d(z)
+    Returns y (fp64).
+    """
+    x = _as_f64(x)
+    g = np.asarray(gain, dtype=np.float64)
+    if g.shape != (x.shape[2],):
+        raise ValueError("gain must have head_dim entries")
+    z = x * _rstd(x, eps) * g[None, None, :]
+    return rope3d(z, thw, cu_seqlens, dims, theta)
+
+
+def qknorm_rope3d_bwd(x, gain, eps: float, dy, thw, cu_seqlens, dims, theta: float = 10000.0):
+    """Gradients of qknorm_rope3d with respect to x and the gain, given dy.
+
+    With n = x r (the normalised vector), z = n g and y = R z (R the rotation,
+    orthogonal):
+        dz     = R^T dy                               (rotation by the negated angle)
+        dgain  = sum over (token, head) of dz * n
+        dn     = dz * g
+        dx     = r * (dn - n * mean_d(dn_d n_d))      (Jacobian of x -> x r)
+    Returns dx [total, heads, head_dim] and dgain [head_dim], both fp64.
+    """
+    x, dy = _as_f64(x), _as_f64(dy)
+    g = np.asarray(gain, dtype=np.float64)
+    r = _rstd(x, eps)
+    n = x * r
+    dz = rope3d(dy, thw, cu_seqlens, dims, theta, inverse=True)
+    dgain = np.sum(dz * n, axis=(0, 1))
+    dn = dz * g[None, None, :]
+    dx = r * (dn - n * np.mean(dn * n, axis=2, keepdims=True))
+    return dx, dgain
 
 
 def _softmax_rows(S: np.ndarray):
