@@ -211,6 +211,33 @@ def main() -> int:
             "frac_of_random_operand_ceiling": achieved / rnd if rnd > 0 else None,
             "note": "loop of MFMA instructions only, sustained; with random operands the clock drops "
                     "under the power limit, which also bounds kernels working on real data"}
+    # Not part of the timed step: the fused per-head normalisation + RoPE (the step upstream of
+    # vfm_rope3d in the paper's model, Section 4.5.1), forward and backward, on the same shapes.
+    gain_d = torch.from_numpy(W.norm_gain(wl)).cuda()
+    dgain = torch.empty(wl.head_dim, dtype=torch.float32, device="cuda")
+
+    def _timed(fn, n=10):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    elems = wl.total_tokens * wl.n_heads * wl.head_dim
+    ms_nf = _timed(lambda: B.vfm_qknorm_rope3d(v, gain_d, 1e-6, thw, cu, wl.rope_dims, wl.theta, y=dq))
+    ms_nb = _timed(lambda: B.vfm_qknorm_rope3d_bwd(v, gain_d, 1e-6, do, thw, cu, wl.rope_dims, wl.theta,
+                                                   dx=dq, dgain=dgain))
+    result["qknorm_rope3d"] = {
+        "note": "fused per-head RMS norm + 3D RoPE, one tensor; outside the timed step; HBM-bound: "
+                "forward 4 B/element (2 read + 2 written), backward 6 B/element (x and dy read, dx written)",
+        "fwd_ms": ms_nf, "fwd_gbs": 4 * elems / (ms_nf * 1e-3) / 1e9,
+        "fwd_frac_hbm_peak": 4 * elems / (ms_nf * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "bwd_ms": ms_nb, "bwd_gbs": 6 * elems / (ms_nb * 1e-3) / 1e9,
+        "bwd_frac_hbm_peak": 6 * elems / (ms_nb * 1e-3) / 1e9 / HBM_PEAK_GBS}
     del q, k, v, do, out, dq, dk, dv, ws, t
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:

@@ -86,6 +86,45 @@ VFM_API int vfm_rope3d(void* x, const int32_t* thw, const int32_t* cu_seqlens, i
                vfm_dtype dt, void* hip_stream);
 
 /*
+ * Per-head normalisation of q or k fused with the 3D rotary embedding above, in one
+ * pass over memory.  Section 4.5.1 normalises Q and K per attention head right
+ * before attention; it is taken here as root-mean-square normalisation with a
+ * learned gain shared by all heads.  For every token and head:
+ *     r   = 1 / sqrt(mean_d x[d]^2 + eps)
+ *     z_d = x[d] * r * gain[d]
+ *     y   = rotation of z exactly as in vfm_rope3d
+ * x, y: bf16 [total_tokens, n_heads, head_dim], y may be the same buffer as x
+ * (in place); gain: device fp32 [head_dim]; eps >= 0.  Sums, r and the rotation
+ * are fp32, y is rounded once to bf16.
+ * Errors: NULL, SHAPE, CU_SEQLENS, THW, SPLIT, DTYPE, ALIGN, LAUNCH.
+ */
+VFM_API int vfm_qknorm_rope3d(const void* x, const float* gain, float eps, void* y,
+                      const int32_t* thw, const int32_t* cu_seqlens, int n_seqs,
+                      int total_tokens, int n_heads, int head_dim,
+                      int dim_t, int dim_h, int dim_w, float theta,
+                      vfm_dtype dt, void* hip_stream);
+
+/*
+ * Gradients of vfm_qknorm_rope3d.  With n = x r, given dy:
+ *     dz      = transpose rotation of dy
+ *     dgain_d = sum over tokens and heads of dz_d n_d
+ *     dn      = dz * gain
+ *     dx      = r * (dn - n * mean_d(dn_d n_d))
+ * x is the forward's input (r is recomputed from it, nothing is saved by the
+ * forward).  dx: bf16, fully overwritten; it may be the same buffer as dy, never
+ * the same as x (SHAPE).  dgain: device fp32 [head_dim], overwritten (zeroed by
+ * this call, then accumulated with fp32 atomics, so its last bits may differ
+ * from run to run; dx is bitwise reproducible).
+ * Errors: NULL, SHAPE, CU_SEQLENS, THW, SPLIT, DTYPE, ALIGN, LAUNCH.
+ */
+VFM_API int vfm_qknorm_rope3d_bwd(const void* x, const float* gain, float eps, const void* dy,
+                          void* dx, float* dgain,
+                          const int32_t* thw, const int32_t* cu_seqlens, int n_seqs,
+                          int total_tokens, int n_heads, int head_dim,
+                          int dim_t, int dim_h, int dim_w, float theta,
+                          vfm_dtype dt, void* hip_stream);
+
+/*
  * Attention forward.  For every clip [a,b) and head h:
  *     S_ij  = scale * sum_d q[i,h,d] k[j,h,d]          i, j in [a,b)
  *     out_i = sum_j softmax_j(S_ij) v[j,h,:]

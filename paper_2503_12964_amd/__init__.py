@@ -6,4 +6,5 @@ Nothing is loaded at import time; the first call into `binding` loads
 libvfm.so and raises if it has not been built.
 """
 from .binding import (VfmError, load_library, strerror, vfm_attn_bwd,  # noqa: F401
-                      vfm_attn_bwd_workspace_size, vfm_attn_fwd, vfm_rope3d)
+                      vfm_attn_bwd_workspace_size, vfm_attn_fwd, vfm_qknorm_rope3d,
+                      vfm_qknorm_rope3d_bwd, vfm_rope3d)

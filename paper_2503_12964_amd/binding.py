@@ -21,7 +21,7 @@ VFM_BF16 = 0
 VFM_F32 = 1
 VFM_MAX_SEQS = 256
 
-EXPORTS = ("vfm_rope3d", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_strerror")
+EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_strerror")
 
 _lib = None
 
@@ -47,6 +47,13 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.vfm_rope3d.restype = c_int
     lib.vfm_rope3d.argtypes = [c_void_p, p_i32, p_i32, c_int, c_int, c_int, c_int, c_int, c_int, c_int,
                                c_float, c_int, c_int, c_void_p]
+    lib.vfm_qknorm_rope3d.restype = c_int
+    lib.vfm_qknorm_rope3d.argtypes = [c_void_p, c_void_p, c_float, c_void_p, p_i32, p_i32, c_int, c_int, c_int,
+                                      c_int, c_int, c_int, c_int, c_float, c_int, c_void_p]
+    lib.vfm_qknorm_rope3d_bwd.restype = c_int
+    lib.vfm_qknorm_rope3d_bwd.argtypes = [c_void_p, c_void_p, c_float, c_void_p, c_void_p, c_void_p, p_i32, p_i32,
+                                          c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_float, c_int,
+                                          c_void_p]
     lib.vfm_attn_fwd.restype = c_int
     lib.vfm_attn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, p_i32, c_int, c_int, c_int, c_int, c_float,
                                  c_void_p, c_void_p, c_int, c_void_p]
@@ -113,6 +120,38 @@ def vfm_rope3d(x, thw, cu_seqlens, dims: Sequence[int], theta: float = 10000.0,
                           int(hd), int(dims[0]), int(dims[1]), int(dims[2]), float(theta), int(bool(inverse)),
                           _dtype_code(x), _stream_ptr(stream)))
     return x
+
+
+def vfm_qknorm_rope3d(x, gain, eps: float, thw, cu_seqlens, dims: Sequence[int], theta: float = 10000.0,
+                      y=None, stream=None):
+    """y = RoPE3D(gain * x / sqrt(mean_d x^2 + eps)) per (token, head); y=None works in place on x."""
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    g = _host_i32(thw).reshape(-1)
+    total, heads, hd = x.shape
+    y = x if y is None else y
+    _check(lib.vfm_qknorm_rope3d(_dev(x, "x"), _dev(gain, "gain"), float(eps), _dev(y, "y"), _i32_ptr(g),
+                                 _i32_ptr(cu), int(cu.size - 1), int(total), int(heads), int(hd),
+                                 int(dims[0]), int(dims[1]), int(dims[2]), float(theta), _dtype_code(x),
+                                 _stream_ptr(stream)))
+    return y
+
+
+def vfm_qknorm_rope3d_bwd(x, gain, eps: float, dy, thw, cu_seqlens, dims: Sequence[int],
+                          theta: float = 10000.0, dx=None, dgain=None, stream=None) -> Tuple:
+    """dx (bf16, shape of x; may be dy itself) and dgain (fp32 [head_dim]) given the forward's input x."""
+    import torch
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    g = _host_i32(thw).reshape(-1)
+    total, heads, hd = x.shape
+    dx = torch.empty_like(x) if dx is None else dx
+    dgain = torch.empty(hd, dtype=torch.float32, device=x.device) if dgain is None else dgain
+    _check(lib.vfm_qknorm_rope3d_bwd(_dev(x, "x"), _dev(gain, "gain"), float(eps), _dev(dy, "dy"), _dev(dx, "dx"),
+                                     _dev(dgain, "dgain"), _i32_ptr(g), _i32_ptr(cu), int(cu.size - 1),
+                                     int(total), int(heads), int(hd), int(dims[0]), int(dims[1]), int(dims[2]),
+                                     float(theta), _dtype_code(x), _stream_ptr(stream)))
+    return dx, dgain
 
 
 def vfm_attn_fwd(q, k, v, cu_seqlens, scale: float, out=None, lse=None, stream=None) -> Tuple:

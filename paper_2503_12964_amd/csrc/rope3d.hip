@@ -6,14 +6,9 @@
 // computed once (angle reduced in fp64, then sincosf) and reused for all
 // heads.  A wavefront therefore moves 256-byte contiguous head rows; every byte
 // of x is read once and written once.
-#include "vfm_common.h"
+#include "rope_common.h"
 
 namespace vfm {
-
-struct RopeFreq {
-  double inv_freq[64];    // per pair index p = element/2: theta^(-2i/d_axis)
-  unsigned char axis[64]; // 0 = t, 1 = h, 2 = w
-};
 
 template <int D>
 __global__ __launch_bounds__(256) void rope3d_kernel(u32x4* __restrict__ x, const RopeTable tab,
@@ -25,36 +20,8 @@ __global__ __launch_bounds__(256) void rope3d_kernel(u32x4* __restrict__ x, cons
   const int chunk = threadIdx.x % kLanesPerTok;
   if (tok >= total) return;
 
-  // clip of this token: last s with cu[s] <= tok (skips empty clips)
-  int lo = 0, hi = tab.n;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (tab.cu[mid] <= tok) lo = mid; else hi = mid;
-  }
-  const int r = tok - tab.cu[lo];
-  const int hw = tab.hw[lo], w = tab.w[lo];
-  int pos[3];
-  pos[0] = r / hw;
-  const int rem = r - pos[0] * hw;
-  pos[1] = rem / w;
-  pos[2] = rem - pos[1] * w;
-
   float cs[4], sn[4];
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const int p = chunk * 4 + e;
-    const int ax = fr.axis[p];
-    // The angle is formed and reduced to [-pi, pi] in fp64 (a handful of operations per
-    // token, reused for every head), so the rotation stays accurate to fp32 rounding
-    // however large the grid position is.
-    const double pa = (double)(ax == 0 ? pos[0] : (ax == 1 ? pos[1] : pos[2]));
-    double ang = pa * fr.inv_freq[p];
-    ang -= 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
-    float s, c;
-    sincosf((float)ang, &s, &c);
-    cs[e] = c;
-    sn[e] = inverse ? -s : s;
-  }
+  rope_cos_sin(tab, fr, tok, chunk, inverse, cs, sn);
 
   u32x4* row = x + ((size_t)tok * n_heads) * kLanesPerTok + chunk;
   constexpr int kUnroll = 4;
@@ -97,16 +64,7 @@ __global__ __launch_bounds__(256) void rope3d_kernel(u32x4* __restrict__ x, cons
 hipError_t launch_rope3d(void* x, const RopeTable& tab, int total, int n_heads, int head_dim,
                          int dim_t, int dim_h, int dim_w, float theta, int inverse,
                          hipStream_t stream) {
-  RopeFreq fr;
-  const int dims[3] = {dim_t, dim_h, dim_w};
-  int p = 0;
-  for (int ax = 0; ax < 3; ++ax) {
-    for (int i = 0; i < dims[ax] / 2; ++i, ++p) {
-      fr.inv_freq[p] = pow((double)theta, -2.0 * (double)i / (double)dims[ax]);
-      fr.axis[p] = (unsigned char)ax;
-    }
-  }
-  for (; p < 64; ++p) { fr.inv_freq[p] = 0.0; fr.axis[p] = 0; }
+  const RopeFreq fr = make_rope_freq(dim_t, dim_h, dim_w, theta);
   if (total == 0) return hipSuccess;
   if (head_dim == 128) {
     const int grid = (total + 15) / 16;

@@ -50,6 +50,38 @@ void build_seg_table(const int32_t* cu, int n_seqs, SegTable* t) {
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// Shared by the RoPE entry points: sizes, split, theta, cu_seqlens and the per-clip grids;
+// fills the clip table the kernels take by value.
+int check_rope_args(const int32_t* thw, const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                    int n_heads, int head_dim, int dim_t, int dim_h, int dim_w, float theta,
+                    vfm_dtype dt, RopeTable* tab) {
+  if (dt != VFM_BF16) return VFM_ERR_DTYPE;
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  if (st) return st;
+  if (!(theta > 0.f) || !isfinite(theta)) return VFM_ERR_SHAPE;
+  if (dim_t < 0 || dim_h < 0 || dim_w < 0 || (dim_t | dim_h | dim_w) & 1 ||
+      dim_t + dim_h + dim_w != head_dim)
+    return VFM_ERR_SPLIT;
+  st = check_cu(cu_seqlens, n_seqs, total_tokens);
+  if (st) return st;
+  tab->n = n_seqs;
+  for (int s = 0; s < n_seqs; ++s) {
+    const long long T = thw[3 * s], H = thw[3 * s + 1], W = thw[3 * s + 2];
+    const int len = cu_seqlens[s + 1] - cu_seqlens[s];
+    tab->cu[s] = cu_seqlens[s];
+    if (len == 0 && T * H * W == 0 && T >= 0 && H >= 0 && W >= 0) {  // empty clip
+      tab->hw[s] = 1; tab->w[s] = 1;
+      continue;
+    }
+    if (T <= 0 || H <= 0 || W <= 0 || T * H * W != len) return VFM_ERR_THW;
+    tab->hw[s] = (int)(H * W);
+    tab->w[s] = (int)W;
+  }
+  tab->cu[n_seqs] = total_tokens;
+  for (int s = n_seqs; s < VFM_MAX_SEQS; ++s) { tab->cu[s + 1] = total_tokens; tab->hw[s] = 1; tab->w[s] = 1; }
+  return VFM_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -58,7 +90,7 @@ const char* vfm_strerror(int status) {
   switch (status) {
     case VFM_OK: return "ok";
     case VFM_ERR_NULL: return "a required pointer is NULL";
-    case VFM_ERR_SHAPE: return "total_tokens, n_heads, head_dim (64 or 128), n_seqs (<= 256) or scale (> 0, finite) out of range";
+    case VFM_ERR_SHAPE: return "total_tokens, n_heads, head_dim (64 or 128), n_seqs (<= 256), scale or theta (> 0, finite) or eps (>= 0) out of range, or dx aliases x";
     case VFM_ERR_CU_SEQLENS: return "cu_seqlens must start at 0, be non-decreasing and end at total_tokens";
     case VFM_ERR_THW: return "each clip needs positive T, H, W with T*H*W equal to its length";
     case VFM_ERR_SPLIT: return "dim_t + dim_h + dim_w must equal head_dim, each part even and >= 0";
@@ -74,35 +106,52 @@ int vfm_rope3d(void* x, const int32_t* thw, const int32_t* cu_seqlens, int n_seq
                int total_tokens, int n_heads, int head_dim, int dim_t, int dim_h, int dim_w,
                float theta, int inverse, vfm_dtype dt, void* hip_stream) {
   if (!x || !thw || !cu_seqlens) return VFM_ERR_NULL;
-  if (dt != VFM_BF16) return VFM_ERR_DTYPE;
-  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
-  if (st) return st;
-  if (!(theta > 0.f) || !isfinite(theta)) return VFM_ERR_SHAPE;
-  if (dim_t < 0 || dim_h < 0 || dim_w < 0 || (dim_t | dim_h | dim_w) & 1 ||
-      dim_t + dim_h + dim_w != head_dim)
-    return VFM_ERR_SPLIT;
-  st = check_cu(cu_seqlens, n_seqs, total_tokens);
-  if (st) return st;
   RopeTable tab;
-  tab.n = n_seqs;
-  for (int s = 0; s < n_seqs; ++s) {
-    const long long T = thw[3 * s], H = thw[3 * s + 1], W = thw[3 * s + 2];
-    const int len = cu_seqlens[s + 1] - cu_seqlens[s];
-    if (len == 0 && T * H * W == 0 && T >= 0 && H >= 0 && W >= 0) {  // empty clip
-      tab.cu[s] = cu_seqlens[s]; tab.hw[s] = 1; tab.w[s] = 1;
-      continue;
-    }
-    if (T <= 0 || H <= 0 || W <= 0 || T * H * W != len) return VFM_ERR_THW;
-    tab.cu[s] = cu_seqlens[s];
-    tab.hw[s] = (int)(H * W);
-    tab.w[s] = (int)W;
-  }
-  tab.cu[n_seqs] = total_tokens;
-  for (int s = n_seqs; s < VFM_MAX_SEQS; ++s) { tab.cu[s + 1] = total_tokens; tab.hw[s] = 1; tab.w[s] = 1; }
+  int st = check_rope_args(thw, cu_seqlens, n_seqs, total_tokens, n_heads, head_dim, dim_t, dim_h,
+                           dim_w, theta, dt, &tab);
+  if (st) return st;
   if (!aligned16(x)) return VFM_ERR_ALIGN;
   if (total_tokens == 0) return VFM_OK;
   hipError_t e = vfm::launch_rope3d(x, tab, total_tokens, n_heads, head_dim, dim_t, dim_h, dim_w,
                                     theta, inverse, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+}
+
+int vfm_qknorm_rope3d(const void* x, const float* gain, float eps, void* y, const int32_t* thw,
+                      const int32_t* cu_seqlens, int n_seqs, int total_tokens, int n_heads,
+                      int head_dim, int dim_t, int dim_h, int dim_w, float theta, vfm_dtype dt,
+                      void* hip_stream) {
+  if (!x || !gain || !y || !thw || !cu_seqlens) return VFM_ERR_NULL;
+  RopeTable tab;
+  int st = check_rope_args(thw, cu_seqlens, n_seqs, total_tokens, n_heads, head_dim, dim_t, dim_h,
+                           dim_w, theta, dt, &tab);
+  if (st) return st;
+  if (!(eps >= 0.f) || !isfinite(eps)) return VFM_ERR_SHAPE;
+  if (!aligned16(x) || !aligned16(y) || (reinterpret_cast<uintptr_t>(gain) & 3u)) return VFM_ERR_ALIGN;
+  if (total_tokens == 0) return VFM_OK;
+  hipError_t e = vfm::launch_qknorm_rope3d(x, y, gain, eps, tab, total_tokens, n_heads, head_dim,
+                                           dim_t, dim_h, dim_w, theta,
+                                           static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+}
+
+int vfm_qknorm_rope3d_bwd(const void* x, const float* gain, float eps, const void* dy, void* dx,
+                          float* dgain, const int32_t* thw, const int32_t* cu_seqlens, int n_seqs,
+                          int total_tokens, int n_heads, int head_dim, int dim_t, int dim_h,
+                          int dim_w, float theta, vfm_dtype dt, void* hip_stream) {
+  if (!x || !gain || !dy || !dx || !dgain || !thw || !cu_seqlens) return VFM_ERR_NULL;
+  RopeTable tab;
+  int st = check_rope_args(thw, cu_seqlens, n_seqs, total_tokens, n_heads, head_dim, dim_t, dim_h,
+                           dim_w, theta, dt, &tab);
+  if (st) return st;
+  if (!(eps >= 0.f) || !isfinite(eps)) return VFM_ERR_SHAPE;
+  if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) ||
+      ((reinterpret_cast<uintptr_t>(gain) | reinterpret_cast<uintptr_t>(dgain)) & 3u))
+    return VFM_ERR_ALIGN;
+  if (dx == x) return VFM_ERR_SHAPE;   // dx may overwrite dy, never x
+  hipError_t e = vfm::launch_qknorm_rope3d_bwd(x, dy, dx, gain, eps, dgain, tab, total_tokens,
+                                               n_heads, head_dim, dim_t, dim_h, dim_w, theta,
+                                               static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
 }
 

@@ -188,6 +188,15 @@ hipError_t launch_rope3d(void* x, const RopeTable& tab, int total, int n_heads, 
                          int dim_t, int dim_h, int dim_w, float theta, int inverse,
                          hipStream_t stream);
 
+hipError_t launch_qknorm_rope3d(const void* x, void* y, const float* gain, float eps,
+                                const RopeTable& tab, int total, int n_heads, int head_dim,
+                                int dim_t, int dim_h, int dim_w, float theta, hipStream_t stream);
+
+hipError_t launch_qknorm_rope3d_bwd(const void* x, const void* dy, void* dx, const float* gain,
+                                    float eps, float* dgain, const RopeTable& tab, int total,
+                                    int n_heads, int head_dim, int dim_t, int dim_h, int dim_w,
+                                    float theta, hipStream_t stream);
+
 hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, const SegTable& segs,
                            int total, int n_heads, int head_dim, float scale, void* out,
                            float* lse, hipStream_t stream);

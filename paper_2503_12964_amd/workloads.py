@@ -18,7 +18,7 @@ from typing import Sequence, Tuple
 
 import numpy as np
 
-TENSOR_IDS = {"q": 0, "k": 1, "v": 2, "dout": 3}
+TENSOR_IDS = {"q": 0, "k": 1, "v": 2, "dout": 3, "gain": 4, "dy": 5}
 
 
 @dataclass(frozen=True)
@@ -99,6 +99,11 @@ def normal_f32(seed: int, tensor: str, shape: Sequence[int], gain: float = 1.0) 
     if gain != 1.0:
         x *= np.float32(gain)
     return x
+
+
+def norm_gain(wl: Workload) -> np.ndarray:
+    """Learned gain of the per-head normalisation, fp32 [head_dim]: 1 + 0.25 N(0,1), seeded."""
+    return (1.0 + normal_f32(wl.seed, "gain", (wl.head_dim,), 0.25)).astype(np.float32)
 
 
 def make_inputs(wl: Workload, heads: int | None = None, gain_qk: float = 1.0,

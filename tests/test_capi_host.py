@@ -37,6 +37,7 @@ def test_strerror_texts(lib):
 
 FAKE = ctypes.c_void_p(0x10000)      # never dereferenced: validation precedes any launch
 ODD = ctypes.c_void_p(0x10008)
+FAKE2 = ctypes.c_void_p(0x20000)
 
 
 def _i32(a):
@@ -82,6 +83,33 @@ def test_rope_argument_errors(lib):
     assert rope([2, 2, 2], [0, 8], 8, dt=1) == 6
     assert rope([2, 2, 2], [0, 8], 8, x=ODD) == 9
     assert rope([0, 0, 0], [0, 0], 0) == 0
+
+
+def test_qknorm_rope_argument_errors(lib):
+    a, thw = _i32([2, 2, 2])
+    b, cu = _i32([0, 8])
+
+    def fwd(x=FAKE, gain=FAKE, eps=1e-6, y=FAKE, dims=(32, 48, 48), total=8, dt=0):
+        return lib.vfm_qknorm_rope3d(x, gain, eps, y, thw, cu, 1, total, 4, 128, dims[0], dims[1], dims[2],
+                                     1e4, dt, None)
+
+    def bwd(x=FAKE, gain=FAKE, eps=1e-6, dy=FAKE, dx=FAKE2, dgain=FAKE, total=8):
+        return lib.vfm_qknorm_rope3d_bwd(x, gain, eps, dy, dx, dgain, thw, cu, 1, total, 4, 128, 32, 48, 48,
+                                         1e4, 0, None)
+    assert fwd(gain=None) == 1
+    assert fwd(y=None) == 1
+    assert fwd(eps=-1.0) == 2
+    assert fwd(eps=float("nan")) == 2
+    assert fwd(dims=(32, 48, 40)) == 5
+    assert fwd(total=9) == 3
+    assert fwd(dt=1) == 6
+    assert fwd(x=ODD) == 9
+    assert fwd(gain=ctypes.c_void_p(0x10002)) == 9
+    assert bwd(dgain=None) == 1
+    assert bwd(dx=FAKE) == 2                                    # dx must not be x
+    assert bwd(dx=ODD) == 9
+    assert bwd(eps=-1e-3) == 2
+    assert bwd(total=7) == 3
 
 
 def test_bwd_argument_errors_and_workspace(lib):
