@@ -8,6 +8,10 @@ workload is the 720p-class 121-frame latent (T,H,W = 16,44,80 -> 56,320 tokens,
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--no-cpu-baseline]
 
+--workload NAME-spatial (e.g. C4-spatial) runs the spatial-attention view of a workload
+(Section 4.6 of the paper): RoPE on the clips' grids, attention with one sequence per latent
+frame.  It is a second workload, not the headline.
+
 FLOP convention (algorithmic, block-diagonal pairs only): forward 4*D and
 backward 10*D flops per (query, key) pair per head.
 
@@ -130,7 +134,8 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": dst.numel() * 4}))
         return 0
-    wl = W.WORKLOADS[args.workload]
+    spatial = args.workload.endswith("-spatial")
+    wl = W.WORKLOADS[args.workload[:-len("-spatial")] if spatial else args.workload]
     t = _device_tensors(wl)
     q, k, v, do = t["q"], t["k"], t["v"], t["dout"]
     out = torch.empty_like(q)
@@ -139,16 +144,17 @@ def main() -> int:
     ws = torch.empty(B.vfm_attn_bwd_workspace_size(wl.total_tokens, wl.n_heads, wl.head_dim),
                      dtype=torch.uint8, device="cuda")
     cu, thw = wl.cu_seqlens, wl.thw
+    cu_attn = wl.spatial_cu_seqlens if spatial else cu     # attention's sequence boundaries
 
     def step(ev=None):
         if ev: ev[0].record()
         B.vfm_rope3d(q, thw, cu, wl.rope_dims, wl.theta)
         B.vfm_rope3d(k, thw, cu, wl.rope_dims, wl.theta)
         if ev: ev[1].record()
-        B.vfm_attn_fwd(q, k, v, cu, wl.scale, out=out, lse=lse)
+        B.vfm_attn_fwd(q, k, v, cu_attn, wl.scale, out=out, lse=lse)
         if ev: ev[2].record()
         if wl.backward:
-            B.vfm_attn_bwd(q, k, v, out, lse, do, cu, wl.scale, dq=dq, dk=dk, dv=dv, workspace=ws)
+            B.vfm_attn_bwd(q, k, v, out, lse, do, cu_attn, wl.scale, dq=dq, dk=dk, dv=dv, workspace=ws)
         if ev: ev[3].record()
 
     for _ in range(args.warmup):
@@ -167,8 +173,8 @@ def main() -> int:
     ms_bwd = float(np.mean([e[2].elapsed_time(e[3]) for e in events])) if wl.backward else 0.0
     ms_each = [e[0].elapsed_time(e[3]) for e in events]
 
-    f_fwd = wl.flops(backward=False)
-    f_all = wl.flops()
+    f_fwd = wl.flops(backward=False, cu_seqlens=cu_attn)
+    f_all = wl.flops(cu_seqlens=cu_attn)
     f_bwd = f_all - f_fwd
     value = f_all / (ms_step * 1e-3) / 1e12
     rope_bytes = 2 * 2 * wl.total_tokens * wl.n_heads * wl.head_dim * 2   # q and k, read + write
@@ -188,7 +194,8 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: grids {list(wl.grids)} -> {wl.total_tokens} tokens, "
                                f"{wl.n_heads} heads, head_dim {wl.head_dim}, rope split {list(wl.rope_dims)}, "
-                               f"{'rope+fwd+bwd' if wl.backward else 'rope+fwd'}",
+                               f"{'rope+fwd+bwd' if wl.backward else 'rope+fwd'}"
+                               + (f", spatial view: {len(cu_attn) - 1} sequences of one latent frame each" if spatial else ""),
                    "flops_per_step": f_all, "pct_of_bf16_mfma_peak": 100.0 * value / BF16_MFMA_PEAK_TFLOPS},
         "breakdown": {"rope_ms": ms_rope, "fwd_ms": ms_fwd, "bwd_ms": ms_bwd,
                       "fwd_tflops": f_fwd / (ms_fwd * 1e-3) / 1e12,
@@ -240,7 +247,7 @@ def main() -> int:
         "bwd_frac_hbm_peak": 6 * elems / (ms_nb * 1e-3) / 1e9 / HBM_PEAK_GBS}
     del q, k, v, do, out, dq, dk, dv, ws, t
     torch.cuda.empty_cache()
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not spatial:
         result["cpu_baseline"] = _cpu_baseline(wl)
     print(json.dumps(result))
     return 0

@@ -45,6 +45,14 @@ class Workload:
         return np.asarray(self.grids, dtype=np.int32).reshape(-1, 3)
 
     @property
+    def spatial_cu_seqlens(self) -> np.ndarray:
+        """Segment boundaries of spatial attention (Section 4.6): every latent frame of every
+        clip is its own sequence of H*W tokens.  With t the slowest index of the flatten order
+        this is a pure re-reading of the same packed buffer."""
+        lens = [h * w for (t, h, w) in self.grids for _ in range(t)]
+        return np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+
+    @property
     def total_tokens(self) -> int:
         return int(sum(self.seqlens))
 
@@ -57,11 +65,13 @@ class Workload:
         """Number of (query, key) pairs per head: sum over clips of N_s**2."""
         return int(sum(n * n for n in self.seqlens))
 
-    def flops(self, backward: bool | None = None) -> float:
-        """Algorithmic flops: 4*D per pair per head forward, 10*D backward."""
+    def flops(self, backward: bool | None = None, cu_seqlens=None) -> float:
+        """Algorithmic flops: 4*D per pair per head forward, 10*D backward.  cu_seqlens
+        overrides the clip boundaries (e.g. the spatial view)."""
         bwd = self.backward if backward is None else backward
         per_pair = (4 + (10 if bwd else 0)) * self.head_dim
-        return float(per_pair) * self.n_heads * self.pairs
+        pairs = self.pairs if cu_seqlens is None else int(np.sum(np.diff(np.asarray(cu_seqlens, dtype=np.int64)) ** 2))
+        return float(per_pair) * self.n_heads * pairs
 
 
 WORKLOADS = {

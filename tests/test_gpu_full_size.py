@@ -120,6 +120,33 @@ def test_headline_56k_sampled_rows_and_columns():
     assert U.rel_rms(_f32(dv[cols, h, :]), dv_ref) <= U.TOL_GRAD_RELRMS
 
 
+@pytest.mark.parametrize("name,heads", [("C4", (0, 31)), ("C3", (11,))])
+def test_spatial_view_head_subset_full_oracle(name, heads):
+    """Spatial attention (Section 4.6): the same packed buffers read as one sequence per latent
+    frame (C4: 16 x 3,520 tokens; C3: 36 frames of 256 to 1,024 tokens).  RoPE keeps the clips'
+    grids; attention takes the per-frame boundaries.  All 32 / 24 heads run on the GPU; the
+    oracle covers every token of the listed heads."""
+    b = _binding()
+    wl = W.WORKLOADS[name]
+    dev = _upload(wl)
+    heads = list(heads)
+    b.vfm_rope3d(dev["q"], wl.thw, wl.cu_seqlens, wl.rope_dims, wl.theta)
+    b.vfm_rope3d(dev["k"], wl.thw, wl.cu_seqlens, wl.rope_dims, wl.theta)
+    cu = wl.spatial_cu_seqlens
+    out, lse = b.vfm_attn_fwd(dev["q"], dev["k"], dev["v"], cu, wl.scale)
+    dq, dk, dv = b.vfm_attn_bwd(dev["q"], dev["k"], dev["v"], out, lse, dev["dout"], cu, wl.scale)
+    host = {n: _f32(dev[n][:, heads, :]).astype(np.float64) for n in dev}
+    o_ref, l_ref = orc.attn_fwd(host["q"], host["k"], host["v"], cu, wl.scale)
+    g_ref = orc.attn_bwd(host["q"], host["k"], host["v"], host["dout"], cu, wl.scale)
+    o = _f32(out[:, heads, :]).astype(np.float64)
+    assert U.max_abs(o, o_ref) <= U.TOL_OUT_MAXABS
+    assert U.rel_rms(o, o_ref) <= U.TOL_OUT_RELRMS
+    assert U.max_abs(_f32(lse[heads, :]), l_ref) <= U.TOL_LSE_MAXABS
+    for nm, g, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), g_ref):
+        r = U.rel_rms(_f32(g[:, heads, :]).astype(np.float64), ref)
+        assert r <= U.TOL_GRAD_RELRMS, (nm, r)
+
+
 def test_inference_130k_four_steps_one_stream():
     """1080p-class latent, forward only: rope(q), rope(k), attention, four times back to back on
     one stream with no host synchronisation in between; the last step is checked."""

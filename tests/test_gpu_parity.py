@@ -109,6 +109,24 @@ def test_attention_with_rope_end_to_end(name):
     _assert_parity(wl, gpu, host)
 
 
+def test_spatial_attention_view():
+    # Section 4.6: spatial attention re-reads the packed clips as one sequence per latent frame;
+    # RoPE still uses the clips' own grids, attention uses the per-frame boundaries
+    wl = SMALL["ragged128"]
+    b = _binding()
+    inp = W.make_inputs(wl)
+    q, k, v, do = (U.to_device(inp[n]) for n in ("q", "k", "v", "dout"))
+    b.vfm_rope3d(q, wl.thw, wl.cu_seqlens, wl.rope_dims, wl.theta)
+    b.vfm_rope3d(k, wl.thw, wl.cu_seqlens, wl.rope_dims, wl.theta)
+    cu = wl.spatial_cu_seqlens
+    assert cu.tolist() == [0, 100, 200, 300, 301, 378, 549, 720, 891]
+    out, lse = b.vfm_attn_fwd(q, k, v, cu, wl.scale)
+    dq, dk, dv = b.vfm_attn_bwd(q, k, v, out, lse, do, cu, wl.scale)
+    frames = W.Workload("frames", tuple((1, 1, int(n)) for n in np.diff(cu)), wl.n_heads, wl.head_dim,
+                        wl.rope_dims, wl.seed)
+    _assert_parity(frames, (out, lse, dq, dk, dv), tuple(U.to_f64(t) for t in (q, k, v, do)))
+
+
 def test_peaky_softmax_running_max():
     # q, k scaled by 4: scores ~ N(0, 16^2); exercises the running-max update path
     wl = SMALL["ragged128"]
