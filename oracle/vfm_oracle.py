@@ -58,6 +58,8 @@ __all__ = [
     "qknorm_rope3d_bwd",
     "attn_fwd",
     "attn_bwd",
+    "xattn_fwd",
+    "xattn_bwd",
     "attn_fwd_rows",
     "attn_bwd_rows",
     "attn_bwd_cols",
@@ -258,6 +260,67 @@ def attn_bwd(q, k, v, dout, cu_seqlens, scale: float):
             dS = P * (dP - delta)
             dq[a:b, h, :] = scale * (dS @ K)
             dk[a:b, h, :] = scale * (dS.T @ Q)
+    return dq, dk, dv
+
+
+def xattn_fwd(q, k, v, cu_seqlens_q, cu_seqlens_kv, scale: float):
+    """Packed multi-head cross-attention forward (Section 4.2: every transformer block
+    attends from the video query tensor to the text embedding's keys and values).
+
+    Sequence s owns queries [cu_q[s], cu_q[s+1]) of q[total_q, heads, head_dim] and keys /
+    values [cu_kv[s], cu_kv[s+1]) of k, v[total_kv, heads, head_dim]:
+        S_ij = scale * sum_d Q_id K_jd      i in the query range, j in the key range
+        O_i  = sum_j softmax_j(S_ij) V_j,   LSE_i = ln sum_j exp(S_ij)
+    A sequence with queries needs at least one key.  Returns out [total_q, heads, head_dim]
+    and lse [heads, total_q], fp64.
+    """
+    q, k, v = _as_f64(q), _as_f64(k), _as_f64(v)
+    total_q, H, D = q.shape
+    cq = _check_cu(cu_seqlens_q, total_q)
+    ck = _check_cu(cu_seqlens_kv, k.shape[0])
+    if cq.size != ck.size:
+        raise ValueError("cu_seqlens_q and cu_seqlens_kv must name the same number of sequences")
+    out = np.zeros((total_q, H, D))
+    lse = np.zeros((H, total_q))
+    for s in range(cq.size - 1):
+        a, b, c, d = int(cq[s]), int(cq[s + 1]), int(ck[s]), int(ck[s + 1])
+        if b == a:
+            continue
+        if d == c:
+            raise ValueError("a sequence with queries has no keys")
+        for h in range(H):
+            P, L = _softmax_rows(scale * (q[a:b, h, :] @ k[c:d, h, :].T))
+            out[a:b, h, :] = P @ v[c:d, h, :]
+            lse[h, a:b] = L
+    return out, lse
+
+
+def xattn_bwd(q, k, v, dout, cu_seqlens_q, cu_seqlens_kv, scale: float):
+    """Gradients of  sum(out * dout)  of xattn_fwd with respect to q, k, v: the formulas of
+    attn_bwd with i over the sequence's queries and j over its keys.  Keys of a sequence
+    without queries get zero gradients.  Returns dq (shape of q), dk, dv (shape of k), fp64.
+    """
+    q, k, v, dout = _as_f64(q), _as_f64(k), _as_f64(v), _as_f64(dout)
+    cq = _check_cu(cu_seqlens_q, q.shape[0])
+    ck = _check_cu(cu_seqlens_kv, k.shape[0])
+    if cq.size != ck.size:
+        raise ValueError("cu_seqlens_q and cu_seqlens_kv must name the same number of sequences")
+    H = q.shape[1]
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    for s in range(cq.size - 1):
+        a, b, c, d = int(cq[s]), int(cq[s + 1]), int(ck[s]), int(ck[s + 1])
+        if b == a:
+            continue
+        if d == c:
+            raise ValueError("a sequence with queries has no keys")
+        for h in range(H):
+            Q, K, V, dO = q[a:b, h, :], k[c:d, h, :], v[c:d, h, :], dout[a:b, h, :]
+            P, _ = _softmax_rows(scale * (Q @ K.T))
+            delta = (dO * (P @ V)).sum(axis=1, keepdims=True)
+            dS = P * (dO @ V.T - delta)
+            dv[c:d, h, :] = P.T @ dO
+            dq[a:b, h, :] = scale * (dS @ K)
+            dk[c:d, h, :] = scale * (dS.T @ Q)
     return dq, dk, dv
 
 
