@@ -42,7 +42,8 @@
 extern "C" {
 #endif
 
-#define VFM_MAX_SEQS 256
+#define VFM_MAX_SEQS 256    /* clips per call, self-attention and RoPE */
+#define VFM_MAX_XSEQS 128   /* sequences per call, cross-attention */
 
 #define VFM_API __attribute__((visibility("default")))
 
@@ -167,6 +168,41 @@ VFM_API int vfm_attn_bwd(const void* q, const void* k, const void* v, const void
                  int n_seqs, int total_tokens, int n_heads, int head_dim, float scale,
                  void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
                  vfm_dtype dt, void* hip_stream);
+
+/*
+ * Cross-attention forward (Section 4.2: in every transformer block the video
+ * query tensor attends to the text embedding's keys and values).  Sequence s
+ * owns queries [cu_seqlens_q[s], cu_seqlens_q[s+1]) of q[total_q, n_heads,
+ * head_dim] and keys/values [cu_seqlens_kv[s], cu_seqlens_kv[s+1]) of
+ * k, v[total_kv, n_heads, head_dim]:
+ *     S_ij  = scale * sum_d q[i,h,d] k[j,h,d]
+ *     out_i = sum_j softmax_j(S_ij) v[j,h,:],   lse_i = ln sum_j exp(S_ij)
+ * out: bf16 [total_q, n_heads, head_dim]; lse: fp32 [n_heads, total_q].  Both
+ * cu arrays are host int32 [n_seqs+1], n_seqs <= VFM_MAX_XSEQS.  A sequence
+ * with queries must have at least one key (CU_SEQLENS); one with keys and no
+ * queries is legal.  Same kernels, arithmetic and reproducibility as
+ * vfm_attn_fwd, which is the case of equal ranges.
+ * Errors: NULL, SHAPE, CU_SEQLENS, DTYPE, ALIGN, LAUNCH.
+ */
+VFM_API int vfm_xattn_fwd(const void* q, const void* k, const void* v,
+                  const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_kv, int n_seqs,
+                  int total_q, int total_kv, int n_heads, int head_dim, float scale,
+                  void* out, float* lse, vfm_dtype dt, void* hip_stream);
+
+/*
+ * Cross-attention backward: dq [total_q, ...], dk, dv [total_kv, ...] from dout,
+ * with the formulas of vfm_attn_bwd, i over a sequence's queries and j over its
+ * keys.  Keys of a sequence without queries get zero gradients.  workspace: as
+ * for vfm_attn_bwd, sized by vfm_attn_bwd_workspace_size(total_q, n_heads,
+ * head_dim).  Every output is written once, no atomics.
+ * Errors: NULL, SHAPE, CU_SEQLENS, DTYPE, ALIGN, WORKSPACE, LAUNCH.
+ */
+VFM_API int vfm_xattn_bwd(const void* q, const void* k, const void* v, const void* out,
+                  const float* lse, const void* dout,
+                  const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_kv, int n_seqs,
+                  int total_q, int total_kv, int n_heads, int head_dim, float scale,
+                  void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                  vfm_dtype dt, void* hip_stream);
 
 /* Static, human-readable text for a vfm_status. */
 VFM_API const char* vfm_strerror(int status);

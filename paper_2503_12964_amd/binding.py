@@ -21,7 +21,7 @@ VFM_BF16 = 0
 VFM_F32 = 1
 VFM_MAX_SEQS = 256
 
-EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_strerror")
+EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_xattn_fwd", "vfm_xattn_bwd", "vfm_strerror")
 
 _lib = None
 
@@ -63,6 +63,13 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.vfm_attn_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, p_i32, c_int,
                                  c_int, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p, c_void_p,
                                  c_size_t, c_int, c_void_p]
+    lib.vfm_xattn_fwd.restype = c_int
+    lib.vfm_xattn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, p_i32, p_i32, c_int, c_int, c_int, c_int, c_int,
+                                  c_float, c_void_p, c_void_p, c_int, c_void_p]
+    lib.vfm_xattn_bwd.restype = c_int
+    lib.vfm_xattn_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, p_i32, p_i32, c_int,
+                                  c_int, c_int, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p, c_void_p,
+                                  c_size_t, c_int, c_void_p]
     lib.vfm_strerror.restype = ctypes.c_char_p
     lib.vfm_strerror.argtypes = [c_int]
     if path == LIB_PATH:
@@ -192,4 +199,46 @@ def vfm_attn_bwd(q, k, v, out, lse, dout, cu_seqlens, scale: float, dq=None, dk=
                             float(scale), _dev(dq, "dq"), _dev(dk, "dk"), _dev(dv, "dv"),
                             _dev(workspace, "workspace"), int(workspace.numel() * workspace.element_size()),
                             _dtype_code(q), _stream_ptr(stream)))
+    return dq, dk, dv
+
+
+def vfm_xattn_fwd(q, k, v, cu_seqlens_q, cu_seqlens_kv, scale: float, out=None, lse=None, stream=None) -> Tuple:
+    """Cross-attention: out[total_q, heads, head_dim] (bf16), lse[heads, total_q] (fp32)."""
+    import torch
+    lib = load_library()
+    cq, ck = _host_i32(cu_seqlens_q), _host_i32(cu_seqlens_kv)
+    if cq.size != ck.size:
+        raise ValueError("cu_seqlens_q and cu_seqlens_kv must have the same length")
+    total_q, heads, hd = q.shape
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((heads, total_q), dtype=torch.float32, device=q.device)
+    _check(lib.vfm_xattn_fwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _i32_ptr(cq), _i32_ptr(ck), int(cq.size - 1),
+                             int(total_q), int(k.shape[0]), int(heads), int(hd), float(scale), _dev(out, "out"),
+                             _dev(lse, "lse"), _dtype_code(q), _stream_ptr(stream)))
+    return out, lse
+
+
+def vfm_xattn_bwd(q, k, v, out, lse, dout, cu_seqlens_q, cu_seqlens_kv, scale: float, dq=None, dk=None,
+                  dv=None, workspace=None, stream=None) -> Tuple:
+    """Cross-attention gradients: dq (shape of q), dk, dv (shape of k)."""
+    import torch
+    lib = load_library()
+    cq, ck = _host_i32(cu_seqlens_q), _host_i32(cu_seqlens_kv)
+    if cq.size != ck.size:
+        raise ValueError("cu_seqlens_q and cu_seqlens_kv must have the same length")
+    total_q, heads, hd = q.shape
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    need = vfm_attn_bwd_workspace_size(total_q, heads, hd)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    _check(lib.vfm_xattn_bwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"), _dev(lse, "lse"),
+                             _dev(dout, "dout"), _i32_ptr(cq), _i32_ptr(ck), int(cq.size - 1), int(total_q),
+                             int(k.shape[0]), int(heads), int(hd), float(scale), _dev(dq, "dq"), _dev(dk, "dk"),
+                             _dev(dv, "dv"), _dev(workspace, "workspace"),
+                             int(workspace.numel() * workspace.element_size()), _dtype_code(q),
+                             _stream_ptr(stream)))
     return dq, dk, dv

@@ -90,14 +90,14 @@ struct BwdCfg {
   static constexpr int kBatch = 2 * kLoadsPerWave + 1;                   // loads per wave per tile
 };
 
-template <int D>
+template <int D, class Segs>
 __global__ __launch_bounds__(kBwdWaves * 64, 1)
 void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                           const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
                           const float* __restrict__ lse2, const float* __restrict__ delta,
                           const float* __restrict__ sentinel,   // [+inf, 0]
                           __bf16* __restrict__ dk, __bf16* __restrict__ dv,
-                          const SegTable segs, const UnitMap um,
+                          const Segs segs, const UnitMap um,
                           int total, int n_heads, float scale, float scale_log2) {
   using Cfg = BwdCfg<D>;
   constexpr int KS = D / 16;
@@ -111,8 +111,14 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 
   int head, tile;
   if (!map_unit(um, blockIdx.x, head, tile)) return;
-  int seg_a, seg_b, j0;
-  find_tile(segs, kBwdBC, tile, seg_a, seg_b, j0);
+  // key rows [j0, j0 + kBwdBC) of the sequence's key/value range [.., kv_b); the queries it
+  // walks are rows [seg_a, seg_b) of q, dout (the same range for self-attention)
+  int seq, tk;
+  locate_tile<true>(segs, kBwdBC, tile, seq, tk);
+  const int kv_b = segs.kv_start(seq) + segs.kv_len(seq);
+  const int j0 = segs.kv_start(seq) + tk * kBwdBC;
+  const int seg_a = segs.q_start(seq);
+  const int seg_b = seg_a + segs.q_len(seq);
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -124,10 +130,21 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 
   // ---- this wavefront's key/value rows as B operands (lane: row c, columns ks*16+8g..)
   const int jrow = j0 + wave * 32 + c;
-  const bool jvalid = jrow < seg_b;
+  const bool jvalid = jrow < kv_b;
+  if (seg_b == seg_a) {   // keys of a sequence without queries: zero gradients (cross-attention only)
+    if (jvalid) {
+      u32x2 z = {0u, 0u};
+#pragma unroll
+      for (int x = 0; x < D / 8; ++x) {
+        *reinterpret_cast<u32x2*>(dk + (size_t)jrow * row_stride + head_off + 4 * g + 8 * x) = z;
+        *reinterpret_cast<u32x2*>(dv + (size_t)jrow * row_stride + head_off + 4 * g + 8 * x) = z;
+      }
+    }
+    return;
+  }
   bf16x8 kreg[KS], vreg[KS];
   {
-    const size_t off = (size_t)min(jrow, seg_b - 1) * row_stride + head_off + 8 * g;
+    const size_t off = (size_t)min(jrow, kv_b - 1) * row_stride + head_off + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       kreg[ks] = *reinterpret_cast<const bf16x8*>(k + off + ks * 16);
@@ -377,12 +394,12 @@ struct DqCfg {
   static constexpr int kChunksPerThread = kDqBC * kChunksPerRow / (W * 64);
 };
 
-template <int D, int NI, int W>
+template <int D, int NI, int W, class Segs>
 __global__ __launch_bounds__(W * 64, (NI == 1 ? 2 : 1))
 void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                         const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
                         const float* __restrict__ lse2g, const float* __restrict__ delta,
-                        __bf16* __restrict__ dq, const SegTable segs, const UnitMap um,
+                        __bf16* __restrict__ dq, const Segs segs, const UnitMap um,
                         int total, int n_heads, float scale, float scale_log2) {
   using Cfg = DqCfg<D, NI, W>;
   constexpr int KS = D / 16;
@@ -395,8 +412,13 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
 
   int head, tile;
   if (!map_unit(um, blockIdx.x, head, tile)) return;
-  int seg_a, seg_b, q0;
-  find_tile(segs, Cfg::kBR, tile, seg_a, seg_b, q0);
+  // query rows of the range [.., q_b); keys and values are rows [seg_a, seg_b) of k, v
+  int seq, tq;
+  locate_tile<false>(segs, Cfg::kBR, tile, seq, tq);
+  const int q_b = segs.q_start(seq) + segs.q_len(seq);
+  const int q0 = segs.q_start(seq) + tq * Cfg::kBR;
+  const int seg_a = segs.kv_start(seq);
+  const int seg_b = seg_a + segs.kv_len(seq);
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -415,7 +437,7 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
 #pragma unroll
   for (int ib = 0; ib < NI; ++ib) {
     qrow[ib] = q0 + (wave * NI + ib) * 32 + c;
-    const int r = min(qrow[ib], seg_b - 1);
+    const int r = min(qrow[ib], q_b - 1);
     const size_t off = (size_t)r * row_stride + head_off + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -565,7 +587,7 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
 #pragma unroll
   for (int ib = 0; ib < NI; ++ib) {
     const int i = qrow[ib];
-    if (i < seg_b) {
+    if (i < q_b) {
       __bf16* op = dq + (size_t)i * row_stride + head_off + 4 * g;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
@@ -580,13 +602,12 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
   }
 }
 
-template <int D>
+template <int D, class Segs>
 static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, const void* out,
-                               const float* lse, const void* dout, const SegTable& segs, int total,
+                               const float* lse, const void* dout, const Segs& segs, int total,
                                int n_heads, float scale, void* dq, void* dk, void* dv,
                                float* delta, float* lse2, float* sentinel, hipStream_t stream) {
-  if (total == 0) return hipSuccess;
-  {
+  if (total > 0) {   // (with no queries at all only the keys' zero gradients remain to be written)
     constexpr int kTokPerBlock = 256 / (D / 8);
     const int grid = (total + kTokPerBlock - 1) / kTokPerBlock;
     bwd_prepare_kernel<D><<<grid, 256, 0, stream>>>((const u32x4*)out, (const u32x4*)dout, lse,
@@ -596,14 +617,13 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
   }
   {
     using Cfg = BwdCfg<D>;
-    int tiles = 0;
-    for (int s = 0; s < segs.n; ++s) tiles += (segs.len[s] + kBwdBC - 1) / kBwdBC;
+    const int tiles = count_tiles<true>(segs, kBwdBC);
     if (tiles == 0) return hipSuccess;
     UnitMap um;
     um.tiles_per_head = tiles;
     um.n_units = tiles * n_heads;
     um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
-    auto kern = attn_bwd_dkdv_kernel<D>;
+    auto kern = attn_bwd_dkdv_kernel<D, Segs>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
@@ -617,13 +637,13 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
     constexpr int NI = 1;
     constexpr int W = 8;   // 256 query rows share each staged K/V tile
     using Cfg = DqCfg<D, NI, W>;
-    int tiles = 0;
-    for (int s = 0; s < segs.n; ++s) tiles += (segs.len[s] + Cfg::kBR - 1) / Cfg::kBR;
+    const int tiles = count_tiles<false>(segs, Cfg::kBR);
+    if (tiles == 0) return hipSuccess;
     UnitMap um;
     um.tiles_per_head = tiles;
     um.n_units = tiles * n_heads;
     um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
-    auto kern = attn_bwd_dq_kernel<D, NI, W>;
+    auto kern = attn_bwd_dq_kernel<D, NI, W, Segs>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
@@ -634,13 +654,20 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
   }
 }
 
+template <class Segs>
 hipError_t launch_attn_bwd(const void* q, const void* k, const void* v, const void* out,
-                           const float* lse, const void* dout, const SegTable& segs, int total,
+                           const float* lse, const void* dout, const Segs& segs, int total,
                            int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
                            float* delta, float* lse2, float* sentinel, hipStream_t stream) {
   if (head_dim == 128)
     return launch_bwd_d<128>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, sentinel, stream);
   return launch_bwd_d<64>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, sentinel, stream);
 }
+template hipError_t launch_attn_bwd<SegTable>(const void*, const void*, const void*, const void*, const float*,
+                                              const void*, const SegTable&, int, int, int, float, void*, void*,
+                                              void*, float*, float*, float*, hipStream_t);
+template hipError_t launch_attn_bwd<XSegTable>(const void*, const void*, const void*, const void*, const float*,
+                                               const void*, const XSegTable&, int, int, int, float, void*, void*,
+                                               void*, float*, float*, float*, hipStream_t);
 
 }  // namespace vfm

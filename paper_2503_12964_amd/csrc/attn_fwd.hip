@@ -46,11 +46,11 @@ struct FwdCfg {
 // scheduling-group masks
 constexpr int kSgValu = 0x002, kSgMfma = 0x008, kSgDsRead = 0x100;
 
-template <int D, int W>
+template <int D, int W, class Segs>
 __global__ __launch_bounds__(W * 64, 2)
 void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                      const __bf16* __restrict__ v, __bf16* __restrict__ out,
-                     float* __restrict__ lse, const SegTable segs, const UnitMap um,
+                     float* __restrict__ lse, const Segs segs, const UnitMap um,
                      int total, int n_heads, float scale_log2) {
   using Cfg = FwdCfg<D, W>;
   constexpr int KS = D / 16;   // k-steps of the QK^T contraction
@@ -64,8 +64,14 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
 
   int head, tile;
   if (!map_unit(um, blockIdx.x, head, tile)) return;
-  int seg_a, seg_b, q0;
-  find_tile(segs, Cfg::kRows, tile, seg_a, seg_b, q0);
+  // query rows [q0, q0 + rows) of the sequence's query range [.., q_b); its keys and values
+  // are rows [seg_a, seg_b) of k and v (the same range for self-attention)
+  int seq, tq;
+  locate_tile<false>(segs, Cfg::kRows, tile, seq, tq);
+  const int q_b = segs.q_start(seq) + segs.q_len(seq);
+  const int q0 = segs.q_start(seq) + tq * Cfg::kRows;
+  const int seg_a = segs.kv_start(seq);
+  const int seg_b = seg_a + segs.kv_len(seq);
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -80,7 +86,7 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   bf16x8 qreg[KS];
   const int qrow = q0 + wave * 32 + c;
   {
-    const int r = min(qrow, seg_b - 1);
+    const int r = min(qrow, q_b - 1);
     const __bf16* qp = q + (size_t)r * row_stride + (size_t)head * D + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
@@ -325,7 +331,7 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   // ---- epilogue: normalise, write out (bf16) and lse (natural log)
   const float l_tot = pair_sum(l_run);
   const float inv = 1.0f / l_tot;
-  if (qrow < seg_b) {
+  if (qrow < q_b) {
     __bf16* op = out + (size_t)qrow * row_stride + (size_t)head * D + 4 * g;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -340,20 +346,19 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   }
 }
 
-template <int D, int W>
-static hipError_t launch_fwd_cfg(const void* q, const void* k, const void* v, const SegTable& segs,
+template <int D, int W, class Segs>
+static hipError_t launch_fwd_cfg(const void* q, const void* k, const void* v, const Segs& segs,
                                  int total, int n_heads, float scale, void* out, float* lse,
                                  hipStream_t stream) {
   using Cfg = FwdCfg<D, W>;
-  int tiles = 0;
-  for (int s = 0; s < segs.n; ++s) tiles += (segs.len[s] + Cfg::kRows - 1) / Cfg::kRows;
+  const int tiles = count_tiles<false>(segs, Cfg::kRows);
   if (tiles == 0) return hipSuccess;
   UnitMap um;
   um.tiles_per_head = tiles;
   um.n_units = tiles * n_heads;
   um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
   const int grid = um.chunk * kNumXcd;
-  auto kern = attn_fwd_kernel<D, W>;
+  auto kern = attn_fwd_kernel<D, W, Segs>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
   if (e != hipSuccess) return e;
@@ -363,11 +368,16 @@ static hipError_t launch_fwd_cfg(const void* q, const void* k, const void* v, co
   return hipGetLastError();
 }
 
-hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, const SegTable& segs,
+template <class Segs>
+hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, const Segs& segs,
                            int total, int n_heads, int head_dim, float scale, void* out,
                            float* lse, hipStream_t stream) {
   if (head_dim == 128) return launch_fwd_cfg<128, 8>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
   return launch_fwd_cfg<64, 4>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
 }
+template hipError_t launch_attn_fwd<SegTable>(const void*, const void*, const void*, const SegTable&, int,
+                                              int, int, float, void*, float*, hipStream_t);
+template hipError_t launch_attn_fwd<XSegTable>(const void*, const void*, const void*, const XSegTable&, int,
+                                               int, int, float, void*, float*, hipStream_t);
 
 }  // namespace vfm

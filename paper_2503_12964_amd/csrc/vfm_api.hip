@@ -10,6 +10,7 @@ namespace {
 
 using vfm::RopeTable;
 using vfm::SegTable;
+using vfm::XSegTable;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -17,8 +18,8 @@ int check_shape(int n_seqs, int total_tokens, int n_heads, int head_dim) {
   if (n_seqs < 0 || n_seqs > VFM_MAX_SEQS || total_tokens < 0 || n_heads < 1 || n_heads > 65535)
     return VFM_ERR_SHAPE;
   if (head_dim != 64 && head_dim != 128) return VFM_ERR_SHAPE;
-  // element offsets are 64-bit in the kernels; token*heads must still fit an int
-  if ((long long)total_tokens * n_heads > 0x7fffffffLL) return VFM_ERR_SHAPE;
+  // the direct-to-LDS loads address a tensor with 32-bit byte offsets
+  if ((long long)total_tokens * n_heads * head_dim * 2 > 0xffffffffLL) return VFM_ERR_SHAPE;
   return VFM_OK;
 }
 
@@ -46,6 +47,29 @@ void build_seg_table(const int32_t* cu, int n_seqs, SegTable* t) {
     t->len[i] = cu[order[i] + 1] - cu[order[i]];
   }
   for (int i = n; i < VFM_MAX_SEQS; ++i) { t->start[i] = 0; t->len[i] = 0; }
+}
+
+// Cross-attention sequences, most (query x key) pairs first.  Sequences with neither queries
+// nor keys are dropped; one with queries and no keys is an error.
+int build_xseg_table(const int32_t* cu_q, const int32_t* cu_kv, int n_seqs, XSegTable* t) {
+  int order[VFM_MAX_XSEQS];
+  int n = 0;
+  for (int s = 0; s < n_seqs; ++s) {
+    const int nq = cu_q[s + 1] - cu_q[s], nk = cu_kv[s + 1] - cu_kv[s];
+    if (nq > 0 && nk == 0) return VFM_ERR_CU_SEQLENS;
+    if (nq > 0 || nk > 0) order[n++] = s;
+  }
+  auto pairs = [&](int s) { return (long long)(cu_q[s + 1] - cu_q[s]) * (cu_kv[s + 1] - cu_kv[s]); };
+  std::stable_sort(order, order + n, [&](int a, int b) { return pairs(a) > pairs(b); });
+  t->n = n;
+  for (int i = 0; i < VFM_MAX_XSEQS; ++i) {
+    const bool live = i < n;
+    t->qs[i] = live ? cu_q[order[i]] : 0;
+    t->ql[i] = live ? cu_q[order[i] + 1] - cu_q[order[i]] : 0;
+    t->ks[i] = live ? cu_kv[order[i]] : 0;
+    t->kl[i] = live ? cu_kv[order[i] + 1] - cu_kv[order[i]] : 0;
+  }
+  return VFM_OK;
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -208,6 +232,66 @@ int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, c
   build_seg_table(cu_seqlens, n_seqs, &segs);
   hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_tokens, n_heads,
                                       head_dim, scale, dq, dk, dv, delta, lse2, sentinel,
+                                      static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+}
+
+int vfm_xattn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_q,
+                  const int32_t* cu_seqlens_kv, int n_seqs, int total_q, int total_kv, int n_heads,
+                  int head_dim, float scale, void* out, float* lse, vfm_dtype dt, void* hip_stream) {
+  if (!q || !k || !v || !cu_seqlens_q || !cu_seqlens_kv || !out || !lse) return VFM_ERR_NULL;
+  if (dt != VFM_BF16) return VFM_ERR_DTYPE;
+  if (n_seqs > VFM_MAX_XSEQS) return VFM_ERR_SHAPE;
+  int st = check_shape(n_seqs, total_q, n_heads, head_dim);
+  if (!st) st = check_shape(n_seqs, total_kv, n_heads, head_dim);
+  if (st) return st;
+  if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
+  st = check_cu(cu_seqlens_q, n_seqs, total_q);
+  if (!st) st = check_cu(cu_seqlens_kv, n_seqs, total_kv);
+  if (st) return st;
+  XSegTable segs;
+  st = build_xseg_table(cu_seqlens_q, cu_seqlens_kv, n_seqs, &segs);
+  if (st) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
+    return VFM_ERR_ALIGN;
+  if (total_q == 0) return VFM_OK;
+  hipError_t e = vfm::launch_attn_fwd(q, k, v, segs, total_q, n_heads, head_dim, scale, out, lse,
+                                      static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+}
+
+int vfm_xattn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                  const void* dout, const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_kv,
+                  int n_seqs, int total_q, int total_kv, int n_heads, int head_dim, float scale,
+                  void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+                  vfm_dtype dt, void* hip_stream) {
+  if (!q || !k || !v || !out || !lse || !dout || !cu_seqlens_q || !cu_seqlens_kv || !dq || !dk || !dv)
+    return VFM_ERR_NULL;
+  if (dt != VFM_BF16) return VFM_ERR_DTYPE;
+  if (n_seqs > VFM_MAX_XSEQS) return VFM_ERR_SHAPE;
+  int st = check_shape(n_seqs, total_q, n_heads, head_dim);
+  if (!st) st = check_shape(n_seqs, total_kv, n_heads, head_dim);
+  if (st) return st;
+  if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
+  st = check_cu(cu_seqlens_q, n_seqs, total_q);
+  if (!st) st = check_cu(cu_seqlens_kv, n_seqs, total_kv);
+  if (st) return st;
+  XSegTable segs;
+  st = build_xseg_table(cu_seqlens_q, cu_seqlens_kv, n_seqs, &segs);
+  if (st) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse) ||
+      !aligned16(dout) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
+    return VFM_ERR_ALIGN;
+  if (total_kv == 0) return VFM_OK;     // then total_q is 0 too
+  const size_t need = vfm_attn_bwd_workspace_size(total_q, n_heads, head_dim);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
+    return VFM_ERR_WORKSPACE;
+  float* delta = static_cast<float*>(workspace);
+  const size_t part = (need - 256) / 2;
+  float* lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + part);
+  float* sentinel = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * part);
+  hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_q, n_heads, head_dim,
+                                      scale, dq, dk, dv, delta, lse2, sentinel,
                                       static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
 }

@@ -23,11 +23,27 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kNumXcd = 8;  // MI355X: 8 XCDs, workgroups are dealt to them round-robin
 
 // Non-empty clips, longest first.  Passed to kernels by value (kernel argument
-// memory), so no device allocation or copy is needed for the schedule.
+// memory), so no device allocation or copy is needed for the schedule.  Self-attention:
+// a clip's queries and keys are the same token range.
 struct SegTable {
   int n;
   int start[VFM_MAX_SEQS];
   int len[VFM_MAX_SEQS];
+  __device__ __host__ int q_start(int s) const { return start[s]; }
+  __device__ __host__ int q_len(int s) const { return len[s]; }
+  __device__ __host__ int kv_start(int s) const { return start[s]; }
+  __device__ __host__ int kv_len(int s) const { return len[s]; }
+};
+
+// Cross-attention: sequence s owns a query range of one packed tensor and a key/value
+// range of another.  Same size in kernel-argument memory as SegTable.
+struct XSegTable {
+  int n;
+  int qs[VFM_MAX_XSEQS], ql[VFM_MAX_XSEQS], ks[VFM_MAX_XSEQS], kl[VFM_MAX_XSEQS];
+  __device__ __host__ int q_start(int s) const { return qs[s]; }
+  __device__ __host__ int q_len(int s) const { return ql[s]; }
+  __device__ __host__ int kv_start(int s) const { return ks[s]; }
+  __device__ __host__ int kv_len(int s) const { return kl[s]; }
 };
 
 // Clip table for RoPE: all clips in packed order.
@@ -57,19 +73,28 @@ __device__ __forceinline__ bool map_unit(const UnitMap& um, int block, int& head
   return true;
 }
 
-// Tile index (over all clips, longest clip first) -> clip range [a,b) and the
-// tile's first row.  rows_per_tile is the tile height.
-__device__ __forceinline__ void find_tile(const SegTable& segs, int rows_per_tile, int tile,
-                                          int& a, int& b, int& row0) {
-  int s = 0;
+// Tile index (over all sequences in table order) -> sequence s and tile t within it.
+// Tiles are cut from the query ranges (KV = false) or from the key/value ranges (KV = true);
+// rows_per_tile is the tile height.
+template <bool KV, class Segs>
+__device__ __forceinline__ void locate_tile(const Segs& segs, int rows_per_tile, int tile, int& s,
+                                            int& t) {
+  s = 0;
   for (; s < segs.n - 1; ++s) {
-    const int nt = (segs.len[s] + rows_per_tile - 1) / rows_per_tile;
+    const int len = KV ? segs.kv_len(s) : segs.q_len(s);
+    const int nt = (len + rows_per_tile - 1) / rows_per_tile;
     if (tile < nt) break;
     tile -= nt;
   }
-  a = segs.start[s];
-  b = a + segs.len[s];
-  row0 = a + tile * rows_per_tile;
+  t = tile;
+}
+
+template <bool KV, class Segs>
+inline int count_tiles(const Segs& segs, int rows_per_tile) {
+  int tiles = 0;
+  for (int s = 0; s < segs.n; ++s)
+    tiles += ((KV ? segs.kv_len(s) : segs.q_len(s)) + rows_per_tile - 1) / rows_per_tile;
+  return tiles;
 }
 
 // LDS tiles hold rows of D bf16 without padding; the 16-byte chunk index within
@@ -197,12 +222,16 @@ hipError_t launch_qknorm_rope3d_bwd(const void* x, const void* dy, void* dx, con
                                     int n_heads, int head_dim, int dim_t, int dim_h, int dim_w,
                                     float theta, hipStream_t stream);
 
-hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, const SegTable& segs,
-                           int total, int n_heads, int head_dim, float scale, void* out,
+// Segs is SegTable (self-attention) or XSegTable (cross-attention); total_q is the number
+// of query tokens (rows of lse, Delta).
+template <class Segs>
+hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, const Segs& segs,
+                           int total_q, int n_heads, int head_dim, float scale, void* out,
                            float* lse, hipStream_t stream);
 
+template <class Segs>
 hipError_t launch_attn_bwd(const void* q, const void* k, const void* v, const void* out,
-                           const float* lse, const void* dout, const SegTable& segs, int total,
+                           const float* lse, const void* dout, const Segs& segs, int total_q,
                            int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
                            float* delta, float* lse2, float* sentinel, hipStream_t stream);
 
