@@ -10,7 +10,9 @@ workload is the 720p-class 121-frame latent (T,H,W = 16,44,80 -> 56,320 tokens,
 
 --workload NAME-spatial (e.g. C4-spatial) runs the spatial-attention view of a workload
 (Section 4.6 of the paper): RoPE on the clips' grids, attention with one sequence per latent
-frame.  It is a second workload, not the headline.
+frame.  --workload NAME-cross runs cross-attention from the workload's video tokens to a
+512-token text embedding per clip (Section 4.2), forward + backward, no RoPE.  Both are
+further workloads, not the headline.
 
 FLOP convention (algorithmic, block-diagonal pairs only): forward 4*D and
 backward 10*D flops per (query, key) pair per head.
@@ -97,6 +99,72 @@ def _cpu_baseline(wl, rows: int = 24576):
     }
 
 
+TEXT_TOKENS = 512     # keys/values per clip in the cross-attention workload (text embedding length)
+
+
+def _bench_cross(args, wl) -> int:
+    """Cross-attention workload: queries = the workload's packed video tokens, keys/values =
+    TEXT_TOKENS text tokens per clip.  A step is vfm_xattn_fwd + vfm_xattn_bwd."""
+    import torch
+    from paper_2503_12964_amd import binding as B
+    from paper_2503_12964_amd import workloads as W
+    cu_q = wl.cu_seqlens
+    n_seqs = len(cu_q) - 1
+    cu_kv = (np.arange(n_seqs + 1) * TEXT_TOKENS).astype(np.int32)
+    tq, tk = int(cu_q[-1]), int(cu_kv[-1])
+
+    def dev(name, rows):
+        bits = W.f32_to_bf16_bits(W.normal_f32(wl.seed, name, (rows, wl.n_heads, wl.head_dim)))
+        return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).cuda()
+    q, do = dev("q", tq), dev("dout", tq)
+    k, v = dev("k", tk), dev("v", tk)
+    out = torch.empty_like(q)
+    lse = torch.empty((wl.n_heads, tq), dtype=torch.float32, device="cuda")
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+    ws = torch.empty(B.vfm_attn_bwd_workspace_size(tq, wl.n_heads, wl.head_dim), dtype=torch.uint8, device="cuda")
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        B.vfm_xattn_fwd(q, k, v, cu_q, cu_kv, wl.scale, out=out, lse=lse)
+        if ev: ev[1].record()
+        B.vfm_xattn_bwd(q, k, v, out, lse, do, cu_q, cu_kv, wl.scale, dq=dq, dk=dk, dv=dv, workspace=ws)
+        if ev: ev[2].record()
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_fwd = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    ms_bwd = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    pairs = float(np.sum(np.diff(cu_q).astype(np.float64) * np.diff(cu_kv)))
+    f_fwd, f_bwd = 4.0 * wl.head_dim * wl.n_heads * pairs, 10.0 * wl.head_dim * wl.n_heads * pairs
+    # compulsory HBM traffic: q, out (fwd); q, out, dout, dq (bwd); k, v, dk, dv are negligible
+    row_bytes = tq * wl.n_heads * wl.head_dim * 2
+    achieved = f_bwd / (ms_bwd * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": f"cross-attention fwd+bwd TFLOP/s, workload {args.workload}",
+        "value": (f_fwd + f_bwd) / (ms_step * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}-cross: {tq} video query tokens in {n_seqs} clip(s) x {TEXT_TOKENS} text "
+                               f"keys/values per clip, {wl.n_heads} heads, head_dim {wl.head_dim}, fwd+bwd",
+                   "flops_per_step": f_fwd + f_bwd},
+        "breakdown": {"fwd_ms": ms_fwd, "bwd_ms": ms_bwd, "fwd_tflops": f_fwd / (ms_fwd * 1e-3) / 1e12,
+                      "bwd_tflops": achieved,
+                      "fwd_min_hbm_gbs": 2 * row_bytes / (ms_fwd * 1e-3) / 1e9,
+                      "bwd_min_hbm_gbs": 4 * row_bytes / (ms_bwd * 1e-3) / 1e9},
+        "roofline": {"bound": "mfma", "kernel": "attn_bwd_dkdv_kernel + attn_bwd_dq_kernel (cross-attention tables)",
+                     "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": None, "ms": ms_bwd,
+                     "note": "short key ranges: the step also moves 6 x the query tensor through HBM, "
+                             "see breakdown.*_min_hbm_gbs"}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -134,6 +202,8 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4, "bytes_written": dst.numel() * 4}))
         return 0
+    if args.workload.endswith("-cross"):
+        return _bench_cross(args, W.WORKLOADS[args.workload[:-len("-cross")]])
     spatial = args.workload.endswith("-spatial")
     wl = W.WORKLOADS[args.workload[:-len("-spatial")] if spatial else args.workload]
     t = _device_tensors(wl)
