@@ -112,6 +112,38 @@ def test_qknorm_rope_argument_errors(lib):
     assert bwd(total=7) == 3
 
 
+def test_cross_attention_argument_errors(lib):
+    def xf(cu_q, cu_kv, tq, tk, n=None, q=FAKE, dt=0, scale=0.1):
+        a, pq = _i32(cu_q)
+        b, pk = _i32(cu_kv)
+        return lib.vfm_xattn_fwd(q, FAKE, FAKE, pq, pk, len(cu_q) - 1 if n is None else n, tq, tk, 2, 128, scale,
+                                 FAKE, FAKE, dt, None)
+    assert xf([0, 8], [0, 4], 8, 4, q=None) == 1
+    assert xf([0, 8], [0, 4], 8, 5) == 3                        # cu_seqlens_kv does not end at total_kv
+    assert xf([0, 4, 8], [0, 4, 4], 8, 4) == 3                  # queries without keys
+    assert xf([0] * 130, [0] * 130, 0, 0) == 2                  # more sequences than VFM_MAX_XSEQS
+    assert xf([0, 8], [0, 4], 8, 4, dt=1) == 6
+    assert xf([0, 8], [0, 4], 8, 4, q=ODD) == 9
+    assert xf([0, 8], [0, 4], 8, 4, scale=0.0) == 2
+    assert xf([0, 0], [0, 0], 0, 0) == 0
+    a, pq = _i32([0, 8])
+    b, pk = _i32([0, 4])
+
+    def xb(ws=FAKE, ws_bytes=1 << 30, dk=FAKE):
+        return lib.vfm_xattn_bwd(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, pq, pk, 1, 8, 4, 2, 128, 0.1, FAKE, dk, FAKE,
+                                 ws, ws_bytes, 0, None)
+    assert xb(dk=None) == 1
+    assert xb(ws=None) == 7
+    assert xb(ws_bytes=16) == 7
+
+
+def test_tensors_beyond_32bit_byte_offsets_are_rejected(lib):
+    # 131072 tokens x 128 heads x 128 x 2 bytes = 4 GiB: the kernels address tensors with 32-bit byte offsets
+    arr, p = _i32([0, 131072])
+    assert lib.vfm_attn_fwd(FAKE, FAKE, FAKE, p, 1, 131072, 128, 128, 0.1, FAKE, FAKE, 0, None) == 2
+    assert lib.vfm_attn_bwd_workspace_size(131072, 128, 128) == 0
+
+
 def test_bwd_argument_errors_and_workspace(lib):
     size = lib.vfm_attn_bwd_workspace_size
     assert size(0, 2, 128) == 0 or size(0, 2, 128) % 256 == 0
