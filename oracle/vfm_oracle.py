@@ -60,6 +60,8 @@ __all__ = [
     "attn_bwd",
     "xattn_fwd",
     "xattn_bwd",
+    "temporal_attn_fwd",
+    "temporal_attn_bwd",
     "attn_fwd_rows",
     "attn_bwd_rows",
     "attn_bwd_cols",
@@ -321,6 +323,63 @@ def xattn_bwd(q, k, v, dout, cu_seqlens_q, cu_seqlens_kv, scale: float):
             dv[c:d, h, :] = P.T @ dO
             dq[a:b, h, :] = scale * (dS @ K)
             dk[c:d, h, :] = scale * (dS.T @ Q)
+    return dq, dk, dv
+
+
+def _temporal_rows(thw, cu_seqlens):
+    """For every clip, the packed token rows of each temporal sequence: an int array
+    [H*W, T] whose entry (p, t) is the row of pixel p in frame t (t is the slowest index of
+    the flatten order)."""
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    grids = np.asarray(thw, dtype=np.int64).reshape(-1, 3)
+    for s, (T, H, W) in enumerate(grids):
+        n = int(cu[s + 1] - cu[s])
+        if n == 0:
+            continue
+        if T * H * W != n:
+            raise ValueError("T*H*W must equal the clip length")
+        yield int(cu[s]) + np.arange(T)[None, :] * (H * W) + np.arange(H * W)[:, None]
+
+
+def temporal_attn_fwd(q, k, v, thw, cu_seqlens, scale: float):
+    """Temporal attention of the spatial-temporal transformer (Section 4.6): attention among
+    the inter-frame tokens of one pixel, i.e. the buffer [b, h*w*t, d] read as
+    [(b*h*w), t, d].  For clip s with grid (T, H, W) and pixel p the sequence is the T rows
+    cu[s] + t*H*W + p; within it, per head, out = softmax(scale Q K^T) V.
+    Returns out [total, heads, head_dim], fp64.
+    """
+    q, k, v = _as_f64(q), _as_f64(k), _as_f64(v)
+    _check_cu(cu_seqlens, q.shape[0])
+    out = np.zeros_like(q)
+    for rows in _temporal_rows(thw, cu_seqlens):
+        Q, K, V = q[rows], k[rows], v[rows]                     # [pixels, T, heads, D]
+        S = scale * np.einsum("pihd,pjhd->phij", Q, K)
+        S -= S.max(axis=3, keepdims=True)
+        P = np.exp(S)
+        P /= P.sum(axis=3, keepdims=True)
+        out[rows] = np.einsum("phij,pjhd->pihd", P, V)
+    return out
+
+
+def temporal_attn_bwd(q, k, v, dout, thw, cu_seqlens, scale: float):
+    """Gradients of  sum(out * dout)  of temporal_attn_fwd with respect to q, k, v (the
+    formulas of attn_bwd inside every temporal sequence)."""
+    q, k, v, dout = _as_f64(q), _as_f64(k), _as_f64(v), _as_f64(dout)
+    _check_cu(cu_seqlens, q.shape[0])
+    dq, dk, dv = np.zeros_like(q), np.zeros_like(k), np.zeros_like(v)
+    for rows in _temporal_rows(thw, cu_seqlens):
+        Q, K, V, dO = q[rows], k[rows], v[rows], dout[rows]
+        S = scale * np.einsum("pihd,pjhd->phij", Q, K)
+        S -= S.max(axis=3, keepdims=True)
+        P = np.exp(S)
+        P /= P.sum(axis=3, keepdims=True)
+        O = np.einsum("phij,pjhd->pihd", P, V)
+        delta = np.einsum("pihd,pihd->phi", dO, O)[..., None]
+        dP = np.einsum("pihd,pjhd->phij", dO, V)
+        dS = P * (dP - delta)
+        dv[rows] = np.einsum("phij,pihd->pjhd", P, dO)
+        dq[rows] = scale * np.einsum("phij,pjhd->pihd", dS, K)
+        dk[rows] = scale * np.einsum("phij,pihd->pjhd", dS, Q)
     return dq, dk, dv
 
 
