@@ -11,8 +11,10 @@ workload is the 720p-class 121-frame latent (T,H,W = 16,44,80 -> 56,320 tokens,
 --workload NAME-spatial (e.g. C4-spatial) runs the spatial-attention view of a workload
 (Section 4.6 of the paper): RoPE on the clips' grids, attention with one sequence per latent
 frame.  --workload NAME-cross runs cross-attention from the workload's video tokens to a
-512-token text embedding per clip (Section 4.2), forward + backward, no RoPE.  Both are
-further workloads, not the headline.
+512-token text embedding per clip (Section 4.2), forward + backward, no RoPE.
+--workload NAME-temporal runs temporal attention (one sequence per pixel across the clip's
+frames, Section 4.6), forward + backward; it is HBM-bound.  All three are further workloads,
+not the headline.
 
 FLOP convention (algorithmic, block-diagonal pairs only): forward 4*D and
 backward 10*D flops per (query, key) pair per head.
@@ -165,6 +167,54 @@ def _bench_cross(args, wl) -> int:
     return 0
 
 
+def _bench_temporal(args, wl) -> int:
+    """Temporal-attention workload: a step is vfm_tattn_fwd + vfm_tattn_bwd on the workload's clips."""
+    import torch
+    from paper_2503_12964_amd import binding as B
+    t = _device_tensors(wl)
+    q, k, v, do = t["q"], t["k"], t["v"], t["dout"]
+    out, dq, dk, dv = (torch.empty_like(q) for _ in range(4))
+    cu, thw = wl.cu_seqlens, wl.thw
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        B.vfm_tattn_fwd(q, k, v, thw, cu, wl.scale, out=out)
+        if ev: ev[1].record()
+        B.vfm_tattn_bwd(q, k, v, do, thw, cu, wl.scale, dq=dq, dk=dk, dv=dv)
+        if ev: ev[2].record()
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_fwd = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    ms_bwd = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    tensor_bytes = wl.total_tokens * wl.n_heads * wl.head_dim * 2
+    pairs = float(sum(t_ * t_ * h * w for (t_, h, w) in wl.grids))
+    flops = 14.0 * wl.head_dim * wl.n_heads * pairs
+    gbs_bwd = 7 * tensor_bytes / (ms_bwd * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": f"temporal attention fwd+bwd GB/s of algorithmic traffic, workload {args.workload}",
+        "value": 11 * tensor_bytes / (ms_step * 1e-3) / 1e9, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}-temporal: grids {list(wl.grids)} -> {wl.total_tokens} tokens, one sequence "
+                               f"per pixel across frames, {wl.n_heads} heads, head_dim {wl.head_dim}, fwd+bwd",
+                   "flops_per_step": flops},
+        "breakdown": {"fwd_ms": ms_fwd, "bwd_ms": ms_bwd,
+                      "fwd_gbs": 4 * tensor_bytes / (ms_fwd * 1e-3) / 1e9, "bwd_gbs": gbs_bwd,
+                      "tflops": flops / (ms_step * 1e-3) / 1e12},
+        "roofline": {"bound": "hbm", "kernel": "tattn_bwd_kernel", "achieved": gbs_bwd, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": gbs_bwd / HBM_PEAK_GBS, "traffic": None, "ms": ms_bwd,
+                     "note": "algorithmic bytes: q, k, v, dout read and dq, dk, dv written once = 7 tensors "
+                             "(forward: q, k, v read, out written = 4 tensors)"}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -204,6 +254,8 @@ def main() -> int:
         return 0
     if args.workload.endswith("-cross"):
         return _bench_cross(args, W.WORKLOADS[args.workload[:-len("-cross")]])
+    if args.workload.endswith("-temporal"):
+        return _bench_temporal(args, W.WORKLOADS[args.workload[:-len("-temporal")]])
     spatial = args.workload.endswith("-spatial")
     wl = W.WORKLOADS[args.workload[:-len("-spatial")] if spatial else args.workload]
     t = _device_tensors(wl)

@@ -44,6 +44,7 @@ extern "C" {
 
 #define VFM_MAX_SEQS 256    /* clips per call, self-attention and RoPE */
 #define VFM_MAX_XSEQS 128   /* sequences per call, cross-attention */
+#define VFM_MAX_TEMPORAL 16 /* latent frames per clip, temporal attention */
 
 #define VFM_API __attribute__((visibility("default")))
 
@@ -203,6 +204,32 @@ VFM_API int vfm_xattn_bwd(const void* q, const void* k, const void* v, const voi
                   int total_q, int total_kv, int n_heads, int head_dim, float scale,
                   void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
                   vfm_dtype dt, void* hip_stream);
+
+/*
+ * Temporal attention of the spatial-temporal transformer (Section 4.6): attention
+ * among the inter-frame tokens of one pixel, i.e. the packed buffer [b, h*w*t, d]
+ * read as [(b*h*w), t, d].  For clip s with grid (T,H,W) = thw[3s..3s+2] and
+ * pixel p < H*W the sequence is the T rows cu_seqlens[s] + t*H*W + p; per head
+ *     out_i = sum_j softmax_j(scale * q_i . k_j) v_j       i, j over the T frames.
+ * T <= VFM_MAX_TEMPORAL (THW otherwise).  q, k, v, out: bf16 [total_tokens,
+ * n_heads, head_dim]; thw, cu_seqlens: host.  No statistics are saved.
+ * Errors: NULL, SHAPE, CU_SEQLENS, THW, DTYPE, ALIGN, LAUNCH.
+ */
+VFM_API int vfm_tattn_fwd(const void* q, const void* k, const void* v,
+                  const int32_t* thw, const int32_t* cu_seqlens, int n_seqs,
+                  int total_tokens, int n_heads, int head_dim, float scale,
+                  void* out, vfm_dtype dt, void* hip_stream);
+
+/*
+ * Temporal attention backward: dq, dk, dv (bf16, fully overwritten) from dout.
+ * The softmax is recomputed from q and k; Delta_i = sum_j P_ij (dout_i . v_j).
+ * Every output is written once, no atomics, no workspace.
+ * Errors: NULL, SHAPE, CU_SEQLENS, THW, DTYPE, ALIGN, LAUNCH.
+ */
+VFM_API int vfm_tattn_bwd(const void* q, const void* k, const void* v, const void* dout,
+                  const int32_t* thw, const int32_t* cu_seqlens, int n_seqs,
+                  int total_tokens, int n_heads, int head_dim, float scale,
+                  void* dq, void* dk, void* dv, vfm_dtype dt, void* hip_stream);
 
 /* Static, human-readable text for a vfm_status. */
 VFM_API const char* vfm_strerror(int status);

@@ -21,7 +21,8 @@ VFM_BF16 = 0
 VFM_F32 = 1
 VFM_MAX_SEQS = 256
 
-EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_xattn_fwd", "vfm_xattn_bwd", "vfm_strerror")
+EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_xattn_fwd", "vfm_xattn_bwd", "vfm_tattn_fwd", "vfm_tattn_bwd",
+           "vfm_strerror")
 
 _lib = None
 
@@ -70,6 +71,12 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.vfm_xattn_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, p_i32, p_i32, c_int,
                                   c_int, c_int, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p, c_void_p,
                                   c_size_t, c_int, c_void_p]
+    lib.vfm_tattn_fwd.restype = c_int
+    lib.vfm_tattn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, p_i32, p_i32, c_int, c_int, c_int, c_int, c_float,
+                                  c_void_p, c_int, c_void_p]
+    lib.vfm_tattn_bwd.restype = c_int
+    lib.vfm_tattn_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, p_i32, p_i32, c_int, c_int, c_int, c_int,
+                                  c_float, c_void_p, c_void_p, c_void_p, c_int, c_void_p]
     lib.vfm_strerror.restype = ctypes.c_char_p
     lib.vfm_strerror.argtypes = [c_int]
     if path == LIB_PATH:
@@ -241,4 +248,34 @@ def vfm_xattn_bwd(q, k, v, out, lse, dout, cu_seqlens_q, cu_seqlens_kv, scale: f
                              _dev(dv, "dv"), _dev(workspace, "workspace"),
                              int(workspace.numel() * workspace.element_size()), _dtype_code(q),
                              _stream_ptr(stream)))
+    return dq, dk, dv
+
+
+def vfm_tattn_fwd(q, k, v, thw, cu_seqlens, scale: float, out=None, stream=None):
+    """Temporal attention (one sequence per pixel across a clip's frames): out, shape of q."""
+    import torch
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    g = _host_i32(thw).reshape(-1)
+    total, heads, hd = q.shape
+    out = torch.empty_like(q) if out is None else out
+    _check(lib.vfm_tattn_fwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _i32_ptr(g), _i32_ptr(cu), int(cu.size - 1),
+                             int(total), int(heads), int(hd), float(scale), _dev(out, "out"), _dtype_code(q),
+                             _stream_ptr(stream)))
+    return out
+
+
+def vfm_tattn_bwd(q, k, v, dout, thw, cu_seqlens, scale: float, dq=None, dk=None, dv=None, stream=None) -> Tuple:
+    """Temporal attention gradients dq, dk, dv (shape of q)."""
+    import torch
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    g = _host_i32(thw).reshape(-1)
+    total, heads, hd = q.shape
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    _check(lib.vfm_tattn_bwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(dout, "dout"), _i32_ptr(g), _i32_ptr(cu),
+                             int(cu.size - 1), int(total), int(heads), int(hd), float(scale), _dev(dq, "dq"),
+                             _dev(dk, "dk"), _dev(dv, "dv"), _dtype_code(q), _stream_ptr(stream)))
     return dq, dk, dv

@@ -1,0 +1,312 @@
+// Temporal attention for gfx950: one sequence per (clip, pixel) made of that pixel's token
+// in every latent frame (T <= 16 rows, H*W tokens apart in the packed buffer), per head.
+// HBM-bound: the whole problem of one (pixel, head) is a 16 x 16 score tile.
+//
+// One wavefront owns one (pixel, head).  It gathers the T rows of q, k, v (and dout) into a
+// wave-private LDS tile with direct global->LDS loads (16-byte chunks, 256-byte rows, the same
+// XOR swizzle as the other attention kernels), and needs no workgroup barrier at all.
+//   S^T = K Q^T            v_mfma_f32_16x16x32_bf16, A = K rows, B = Q rows
+// leaves lane l with query i = l % 16 and keys j = 4*(l/16) + r in its four registers, so the
+// softmax is a 4-register reduction plus two lane exchanges (xor 16, xor 32), and the
+// normalised bf16 P^T registers are the B operand of
+//   O^T = V^T P^T          v_mfma_f32_16x16x16_bf16, A = V^T through transposing LDS reads.
+// The backward recomputes the softmax (no saved statistics; Delta_i = sum_j P_ij dP_ij) and
+// needs P and dS in both orientations -- lane = query for dQ, lane = key for dK and dV -- which
+// it gets by issuing the score MFMAs twice with the operands swapped.
+// Rows past T are clamped copies of row T-1: as keys they are masked, as queries their
+// results are not stored and their P is zeroed where it would be summed into dK/dV.
+#include "vfm_common.h"
+
+namespace vfm {
+
+namespace {
+
+constexpr int kTRows = 16;       // rows of a temporal tile = largest T served
+constexpr int kTWaves = 4;
+constexpr float kLog2eT = 1.4426950408889634f;
+
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+template <int D>
+struct TCfg {
+  static constexpr int kTileBytes = kTRows * D * 2;
+  static constexpr int kChunksPerRow = D / 8;
+  static constexpr int kLoadsPerTile = kTRows * kChunksPerRow / 64;
+};
+
+__device__ __forceinline__ f32x4v mfma16x32(bf16x8 a, bf16x8 b, f32x4v c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4v mfma16x16(bf16x4 a, bf16x4 b, f32x4v c) {
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ bf16x4 lds_tr4(const char* base, int off) {
+  return __builtin_bit_cast(bf16x4, lds_read_tr(base, off));
+}
+
+// Which (clip, pixel, head) this wavefront owns.  Returns false past the end.
+struct TUnit {
+  int head, first_row, hw, T;   // rows of the sequence: first_row + t*hw, t < T
+};
+__device__ __forceinline__ bool temporal_unit(const TemporalTable& tab, int n_heads, TUnit& u) {
+  const long long unit = (long long)blockIdx.x * kTWaves + (threadIdx.x >> 6);
+  const long long n_units = (long long)tab.pix_cu[tab.n] * n_heads;
+  if (unit >= n_units) return false;
+  u.head = (int)(unit % n_heads);
+  const int pp = (int)(unit / n_heads);
+  int lo = 0, hi = tab.n;            // last clip s with pix_cu[s] <= pp (skips empty clips)
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (tab.pix_cu[mid] <= pp) lo = mid; else hi = mid;
+  }
+  u.hw = tab.hw[lo];
+  u.first_row = tab.cu[lo] + (pp - tab.pix_cu[lo]);
+  u.T = (tab.cu[lo + 1] - tab.cu[lo]) / u.hw;
+  return true;
+}
+
+// Gather the sequence's rows of one tensor into a swizzled [16][D] LDS tile.
+template <int D>
+__device__ __forceinline__ void gather_tile(const __bf16* base, const TUnit& u, uint32_t row_bytes,
+                                            uint32_t lds_tile, int lane) {
+  using Cfg = TCfg<D>;
+#pragma unroll
+  for (int x = 0; x < Cfg::kLoadsPerTile; ++x) {
+    const int p = x * 64 + lane;
+    const int r = p / Cfg::kChunksPerRow;
+    const int chunk = (p % Cfg::kChunksPerRow) ^ swz<D>(r);
+    const uint32_t off = (uint32_t)(u.first_row + min(r, u.T - 1) * u.hw) * row_bytes +
+                         (uint32_t)(u.head * D * 2 + chunk * 16);
+    lds_dma16(base, off, lds_tile + x * 1024);
+  }
+}
+
+// Row operands of a tile for the 16x16x32 MFMA: lane l holds row l%16, columns ks*32 + 8*(l/16)..+7.
+template <int D>
+__device__ __forceinline__ void read_rows(const char* tile, int lane, bf16x8 (&f)[D / 32]) {
+#pragma unroll
+  for (int ks = 0; ks < D / 32; ++ks) f[ks] = lds_read_b128(tile, tile_off<D>(lane & 15, ks * 32 + 8 * (lane >> 4)));
+}
+
+// Transposed operand for the 16x16x16 MFMA: lane l gets X[4*(l/16) + r][db*16 + l%16], r < 4.
+template <int D>
+__device__ __forceinline__ bf16x4 read_tr(const char* tile, int lane, int db) {
+  return lds_tr4(tile, tile_off<D>(4 * (lane >> 4) + ((lane & 15) >> 2), db * 16 + 4 * (lane & 3)));
+}
+
+__device__ __forceinline__ float quad_group_max(float x) {   // over lanes l, l^16, l^32, l^48
+  x = fmaxf(x, __shfl_xor(x, 16));
+  return fmaxf(x, __shfl_xor(x, 32));
+}
+__device__ __forceinline__ float quad_group_sum(float x) {
+  x += __shfl_xor(x, 16);
+  return x + __shfl_xor(x, 32);
+}
+
+// Store a 16x16x16 result tile C[d = db*16 + 4*(l/16) + r][token = l%16] as 4 bf16 of row `token`.
+template <int D>
+__device__ __forceinline__ void store_tile(__bf16* base, const TUnit& u, size_t row_stride, int lane,
+                                           int db, f32x4v c, float mul) {
+  if ((lane & 15) < u.T) {
+    const size_t row = (size_t)(u.first_row + (lane & 15) * u.hw);
+    f32x4 o = {c[0] * mul, c[1] * mul, c[2] * mul, c[3] * mul};
+    *reinterpret_cast<bf16x4*>(base + row * row_stride + (size_t)u.head * D + db * 16 + 4 * (lane >> 4)) =
+        to_bf16x4(o);
+  }
+}
+
+}  // namespace
+
+template <int D>
+__global__ __launch_bounds__(kTWaves * 64) void tattn_fwd_kernel(const __bf16* __restrict__ q,
+                                                                 const __bf16* __restrict__ k,
+                                                                 const __bf16* __restrict__ v,
+                                                                 __bf16* __restrict__ out,
+                                                                 const TemporalTable tab, int n_heads,
+                                                                 float scale_log2) {
+  using Cfg = TCfg<D>;
+  constexpr int TB = Cfg::kTileBytes;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  TUnit u;
+  if (!temporal_unit(tab, n_heads, u)) return;   // whole wavefronts leave; there are no barriers
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const size_t row_stride = (size_t)n_heads * D;
+  const uint32_t row_bytes = (uint32_t)row_stride * 2u;
+  char* mine = smem + wave * 3 * TB;
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(mine));
+  gather_tile<D>(q, u, row_bytes, lds0, lane);
+  gather_tile<D>(k, u, row_bytes, lds0 + TB, lane);
+  gather_tile<D>(v, u, row_bytes, lds0 + 2 * TB, lane);
+  wait_vmcnt<0>();
+
+  bf16x8 qf[D / 32], kf[D / 32];
+  read_rows<D>(mine, lane, qf);
+  read_rows<D>(mine + TB, lane, kf);
+  f32x4v st = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int ks = 0; ks < D / 32; ++ks) st = mfma16x32(kf[ks], qf[ks], st);
+  // lane: query l%16; register r: key 4*(l/16) + r
+  float mx = -INFINITY;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    if (4 * (lane >> 4) + r >= u.T) st[r] = -INFINITY;
+    mx = fmaxf(mx, st[r]);
+  }
+  const float m2 = quad_group_max(mx) * scale_log2;
+  f32x4 p;
+  float sum = 0.f;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    p[r] = fast_exp2(st[r] * scale_log2 - m2);
+    sum += p[r];
+  }
+  const float inv = 1.0f / quad_group_sum(sum);
+#pragma unroll
+  for (int r = 0; r < 4; ++r) p[r] *= inv;
+  const bf16x4 pb = to_bf16x4(p);
+  const f32x4v zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int db = 0; db < D / 16; ++db) {
+    const f32x4v o = mfma16x16(read_tr<D>(mine + 2 * TB, lane, db), pb, zero);
+    store_tile<D>(out, u, row_stride, lane, db, o, 1.0f);
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(kTWaves * 64) void tattn_bwd_kernel(const __bf16* __restrict__ q,
+                                                                 const __bf16* __restrict__ k,
+                                                                 const __bf16* __restrict__ v,
+                                                                 const __bf16* __restrict__ dout,
+                                                                 __bf16* __restrict__ dq,
+                                                                 __bf16* __restrict__ dk,
+                                                                 __bf16* __restrict__ dv,
+                                                                 const TemporalTable tab, int n_heads,
+                                                                 float scale, float scale_log2) {
+  using Cfg = TCfg<D>;
+  constexpr int TB = Cfg::kTileBytes;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  TUnit u;
+  if (!temporal_unit(tab, n_heads, u)) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const size_t row_stride = (size_t)n_heads * D;
+  const uint32_t row_bytes = (uint32_t)row_stride * 2u;
+  char* qt = smem + wave * 4 * TB;
+  char* kt = qt + TB;
+  char* vt = qt + 2 * TB;
+  char* dot = qt + 3 * TB;
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(qt));
+  gather_tile<D>(q, u, row_bytes, lds0, lane);
+  gather_tile<D>(k, u, row_bytes, lds0 + TB, lane);
+  gather_tile<D>(v, u, row_bytes, lds0 + 2 * TB, lane);
+  gather_tile<D>(dout, u, row_bytes, lds0 + 3 * TB, lane);
+  wait_vmcnt<0>();
+
+  bf16x8 qf[D / 32], kf[D / 32], vf[D / 32], df[D / 32];
+  read_rows<D>(qt, lane, qf);
+  read_rows<D>(kt, lane, kf);
+  read_rows<D>(vt, lane, vf);
+  read_rows<D>(dot, lane, df);
+  // "A": lane = query, registers = keys (S^T, dP^T);  "B": lane = key, registers = queries (S, dP)
+  f32x4v sA = {0.f, 0.f, 0.f, 0.f}, sB = sA, dpA = sA, dpB = sA;
+#pragma unroll
+  for (int ks = 0; ks < D / 32; ++ks) {
+    sA = mfma16x32(kf[ks], qf[ks], sA);
+    sB = mfma16x32(qf[ks], kf[ks], sB);
+    dpA = mfma16x32(vf[ks], df[ks], dpA);
+    dpB = mfma16x32(df[ks], vf[ks], dpB);
+  }
+  const int base_r = 4 * (lane >> 4);
+  // softmax statistics per query, in orientation A
+  float mx = -INFINITY;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    if (base_r + r >= u.T) sA[r] = -INFINITY;
+    mx = fmaxf(mx, sA[r]);
+  }
+  const float m2 = quad_group_max(mx) * scale_log2;
+  float pA[4], sum = 0.f;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    pA[r] = fast_exp2(sA[r] * scale_log2 - m2);
+    sum += pA[r];
+  }
+  sum = quad_group_sum(sum);
+  const float lse2 = m2 + __log2f(sum);      // P = exp2(s*scale_log2 - lse2)
+  const float inv = 1.0f / sum;
+  float dl = 0.f;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    pA[r] *= inv;
+    dl += pA[r] * dpA[r];
+  }
+  const float delta = quad_group_sum(dl);    // Delta_i = sum_j P_ij dP_ij
+  f32x4 dsA;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) dsA[r] = pA[r] * (dpA[r] - delta);
+  const bf16x4 dsAb = to_bf16x4(dsA);
+  // orientation B: register r belongs to query base_r + r, whose statistics lane base_r + r holds
+  f32x4 pB, dsB;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const float l2 = __shfl(lse2, base_r + r);
+    const float dd = __shfl(delta, base_r + r);
+    const float pv = (base_r + r < u.T) ? fast_exp2(sB[r] * scale_log2 - l2) : 0.f;   // padded queries add nothing
+    pB[r] = pv;
+    dsB[r] = pv * (dpB[r] - dd);
+  }
+  const bf16x4 pBb = to_bf16x4(pB), dsBb = to_bf16x4(dsB);
+  const f32x4v zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int db = 0; db < D / 16; ++db) {
+    // dV^T[d, j] = sum_i dO[i, d] P[i, j];  dK^T[d, j] = scale sum_i Q[i, d] dS[i, j]
+    store_tile<D>(dv, u, row_stride, lane, db, mfma16x16(read_tr<D>(dot, lane, db), pBb, zero), 1.0f);
+    store_tile<D>(dk, u, row_stride, lane, db, mfma16x16(read_tr<D>(qt, lane, db), dsBb, zero), scale);
+    // dQ^T[d, i] = scale sum_j K[j, d] dS^T[j, i]
+    store_tile<D>(dq, u, row_stride, lane, db, mfma16x16(read_tr<D>(kt, lane, db), dsAb, zero), scale);
+  }
+}
+
+template <int D>
+static hipError_t launch_t(const void* q, const void* k, const void* v, const void* dout,
+                           const TemporalTable& tab, int n_heads, float scale, void* o0, void* o1,
+                           void* o2, hipStream_t stream) {
+  const long long n_units = (long long)tab.pix_cu[tab.n] * n_heads;
+  if (n_units == 0) return hipSuccess;
+  const int grid = (int)((n_units + kTWaves - 1) / kTWaves);
+  const int tiles = dout ? 4 : 3;
+  const int lds = kTWaves * tiles * TCfg<D>::kTileBytes;
+  if (!dout) {
+    auto kern = tattn_fwd_kernel<D>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    kern<<<grid, kTWaves * 64, lds, stream>>>((const __bf16*)q, (const __bf16*)k, (const __bf16*)v,
+                                              (__bf16*)o0, tab, n_heads, scale * kLog2eT);
+  } else {
+    auto kern = tattn_bwd_kernel<D>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    kern<<<grid, kTWaves * 64, lds, stream>>>((const __bf16*)q, (const __bf16*)k, (const __bf16*)v,
+                                              (const __bf16*)dout, (__bf16*)o0, (__bf16*)o1, (__bf16*)o2,
+                                              tab, n_heads, scale, scale * kLog2eT);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_tattn_fwd(const void* q, const void* k, const void* v, const TemporalTable& tab,
+                            int n_heads, int head_dim, float scale, void* out, hipStream_t stream) {
+  if (head_dim == 128) return launch_t<128>(q, k, v, nullptr, tab, n_heads, scale, out, nullptr, nullptr, stream);
+  return launch_t<64>(q, k, v, nullptr, tab, n_heads, scale, out, nullptr, nullptr, stream);
+}
+
+hipError_t launch_tattn_bwd(const void* q, const void* k, const void* v, const void* dout,
+                            const TemporalTable& tab, int n_heads, int head_dim, float scale, void* dq,
+                            void* dk, void* dv, hipStream_t stream) {
+  if (head_dim == 128) return launch_t<128>(q, k, v, dout, tab, n_heads, scale, dq, dk, dv, stream);
+  return launch_t<64>(q, k, v, dout, tab, n_heads, scale, dq, dk, dv, stream);
+}
+
+}  // namespace vfm

@@ -72,6 +72,30 @@ int build_xseg_table(const int32_t* cu_q, const int32_t* cu_kv, int n_seqs, XSeg
   return VFM_OK;
 }
 
+// Temporal attention: per-clip grids must match the clip lengths and have at most
+// VFM_MAX_TEMPORAL frames.
+int build_temporal_table(const int32_t* thw, const int32_t* cu, int n_seqs, int total,
+                         vfm::TemporalTable* t) {
+  t->n = n_seqs;
+  int pix = 0;
+  for (int s = 0; s < n_seqs; ++s) {
+    const long long T = thw[3 * s], H = thw[3 * s + 1], W = thw[3 * s + 2];
+    const int len = cu[s + 1] - cu[s];
+    t->cu[s] = cu[s];
+    t->pix_cu[s] = pix;
+    if (len == 0 && T * H * W == 0 && T >= 0 && H >= 0 && W >= 0) { t->hw[s] = 1; continue; }
+    if (T <= 0 || H <= 0 || W <= 0 || T * H * W != len || T > VFM_MAX_TEMPORAL) return VFM_ERR_THW;
+    t->hw[s] = (int)(H * W);
+    pix += (int)(H * W);
+  }
+  for (int s = n_seqs; s <= VFM_MAX_SEQS; ++s) {
+    t->cu[s] = total;
+    t->pix_cu[s] = pix;
+    if (s < VFM_MAX_SEQS) t->hw[s] = 1;
+  }
+  return VFM_OK;
+}
+
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Shared by the RoPE entry points: sizes, split, theta, cu_seqlens and the per-clip grids;
@@ -116,7 +140,7 @@ const char* vfm_strerror(int status) {
     case VFM_ERR_NULL: return "a required pointer is NULL";
     case VFM_ERR_SHAPE: return "total_tokens, n_heads, head_dim (64 or 128), n_seqs (<= 256), scale or theta (> 0, finite) or eps (>= 0) out of range, or dx aliases x";
     case VFM_ERR_CU_SEQLENS: return "cu_seqlens must start at 0, be non-decreasing and end at total_tokens";
-    case VFM_ERR_THW: return "each clip needs positive T, H, W with T*H*W equal to its length";
+    case VFM_ERR_THW: return "each clip needs positive T, H, W with T*H*W equal to its length (temporal attention: T <= 16)";
     case VFM_ERR_SPLIT: return "dim_t + dim_h + dim_w must equal head_dim, each part even and >= 0";
     case VFM_ERR_DTYPE: return "unsupported element type (only bf16)";
     case VFM_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or smaller than vfm_attn_bwd_workspace_size()";
@@ -293,6 +317,48 @@ int vfm_xattn_bwd(const void* q, const void* k, const void* v, const void* out, 
   hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_q, n_heads, head_dim,
                                       scale, dq, dk, dv, delta, lse2, sentinel,
                                       static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+}
+
+int vfm_tattn_fwd(const void* q, const void* k, const void* v, const int32_t* thw,
+                  const int32_t* cu_seqlens, int n_seqs, int total_tokens, int n_heads, int head_dim,
+                  float scale, void* out, vfm_dtype dt, void* hip_stream) {
+  if (!q || !k || !v || !thw || !cu_seqlens || !out) return VFM_ERR_NULL;
+  if (dt != VFM_BF16) return VFM_ERR_DTYPE;
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  if (st) return st;
+  if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
+  st = check_cu(cu_seqlens, n_seqs, total_tokens);
+  if (st) return st;
+  vfm::TemporalTable tab;
+  st = build_temporal_table(thw, cu_seqlens, n_seqs, total_tokens, &tab);
+  if (st) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return VFM_ERR_ALIGN;
+  if (total_tokens == 0) return VFM_OK;
+  hipError_t e = vfm::launch_tattn_fwd(q, k, v, tab, n_heads, head_dim, scale, out,
+                                       static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+}
+
+int vfm_tattn_bwd(const void* q, const void* k, const void* v, const void* dout, const int32_t* thw,
+                  const int32_t* cu_seqlens, int n_seqs, int total_tokens, int n_heads, int head_dim,
+                  float scale, void* dq, void* dk, void* dv, vfm_dtype dt, void* hip_stream) {
+  if (!q || !k || !v || !dout || !thw || !cu_seqlens || !dq || !dk || !dv) return VFM_ERR_NULL;
+  if (dt != VFM_BF16) return VFM_ERR_DTYPE;
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  if (st) return st;
+  if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
+  st = check_cu(cu_seqlens, n_seqs, total_tokens);
+  if (st) return st;
+  vfm::TemporalTable tab;
+  st = build_temporal_table(thw, cu_seqlens, n_seqs, total_tokens, &tab);
+  if (st) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(dout) || !aligned16(dq) ||
+      !aligned16(dk) || !aligned16(dv))
+    return VFM_ERR_ALIGN;
+  if (total_tokens == 0) return VFM_OK;
+  hipError_t e = vfm::launch_tattn_bwd(q, k, v, dout, tab, n_heads, head_dim, scale, dq, dk, dv,
+                                       static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
 }
 

@@ -54,6 +54,14 @@ struct RopeTable {
   int w[VFM_MAX_SEQS];   // W
 };
 
+// Clip table for temporal attention: packed token and pixel offsets of every clip.
+struct TemporalTable {
+  int n;
+  int cu[VFM_MAX_SEQS + 1];      // first packed token of clip s
+  int pix_cu[VFM_MAX_SEQS + 1];  // pixels (H*W) of the clips before s
+  int hw[VFM_MAX_SEQS];          // H*W of clip s (1 for an empty clip)
+};
+
 // Work unit u = head * tiles_per_head + tile, units split into kNumXcd
 // contiguous chunks so that one XCD (one L2) walks the tiles of one head
 // together.  Returns false if this workgroup has nothing to do.
@@ -221,6 +229,13 @@ hipError_t launch_qknorm_rope3d_bwd(const void* x, const void* dy, void* dx, con
                                     float eps, float* dgain, const RopeTable& tab, int total,
                                     int n_heads, int head_dim, int dim_t, int dim_h, int dim_w,
                                     float theta, hipStream_t stream);
+
+hipError_t launch_tattn_fwd(const void* q, const void* k, const void* v, const TemporalTable& tab,
+                            int n_heads, int head_dim, float scale, void* out, hipStream_t stream);
+
+hipError_t launch_tattn_bwd(const void* q, const void* k, const void* v, const void* dout,
+                            const TemporalTable& tab, int n_heads, int head_dim, float scale, void* dq,
+                            void* dk, void* dv, hipStream_t stream);
 
 // Segs is SegTable (self-attention) or XSegTable (cross-attention); total_q is the number
 // of query tokens (rows of lse, Delta).

@@ -1,0 +1,82 @@
+"""GPU parity of temporal attention (one sequence per pixel across a clip's frames) against the
+fp64 oracle, through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import vfm_oracle as orc
+from paper_2503_12964_amd import workloads as W
+from tests import parity_utils as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _binding():
+    from paper_2503_12964_amd import binding
+    binding.load_library()
+    return binding
+
+
+CASES = {
+    # frame counts 1, 2, 7, 16 and an empty clip; pixel counts that are not multiples of the 4 waves
+    "t128": W.Workload("t128", ((16, 3, 5), (1, 2, 3), (0, 1, 1), (7, 1, 1), (2, 5, 5)), 3, 128, (32, 48, 48), seed=31),
+    "t64": W.Workload("t64", ((5, 3, 3), (16, 1, 2), (3, 4, 1)), 2, 64, (16, 24, 24), seed=32),
+}
+
+
+def _check(wl, gpu, dev, heads=None):
+    out, dq, dk, dv = gpu
+    hs = slice(None) if heads is None else list(heads)
+    host = {n: U.to_f64(t[:, hs, :]) for n, t in dev.items()}
+    o_ref = orc.temporal_attn_fwd(host["q"], host["k"], host["v"], wl.thw, wl.cu_seqlens, wl.scale)
+    g_ref = orc.temporal_attn_bwd(host["q"], host["k"], host["v"], host["dout"], wl.thw, wl.cu_seqlens, wl.scale)
+    o = U.to_f64(out[:, hs, :])
+    assert np.all(np.isfinite(o))
+    # at most 16 keys: outputs are O(|v|), so the absolute bound is taken relative to max(1, |ref|)
+    assert np.max(np.abs(o - o_ref) / np.maximum(1.0, np.abs(o_ref))) <= U.TOL_OUT_MAXABS
+    assert U.rel_rms(o, o_ref) <= U.TOL_OUT_RELRMS
+    for nm, g, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), g_ref):
+        got = U.to_f64(g[:, hs, :])
+        assert np.all(np.isfinite(got))
+        r = U.rel_rms(got, ref)
+        assert r <= U.TOL_GRAD_RELRMS, (nm, r)
+
+
+def _run(b, wl):
+    inp = W.make_inputs(wl)
+    dev = {n: U.to_device(inp[n]) for n in ("q", "k", "v", "dout")}
+    out = b.vfm_tattn_fwd(dev["q"], dev["k"], dev["v"], wl.thw, wl.cu_seqlens, wl.scale)
+    dq, dk, dv = b.vfm_tattn_bwd(dev["q"], dev["k"], dev["v"], dev["dout"], wl.thw, wl.cu_seqlens, wl.scale)
+    return dev, (out, dq, dk, dv)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_temporal_attention_matches_oracle(name):
+    wl = CASES[name]
+    dev, gpu = _run(_binding(), wl)
+    _check(wl, gpu, dev)
+
+
+def test_single_frame_clip_copies_values_and_has_zero_qk_gradients():
+    wl = CASES["t128"]
+    dev, (out, dq, dk, dv) = _run(_binding(), wl)
+    a, b = int(wl.cu_seqlens[1]), int(wl.cu_seqlens[2])      # the (1,2,3) clip
+    assert np.array_equal(U.to_bits(out[a:b]), U.to_bits(dev["v"][a:b]))
+    assert not np.any(U.to_f64(dq[a:b])) and not np.any(U.to_f64(dk[a:b]))
+    assert np.array_equal(U.to_bits(dv[a:b]), U.to_bits(dev["dout"][a:b]))
+
+
+def test_more_than_sixteen_frames_is_an_error():
+    import torch
+    b = _binding()
+    x = torch.zeros((17 * 4, 1, 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(b.VfmError):
+        b.vfm_tattn_fwd(x, x, x, [(17, 2, 2)], [0, 68], 0.125)
+
+
+def test_full_size_c4_every_element():
+    """The 56,320-token latent (16 frames x 3,520 pixels), 32 heads: every element of out, dq,
+    dk, dv against the oracle, four heads at a time."""
+    wl = W.WORKLOADS["C4"]
+    dev, gpu = _run(_binding(), wl)
+    for h0 in range(0, wl.n_heads, 4):
+        _check(wl, gpu, dev, heads=range(h0, h0 + 4))
