@@ -137,6 +137,25 @@ def test_cross_attention_argument_errors(lib):
     assert xb(ws_bytes=16) == 7
 
 
+def test_temporal_attention_argument_errors(lib):
+    def tf(thw, cu, total, q=FAKE, out=FAKE, dt=0, scale=0.1):
+        a, pa = _i32(thw)
+        b, pb = _i32(cu)
+        return lib.vfm_tattn_fwd(q, FAKE, FAKE, pa, pb, len(cu) - 1, total, 2, 128, scale, out, dt, None)
+    assert tf([2, 2, 2], [0, 8], 8, out=None) == 1
+    assert tf([17, 1, 1], [0, 17], 17) == 4                     # more than VFM_MAX_TEMPORAL frames
+    assert tf([2, 2, 3], [0, 8], 8) == 4
+    assert tf([2, 2, 2], [0, 9], 8) == 3
+    assert tf([2, 2, 2], [0, 8], 8, dt=1) == 6
+    assert tf([2, 2, 2], [0, 8], 8, q=ODD) == 9
+    assert tf([2, 2, 2], [0, 8], 8, scale=float("inf")) == 2
+    assert tf([0, 0, 0], [0, 0], 0) == 0
+    a, pa = _i32([2, 2, 2])
+    b, pb = _i32([0, 8])
+    assert lib.vfm_tattn_bwd(FAKE, FAKE, FAKE, FAKE, pa, pb, 1, 8, 2, 128, 0.1, FAKE, None, FAKE, 0, None) == 1
+    assert lib.vfm_tattn_bwd(FAKE, FAKE, FAKE, FAKE, pa, pb, 1, 8, 2, 96, 0.1, FAKE, FAKE, FAKE, 0, None) == 2
+
+
 def test_tensors_beyond_32bit_byte_offsets_are_rejected(lib):
     # 131072 tokens x 128 heads x 128 x 2 bytes = 4 GiB: the kernels address tensors with 32-bit byte offsets
     arr, p = _i32([0, 131072])
