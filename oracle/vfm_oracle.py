@@ -62,6 +62,8 @@ __all__ = [
     "xattn_bwd",
     "temporal_attn_fwd",
     "temporal_attn_bwd",
+    "fp8_e4m3_decode",
+    "fp8_e4m3_encode",
     "attn_fwd_rows",
     "attn_bwd_rows",
     "attn_bwd_cols",
@@ -381,6 +383,35 @@ def temporal_attn_bwd(q, k, v, dout, thw, cu_seqlens, scale: float):
         dq[rows] = scale * np.einsum("phij,pjhd->pihd", dS, K)
         dk[rows] = scale * np.einsum("phij,pihd->pjhd", dS, Q)
     return dq, dk, dv
+
+
+def fp8_e4m3_decode(codes) -> np.ndarray:
+    """Values of 8-bit floating point codes in the E4M3 format of the OCP 8-bit floating
+    point specification (the format of FP8 attention, Section 5.2): 1 sign, 4 exponent
+    (bias 7), 3 mantissa bits; no infinities; exponent and mantissa all ones is NaN;
+    exponent 0 is subnormal, (m/8) * 2**-6.  Largest finite value 448.  Returns fp64."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    sign = np.where(c & 0x80, -1.0, 1.0)
+    e = (c >> 3) & 0xF
+    m = (c & 0x7).astype(np.float64)
+    val = np.where(e == 0, (m / 8.0) * 2.0 ** -6, (1.0 + m / 8.0) * 2.0 ** (e - 7.0))
+    val = np.where((c & 0x7F) == 0x7F, np.nan, val)
+    return sign * val
+
+
+def fp8_e4m3_encode(x) -> np.ndarray:
+    """Nearest E4M3 code of each value, ties to the even code, magnitudes beyond 448
+    saturating to 448 (the quantiser clamps before it rounds).  NaN maps to 0x7F."""
+    x = np.asarray(x, dtype=np.float64)
+    grid = fp8_e4m3_decode(np.arange(0x7F, dtype=np.uint8))          # 0 .. 448, increasing
+    a = np.minimum(np.abs(x), 448.0)
+    hi = np.clip(np.searchsorted(grid, a, side="left"), 0, 0x7E)     # first code with value >= a
+    lo = np.maximum(hi - 1, 0)
+    d_hi, d_lo = grid[hi] - a, a - grid[lo]
+    pick_lo = (d_lo < d_hi) | ((d_lo == d_hi) & (lo % 2 == 0))
+    code = np.where(pick_lo, lo, hi).astype(np.uint8)
+    code = np.where(np.signbit(x), code | 0x80, code).astype(np.uint8)
+    return np.where(np.isnan(x), np.uint8(0x7F), code).astype(np.uint8)
 
 
 def _segment_of(cu: np.ndarray, n: int):
