@@ -13,8 +13,9 @@ workload is the 720p-class 121-frame latent (T,H,W = 16,44,80 -> 56,320 tokens,
 frame.  --workload NAME-cross runs cross-attention from the workload's video tokens to a
 512-token text embedding per clip (Section 4.2), forward + backward, no RoPE.
 --workload NAME-temporal runs temporal attention (one sequence per pixel across the clip's
-frames, Section 4.6), forward + backward; it is HBM-bound.  All three are further workloads,
-not the headline.
+frames, Section 4.6), forward + backward; it is HBM-bound.  --workload NAME-fp8 runs the FP8
+(E4M3) attention forward of Section 5.2: a step is vfm_fp8_pack + vfm_attn_fwd_fp8.  All four
+are further workloads, not the headline.
 
 FLOP convention (algorithmic, block-diagonal pairs only): forward 4*D and
 backward 10*D flops per (query, key) pair per head.
@@ -215,6 +216,54 @@ def _bench_temporal(args, wl) -> int:
     return 0
 
 
+def _bench_fp8(args, wl) -> int:
+    """FP8 forward workload: a step quantises and packs q, k, v, then runs vfm_attn_fwd_fp8."""
+    import torch
+    from paper_2503_12964_amd import binding as B
+    t = _device_tensors(wl)
+    q, k, v = t["q"], t["k"], t["v"]
+    cu = wl.cu_seqlens
+    scales = (32.0, 64.0, 16.0)
+    q8, k8, vT8 = B.vfm_fp8_pack(q, k, v, cu, *scales)
+    out = torch.empty_like(q)
+    lse = torch.empty((wl.n_heads, wl.total_tokens), dtype=torch.float32, device="cuda")
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        B.vfm_fp8_pack(q, k, v, cu, *scales, q8=q8, k8=k8, vT8=vT8)
+        if ev: ev[1].record()
+        B.vfm_attn_fwd_fp8(q8, k8, vT8, cu, wl.n_heads, wl.head_dim, wl.scale, *scales, out=out, lse=lse)
+        if ev: ev[2].record()
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_pack = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
+    ms_fwd = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
+    f_fwd = wl.flops(backward=False)
+    achieved = f_fwd / (ms_fwd * 1e-3) / 1e12
+    tensor_bytes = wl.total_tokens * wl.n_heads * wl.head_dim * 2
+    print(json.dumps({
+        "metric": f"FP8 attention forward TFLOP/s, workload {args.workload}",
+        "value": f_fwd / (ms_step * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "fp8", "data": "synthetic",
+        "config": {"workload": f"{wl.name}-fp8: grids {list(wl.grids)} -> {wl.total_tokens} tokens, {wl.n_heads} heads, "
+                               f"head_dim {wl.head_dim}, E4M3 operands and probabilities, pack + forward",
+                   "flops_per_step": f_fwd},
+        "breakdown": {"pack_ms": ms_pack, "fwd_ms": ms_fwd, "fwd_tflops": achieved,
+                      "pack_gbs": 4.5 * tensor_bytes / (ms_pack * 1e-3) / 1e9},
+        "roofline": {"bound": "mfma", "kernel": "attn_fwd_fp8_kernel", "achieved": achieved, "peak": 5000.0,
+                     "unit": "TFLOP/s", "frac": achieved / 5000.0, "traffic": None, "ms": ms_fwd,
+                     "note": "vfm_attn_fwd_fp8 call; 4*D flops/pair/head against the published dense fp8 peak"}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -254,6 +303,8 @@ def main() -> int:
         return 0
     if args.workload.endswith("-cross"):
         return _bench_cross(args, W.WORKLOADS[args.workload[:-len("-cross")]])
+    if args.workload.endswith("-fp8"):
+        return _bench_fp8(args, W.WORKLOADS[args.workload[:-len("-fp8")]])
     if args.workload.endswith("-temporal"):
         return _bench_temporal(args, W.WORKLOADS[args.workload[:-len("-temporal")]])
     spatial = args.workload.endswith("-spatial")

@@ -231,6 +231,54 @@ VFM_API int vfm_tattn_bwd(const void* q, const void* k, const void* v, const voi
                   int total_tokens, int n_heads, int head_dim, float scale,
                   void* dq, void* dk, void* dv, vfm_dtype dt, void* hip_stream);
 
+/*
+ * FP8 attention forward (Section 5.2 reports FP8 multi-head attention for
+ * inference).  Operands are 8-bit floats in the E4M3 format of the OCP 8-bit
+ * floating point specification, prepared once per (q, k, v) by vfm_fp8_pack:
+ *   x8 = round_to_nearest_even(clamp(x * x_scale, -448, 448))
+ * with one caller-chosen scale per tensor, into three packed buffers (per head h;
+ * a "unit" is 64 consecutive keys of one clip, zero padded at the clip's end;
+ * units are numbered clip by clip in packed order, clip s owning
+ * ceil(len_s / 64) of them):
+ *   q8  [n_heads][total_tokens][head_dim]
+ *   k8  [n_heads][units][64][head_dim]: key row r of a unit holds its 16-byte
+ *       chunk c at chunk position c ^ ((r >> 1) & 7) (head_dim 128) or
+ *       c ^ ((r >> 2) & 3) (head_dim 64)
+ *   vT8 [n_heads][units][head_dim][64]: row d holds, at 16-byte chunk position
+ *       c ^ ((d >> 2) & 3), the logical chunk c of a 64-byte row whose byte
+ *       32 g + j (g < 2, j < 32) is key  32 (j / 16) + 8 ((j % 16) / 4) + 4 g + j % 4
+ *       of the unit.
+ * (The chunk permutations are the kernels' LDS bank swizzle, the byte order is
+ * the order the matrix instruction consumes keys in; callers treat the buffers
+ * as opaque.)  vfm_fp8_pack_sizes returns the three sizes in bytes.
+ * Errors: NULL, SHAPE (incl. a packed buffer beyond 4 GiB), CU_SEQLENS, DTYPE,
+ * ALIGN, LAUNCH.
+ */
+VFM_API int vfm_fp8_pack_sizes(const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                       int n_heads, int head_dim,
+                       size_t* q8_bytes, size_t* k8_bytes, size_t* vT8_bytes);
+VFM_API int vfm_fp8_pack(const void* q, const void* k, const void* v,
+                 const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                 int n_heads, int head_dim, float q_scale, float k_scale, float v_scale,
+                 void* q8, void* k8, void* vT8, vfm_dtype dt, void* hip_stream);
+
+/*
+ * out, lse as vfm_attn_fwd, computed from the packed E4M3 operands with FP8
+ * matrix instructions and fp32 accumulation:
+ *     S_ij = scale / (q_scale k_scale) * sum_d q8[i,d] k8[j,d]
+ *     out_i = (1 / v_scale) * sum_j softmax_j(S_ij) v8[j,:]
+ * The probabilities are rounded to E4M3 (3 mantissa bits) before the second
+ * product, so out carries a relative error of a few percent against the exact
+ * result on the same quantised operands; lse is accumulated in fp32.  out: bf16
+ * [total_tokens, n_heads, head_dim]; lse: fp32 [n_heads, total_tokens].
+ * Errors: NULL, SHAPE, CU_SEQLENS, ALIGN, LAUNCH.
+ */
+VFM_API int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8,
+                     const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                     int n_heads, int head_dim, float scale,
+                     float q_scale, float k_scale, float v_scale,
+                     void* out, float* lse, void* hip_stream);
+
 /* Static, human-readable text for a vfm_status. */
 VFM_API const char* vfm_strerror(int status);
 

@@ -22,7 +22,7 @@ VFM_F32 = 1
 VFM_MAX_SEQS = 256
 
 EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_xattn_fwd", "vfm_xattn_bwd", "vfm_tattn_fwd", "vfm_tattn_bwd",
-           "vfm_strerror")
+           "vfm_fp8_pack_sizes", "vfm_fp8_pack", "vfm_attn_fwd_fp8", "vfm_strerror")
 
 _lib = None
 
@@ -77,6 +77,15 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.vfm_tattn_bwd.restype = c_int
     lib.vfm_tattn_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, p_i32, p_i32, c_int, c_int, c_int, c_int,
                                   c_float, c_void_p, c_void_p, c_void_p, c_int, c_void_p]
+    p_size = ctypes.POINTER(c_size_t)
+    lib.vfm_fp8_pack_sizes.restype = c_int
+    lib.vfm_fp8_pack_sizes.argtypes = [p_i32, c_int, c_int, c_int, c_int, p_size, p_size, p_size]
+    lib.vfm_fp8_pack.restype = c_int
+    lib.vfm_fp8_pack.argtypes = [c_void_p, c_void_p, c_void_p, p_i32, c_int, c_int, c_int, c_int, c_float, c_float,
+                                 c_float, c_void_p, c_void_p, c_void_p, c_int, c_void_p]
+    lib.vfm_attn_fwd_fp8.restype = c_int
+    lib.vfm_attn_fwd_fp8.argtypes = [c_void_p, c_void_p, c_void_p, p_i32, c_int, c_int, c_int, c_int, c_float,
+                                     c_float, c_float, c_float, c_void_p, c_void_p, c_void_p]
     lib.vfm_strerror.restype = ctypes.c_char_p
     lib.vfm_strerror.argtypes = [c_int]
     if path == LIB_PATH:
@@ -279,3 +288,47 @@ def vfm_tattn_bwd(q, k, v, dout, thw, cu_seqlens, scale: float, dq=None, dk=None
                              int(cu.size - 1), int(total), int(heads), int(hd), float(scale), _dev(dq, "dq"),
                              _dev(dk, "dk"), _dev(dv, "dv"), _dtype_code(q), _stream_ptr(stream)))
     return dq, dk, dv
+
+
+def vfm_fp8_pack_sizes(cu_seqlens, n_heads: int, head_dim: int) -> Tuple[int, int, int]:
+    """Bytes of the packed q8, k8 and vT8 buffers for these clips."""
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib.vfm_fp8_pack_sizes(_i32_ptr(cu), int(cu.size - 1), int(cu[-1]), int(n_heads), int(head_dim),
+                                  ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+    return int(a.value), int(b.value), int(c.value)
+
+
+def vfm_fp8_pack(q, k, v, cu_seqlens, q_scale: float, k_scale: float, v_scale: float, q8=None, k8=None,
+                 vT8=None, stream=None) -> Tuple:
+    """Quantise bf16 q, k, v to E4M3 in the packed layout vfm_attn_fwd_fp8 reads (uint8 device buffers)."""
+    import torch
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    total, heads, hd = q.shape
+    nq, nk, nv = vfm_fp8_pack_sizes(cu, heads, hd)
+    q8 = torch.empty(max(nq, 16), dtype=torch.uint8, device=q.device) if q8 is None else q8
+    k8 = torch.empty(max(nk, 16), dtype=torch.uint8, device=q.device) if k8 is None else k8
+    vT8 = torch.empty(max(nv, 16), dtype=torch.uint8, device=q.device) if vT8 is None else vT8
+    _check(lib.vfm_fp8_pack(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _i32_ptr(cu), int(cu.size - 1), int(total),
+                            int(heads), int(hd), float(q_scale), float(k_scale), float(v_scale), _dev(q8, "q8"),
+                            _dev(k8, "k8"), _dev(vT8, "vT8"), _dtype_code(q), _stream_ptr(stream)))
+    return q8, k8, vT8
+
+
+def vfm_attn_fwd_fp8(q8, k8, vT8, cu_seqlens, n_heads: int, head_dim: int, scale: float, q_scale: float,
+                     k_scale: float, v_scale: float, out=None, lse=None, stream=None) -> Tuple:
+    """FP8 attention forward on packed operands: out (bf16 [total, heads, head_dim]) and lse (fp32)."""
+    import torch
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    total = int(cu[-1])
+    if out is None:
+        out = torch.empty((total, n_heads, head_dim), dtype=torch.bfloat16, device=q8.device)
+    if lse is None:
+        lse = torch.empty((n_heads, total), dtype=torch.float32, device=q8.device)
+    _check(lib.vfm_attn_fwd_fp8(_dev(q8, "q8"), _dev(k8, "k8"), _dev(vT8, "vT8"), _i32_ptr(cu), int(cu.size - 1),
+                                total, int(n_heads), int(head_dim), float(scale), float(q_scale), float(k_scale),
+                                float(v_scale), _dev(out, "out"), _dev(lse, "lse"), _stream_ptr(stream)))
+    return out, lse

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libvfm.so")
 CEILING_PATH = os.path.join(HERE, "mfma_ceiling")   # standalone matrix-pipe ceiling measurement
-SOURCES = ["vfm_api.hip", "rope3d.hip", "qknorm_rope3d.hip", "attn_fwd.hip", "attn_bwd.hip", "tattn.hip"]
+SOURCES = ["vfm_api.hip", "rope3d.hip", "qknorm_rope3d.hip", "attn_fwd.hip", "attn_bwd.hip", "tattn.hip", "attn_fp8.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

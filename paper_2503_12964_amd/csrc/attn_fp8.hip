@@ -1,0 +1,397 @@
+// FP8 (E4M3) attention forward for gfx950, and the packing pass that prepares its operands.
+//
+// v_mfma_f32_32x32x64_f8f6f4 contracts 64 fp8 values per instruction (a lane holds 32 bytes of
+// one operand row) at about twice the bf16 rate, so the kernel works in units of 64 keys:
+//     S^T[64 keys, 32 q] = K Q^T      two 32-key tiles x (D/64) instructions, A = K rows, B = Q rows
+//     O^T[D, 32 q]      += V^T P^T    D/32 instructions, A = rows of V^T, B = P (fp8) from registers
+// The contraction slots of the second product are bound to keys in the order the first
+// product's accumulators hold them, as in the bf16 kernel; here that order is baked into the
+// packed V^T buffer, so each lane's 32 keys are 32 contiguous bytes.
+//
+// Packed operand layout (written by vfm_fp8_pack, all fp8 bytes, per head h):
+//   q8  [H][total][D]                       plain rows
+//   k8  [H][units][64 keys][D]              one unit = 64 consecutive keys of ONE clip (zero padded
+//   vT8 [H][units][D][64 keys, permuted]    at the clip's end), contiguous, with the LDS bank
+//                                           swizzle already applied to its 16-byte chunks
+// so a unit is staged by a linear 8 KB (D = 128) direct-to-LDS copy with no address arithmetic,
+// and both operand reads are conflict-free 16-byte LDS reads.
+//
+// Softmax as in the bf16 kernel (lazy reference point, overflow detected on the row sums),
+// except that the exponentials are scaled by 2^6 before they are rounded to E4M3, which keeps
+// small probabilities out of the subnormal range (P <= 448 * 2^-6 = 7 relative to the reference).
+#include "vfm_common.h"
+
+namespace vfm {
+
+namespace {
+
+constexpr int kF8Unit = 64;
+constexpr int kF8Waves = 8;
+constexpr int kF8Rows = kF8Waves * 32;   // query rows per workgroup
+constexpr int kF8Ring = 3;
+constexpr float kF8Log2e = 1.4426950408889634f;
+constexpr float kF8Ln2 = 0.6931471805599453f;
+constexpr float kF8PShift = 6.0f;        // P is stored as 2^6 P
+constexpr float kF8SafeSum = 448.0f;     // largest finite E4M3: bounds every scaled P of the unit
+constexpr float kF8Max = 448.0f;
+
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+
+// LDS / packed-buffer swizzle of the 16-byte chunk index
+template <int D>
+__device__ __host__ __forceinline__ int k_swz(int key_row) {      // K unit: rows of D bytes
+  return D == 128 ? ((key_row >> 1) & 7) : ((key_row >> 2) & 3);
+}
+__device__ __host__ __forceinline__ int v_swz(int d_row) { return (d_row >> 2) & 3; }   // V^T unit: rows of 64 bytes
+
+__device__ __forceinline__ float clamp448(float x) { return fminf(fmaxf(x, -kF8Max), kF8Max); }
+
+// four floats -> four E4M3 bytes (round to nearest even; the inputs are already within +-448)
+__device__ __forceinline__ uint32_t pack_fp8x4(float a, float b, float c, float d) {
+  int v = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
+  v = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, v, true);
+  return (uint32_t)v;
+}
+
+// 16 bf16 values (two 16-byte words) -> 16 scaled, clamped E4M3 bytes
+__device__ __forceinline__ u32x4 quantize16(u32x4 lo, u32x4 hi, float scale) {
+  u32x4 o;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const u32x4& src = w < 2 ? lo : hi;
+    const uint32_t a = src[(2 * w) & 3], b = src[(2 * w + 1) & 3];
+    o[w] = pack_fp8x4(clamp448(__builtin_bit_cast(float, a << 16) * scale),
+                      clamp448(__builtin_bit_cast(float, a & 0xffff0000u) * scale),
+                      clamp448(__builtin_bit_cast(float, b << 16) * scale),
+                      clamp448(__builtin_bit_cast(float, b & 0xffff0000u) * scale));
+  }
+  return o;
+}
+
+__device__ __forceinline__ f32x16 mfma_f8(i32x8 a, i32x8 b, f32x16 c) {
+  // formats 0/0 = E4M3 for both operands; block scales 2^0
+  return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0x7f7f7f7f, 0, 0x7f7f7f7f);
+}
+
+__device__ __forceinline__ i32x8 lds_read_32b(const char* base, int off0, int off1) {
+  const u32x4 lo = *reinterpret_cast<const u32x4*>(base + off0);
+  const u32x4 hi = *reinterpret_cast<const u32x4*>(base + off1);
+  i32x8 r = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+  return r;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- packing
+template <int D>
+__global__ __launch_bounds__(256) void fp8_pack_q_kernel(const u32x4* __restrict__ q,
+                                                         u32x4* __restrict__ q8, float scale,
+                                                         int total, int n_heads) {
+  constexpr int CPR = D / 16;   // 16-byte output chunks per row
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)total * n_heads * CPR) return;
+  const int chunk = (int)(idx % CPR);
+  const long long row = idx / CPR;          // token * n_heads + head
+  const int head = (int)(row % n_heads);
+  const long long tok = row / n_heads;
+  const u32x4* src = q + row * (D / 8) + chunk * 2;
+  q8[((long long)head * total + tok) * CPR + chunk] = quantize16(src[0], src[1], scale);
+}
+
+// One workgroup packs one (unit, head): 64 keys of k into the swizzled K unit and the same 64
+// rows of v, transposed and key-permuted, into the V^T unit.
+template <int D>
+__global__ __launch_bounds__(256) void fp8_pack_kv_kernel(const u32x4* __restrict__ k,
+                                                          const u32x4* __restrict__ v,
+                                                          u32x4* __restrict__ k8, u32x4* __restrict__ vT8,
+                                                          float k_scale, float v_scale,
+                                                          const Fp8ClipTable clips, int n_units,
+                                                          int n_heads) {
+  constexpr int CPR = D / 16;
+  __shared__ __attribute__((aligned(16))) unsigned char vb[kF8Unit][D + 16];   // padded rows
+  const int unit = blockIdx.x, head = blockIdx.y;
+  int lo = 0, hi = clips.n;               // last clip whose first unit is <= unit (skips empty clips)
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (clips.unit0[mid] <= unit) lo = mid; else hi = mid;
+  }
+  const int key0 = clips.cu[lo] + (unit - clips.unit0[lo]) * kF8Unit;
+  const int valid = min(kF8Unit, clips.cu[lo + 1] - key0);
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  u32x4* kdst = k8 + ((size_t)head * n_units + unit) * (kF8Unit * CPR);
+  for (int oc = threadIdx.x; oc < kF8Unit * CPR; oc += 256) {
+    const int r = oc / CPR, pc = oc % CPR;
+    const int lc = pc ^ k_swz<D>(r);
+    u32x4 kq = zero, vq = zero;
+    if (r < valid) {
+      const size_t src = ((size_t)(key0 + r) * n_heads + head) * (D / 8) + lc * 2;
+      kq = quantize16(k[src], k[src + 1], k_scale);
+      const size_t srcv = ((size_t)(key0 + r) * n_heads + head) * (D / 8) + pc * 2;
+      vq = quantize16(v[srcv], v[srcv + 1], v_scale);
+    }
+    kdst[oc] = kq;
+    *reinterpret_cast<u32x4*>(&vb[r][pc * 16]) = vq;     // V staged unswizzled: vb[key][d]
+  }
+  __syncthreads();
+  u32x4* vdst = vT8 + ((size_t)head * n_units + unit) * (D * 4);
+  for (int oc = threadIdx.x; oc < D * 4; oc += 256) {
+    const int d = oc >> 2, pc = oc & 3;
+    const int lc = pc ^ v_swz(d);
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int b = lc * 16 + i;              // logical byte of the row: lane group g, slot j
+      const int g = b >> 5, j = b & 31;
+      const int key = 32 * (j >> 4) + 8 * ((j & 15) >> 2) + 4 * g + (j & 3);
+      const uint32_t byte = vb[key][d];
+      w[i >> 2] = (i & 3) == 0 ? byte : (w[i >> 2] | (byte << (8 * (i & 3))));
+    }
+    const u32x4 o = {w[0], w[1], w[2], w[3]};
+    vdst[oc] = o;
+  }
+}
+
+// ---------------------------------------------------------------- forward
+template <int D>
+__global__ __launch_bounds__(kF8Waves * 64, 2)
+void attn_fwd_fp8_kernel(const unsigned char* __restrict__ q8, const unsigned char* __restrict__ k8,
+                         const unsigned char* __restrict__ vT8, __bf16* __restrict__ out,
+                         float* __restrict__ lse, const Fp8SegTable segs, const UnitMap um, int total,
+                         int n_heads, int n_units, float scale_log2, float out_scale) {
+  constexpr int KS = D / 64;            // instructions per 32-key score tile
+  constexpr int DB = D / 32;            // 32-row blocks of O^T
+  constexpr int UB = kF8Unit * D;       // bytes of a K unit and of a V^T unit
+  constexpr int kLoadWaves = UB / 1024; // waves that take part in staging a unit (1 KB each)
+
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // ring of (K unit, V^T unit)
+
+  int head, tile;
+  if (!map_unit(um, blockIdx.x, head, tile)) return;
+  int seq, tq;
+  locate_tile<false>(segs, kF8Rows, tile, seq, tq);
+  const int seg_a = segs.start[seq], seg_b = seg_a + segs.len[seq];
+  const int q0 = seg_a + tq * kF8Rows;
+  const int unit0 = segs.unit0[seq];
+  const int n_u = (segs.len[seq] + kF8Unit - 1) / kF8Unit;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int c = lane & 31, g = lane >> 5;
+
+  // ---- Q operand: row of this lane's query, bytes ks*64 + 32g .. +31
+  const int qrow = q0 + wave * 32 + c;
+  i32x8 qreg[KS];
+  {
+    const unsigned char* qp = q8 + ((size_t)head * total + min(qrow, seg_b - 1)) * D + 32 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const u32x4 lo = *reinterpret_cast<const u32x4*>(qp + ks * 64);
+      const u32x4 hi = *reinterpret_cast<const u32x4*>(qp + ks * 64 + 16);
+      qreg[ks] = i32x8{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+    }
+  }
+
+  // ---- staging: a unit is UB contiguous bytes in each packed buffer; wave w copies bytes
+  // [w*1024, w*1024 + 1024) of it, lane L its 16-byte chunk L.  Units past the clip's last one
+  // re-request the last unit (never used) so every wave keeps the same number of loads in flight.
+  const unsigned char* kbase = k8 + (size_t)head * n_units * UB;
+  const unsigned char* vbase = vT8 + (size_t)head * n_units * UB;
+  const uint32_t lane_off = (uint32_t)(wave * 1024 + lane * 16);
+  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(lds_addr_of(smem) + wave * 1024);
+  auto issue_unit = [&](int u, int slot) {
+    if (wave < kLoadWaves) {
+      const uint32_t off = (uint32_t)(unit0 + min(u, n_u - 1)) * UB + lane_off;
+      lds_dma16(kbase, off, wave_lds + slot * 2 * UB);
+      lds_dma16(vbase, off, wave_lds + slot * 2 * UB + UB);
+    }
+  };
+
+  // ---- per-lane LDS offsets
+  // K tile t, step ks: row 32t + c, logical chunks ks*4 + 2g and +1
+  int koff[2][KS][2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int r = 32 * t + c;
+        koff[t][ks][h] = r * D + (((ks * 4 + 2 * g + h) ^ k_swz<D>(r)) << 4);
+      }
+  // V^T block db: row db*32 + c, logical chunks 2g and 2g+1
+  int voff[DB][2];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int d = db * 32 + c;
+      voff[db][h] = d * 64 + (((2 * g + h) ^ v_swz(d)) << 4);
+    }
+
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  f32x16 oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) oacc[db] = zero16;
+  float m_ref = 0.f, l_run = 0.f;     // reference point (log2 units, shifted) and running sum of scaled P
+
+  issue_unit(0, 0);
+  issue_unit(1, 1);
+
+  for (int u = 0; u < n_u; ++u) {
+    const int slot = u % kF8Ring;
+    wait_vmcnt<2>();          // unit u has landed (unit u+1 may still be in flight) ...
+    __syncthreads();          // ... for every wave, and every wave is done with unit u-1
+    issue_unit(u + 2, (u + 2) % kF8Ring);
+    const char* kt = smem + slot * 2 * UB;
+    const char* vt = kt + UB;
+
+    // ---- S^T for the unit's two 32-key tiles
+    f32x16 s[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        s[t] = mfma_f8(lds_read_32b(kt, koff[t][ks][0], koff[t][ks][1]), qreg[ks], ks == 0 ? zero16 : s[t]);
+    // V^T operands requested in the shadow of the score instructions
+    i32x8 va[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) va[db] = lds_read_32b(vt, voff[db][0], voff[db][1]);
+
+    const int j0 = seg_a + u * kF8Unit;
+    if (j0 + kF8Unit > seg_b) {       // keys past the clip end (last unit only)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (j0 + 32 * t + 8 * (r >> 2) + 4 * g + (r & 3) >= seg_b) s[t][r] = -INFINITY;
+    }
+    if (u == 0) {   // first reference point: the exact row max of unit 0
+      float mx = s[0][0];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
+      m_ref = pair_max(mx) * scale_log2 - kF8PShift;
+    }
+
+    // ---- scaled exponentials against the current reference, packed to E4M3
+    float p[2][16];
+    float lsum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        p[t][r] = fast_exp2(s[t][r] * scale_log2 - m_ref);
+        lsum += p[t][r];
+      }
+    // every scaled P <= lsum, so lsum <= 448 keeps all of them finite in E4M3 (overflow fails too)
+    if (__builtin_amdgcn_ballot_w64(!(lsum <= kF8SafeSum)) != 0) {
+      // rare: move the reference to the true running max, redo the unit, rescale sums and O
+      float mx = s[0][0];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
+      const float m_new = fmaxf(m_ref, pair_max(mx) * scale_log2 - kF8PShift);
+      const float alpha = fast_exp2(m_ref - m_new);
+      m_ref = m_new;
+      lsum = 0.f;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          p[t][r] = fast_exp2(s[t][r] * scale_log2 - m_new);
+          lsum += p[t][r];
+        }
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    }
+    l_run += lsum;
+    i32x8 pb;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+        pb[4 * t + w] = (int)pack_fp8x4(p[t][4 * w], p[t][4 * w + 1], p[t][4 * w + 2], p[t][4 * w + 3]);
+
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int db = 0; db < DB; ++db) oacc[db] = mfma_f8(va[db], pb, oacc[db]);
+  }
+  wait_vmcnt<0>();   // no load may still be writing LDS when the workgroup ends
+
+  // ---- epilogue: out = O * (v dequantisation scale) / l, lse in natural-log units
+  const float l_tot = pair_sum(l_run);
+  const float inv = out_scale / l_tot;
+  if (qrow < seg_b) {
+    __bf16* op = out + ((size_t)qrow * n_heads + head) * D + 4 * g;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        f32x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = oacc[db][q4 * 4 + e] * inv;
+        *reinterpret_cast<bf16x4*>(op + db * 32 + q4 * 8) = to_bf16x4(o);
+      }
+    if (g == 0) lse[(size_t)head * total + qrow] = (m_ref + __log2f(l_tot)) * kF8Ln2;
+  }
+}
+
+// ---------------------------------------------------------------- launchers
+template <int D>
+static hipError_t pack_d(const void* q, const void* k, const void* v, const Fp8ClipTable& clips,
+                         int n_units, int total, int n_heads, float qs, float ks, float vs, void* q8,
+                         void* k8, void* vT8, hipStream_t stream) {
+  const long long chunks = (long long)total * n_heads * (D / 16);
+  fp8_pack_q_kernel<D><<<(int)((chunks + 255) / 256), 256, 0, stream>>>((const u32x4*)q, (u32x4*)q8, qs, total,
+                                                                        n_heads);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  fp8_pack_kv_kernel<D><<<dim3(n_units, n_heads), 256, 0, stream>>>(
+      (const u32x4*)k, (const u32x4*)v, (u32x4*)k8, (u32x4*)vT8, ks, vs, clips, n_units, n_heads);
+  return hipGetLastError();
+}
+
+hipError_t launch_fp8_pack(const void* q, const void* k, const void* v, const Fp8ClipTable& clips,
+                           int n_units, int total, int n_heads, int head_dim, float qs, float ks,
+                           float vs, void* q8, void* k8, void* vT8, hipStream_t stream) {
+  if (total == 0 || n_units == 0) return hipSuccess;
+  if (head_dim == 128) return pack_d<128>(q, k, v, clips, n_units, total, n_heads, qs, ks, vs, q8, k8, vT8, stream);
+  return pack_d<64>(q, k, v, clips, n_units, total, n_heads, qs, ks, vs, q8, k8, vT8, stream);
+}
+
+template <int D>
+static hipError_t fwd_fp8_d(const void* q8, const void* k8, const void* vT8, const Fp8SegTable& segs,
+                            int n_units, int total, int n_heads, float scale_log2, float out_scale,
+                            void* out, float* lse, hipStream_t stream) {
+  int tiles = 0;
+  for (int s = 0; s < segs.n; ++s) tiles += (segs.len[s] + kF8Rows - 1) / kF8Rows;
+  if (tiles == 0) return hipSuccess;
+  UnitMap um;
+  um.tiles_per_head = tiles;
+  um.n_units = tiles * n_heads;
+  um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
+  constexpr int lds = kF8Ring * 2 * kF8Unit * D;
+  auto kern = attn_fwd_fp8_kernel<D>;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e != hipSuccess) return e;
+  kern<<<um.chunk * kNumXcd, kF8Waves * 64, lds, stream>>>(
+      (const unsigned char*)q8, (const unsigned char*)k8, (const unsigned char*)vT8, (__bf16*)out, lse,
+      segs, um, total, n_heads, n_units, scale_log2, out_scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const Fp8SegTable& segs,
+                               int n_units, int total, int n_heads, int head_dim, float scale_times_descale,
+                               float v_descale, void* out, float* lse, hipStream_t stream) {
+  const float sl2 = scale_times_descale * kF8Log2e;
+  if (head_dim == 128)
+    return fwd_fp8_d<128>(q8, k8, vT8, segs, n_units, total, n_heads, sl2, v_descale, out, lse, stream);
+  return fwd_fp8_d<64>(q8, k8, vT8, segs, n_units, total, n_heads, sl2, v_descale, out, lse, stream);
+}
+
+}  // namespace vfm

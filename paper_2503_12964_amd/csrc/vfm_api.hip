@@ -96,6 +96,35 @@ int build_temporal_table(const int32_t* thw, const int32_t* cu, int n_seqs, int 
   return VFM_OK;
 }
 
+constexpr int kFp8Unit = 64;   // keys per packed unit of the FP8 path
+
+// Units of 64 keys per clip (never straddling clips); returns their total.
+int build_fp8_tables(const int32_t* cu, int n_seqs, int total, vfm::Fp8ClipTable* clips,
+                     vfm::Fp8SegTable* segs) {
+  int units = 0;
+  clips->n = n_seqs;
+  for (int s = 0; s < n_seqs; ++s) {
+    clips->cu[s] = cu[s];
+    clips->unit0[s] = units;
+    units += (cu[s + 1] - cu[s] + kFp8Unit - 1) / kFp8Unit;
+  }
+  for (int s = n_seqs; s <= VFM_MAX_SEQS; ++s) { clips->cu[s] = total; clips->unit0[s] = units; }
+  if (segs) {
+    SegTable plain;
+    build_seg_table(cu, n_seqs, &plain);
+    segs->n = plain.n;
+    for (int i = 0; i < VFM_MAX_SEQS; ++i) {
+      segs->start[i] = plain.start[i];
+      segs->len[i] = plain.len[i];
+      segs->unit0[i] = 0;
+      if (i < plain.n)
+        for (int s = 0; s < n_seqs; ++s)
+          if (cu[s] == plain.start[i] && cu[s + 1] - cu[s] == plain.len[i]) { segs->unit0[i] = clips->unit0[s]; break; }
+    }
+  }
+  return units;
+}
+
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Shared by the RoPE entry points: sizes, split, theta, cu_seqlens and the per-clip grids;
@@ -359,6 +388,67 @@ int vfm_tattn_bwd(const void* q, const void* k, const void* v, const void* dout,
   if (total_tokens == 0) return VFM_OK;
   hipError_t e = vfm::launch_tattn_bwd(q, k, v, dout, tab, n_heads, head_dim, scale, dq, dk, dv,
                                        static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+}
+
+int vfm_fp8_pack_sizes(const int32_t* cu_seqlens, int n_seqs, int total_tokens, int n_heads,
+                       int head_dim, size_t* q8_bytes, size_t* k8_bytes, size_t* vT8_bytes) {
+  if (!cu_seqlens || !q8_bytes || !k8_bytes || !vT8_bytes) return VFM_ERR_NULL;
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  if (st) return st;
+  st = check_cu(cu_seqlens, n_seqs, total_tokens);
+  if (st) return st;
+  vfm::Fp8ClipTable clips;
+  const size_t units = (size_t)build_fp8_tables(cu_seqlens, n_seqs, total_tokens, &clips, nullptr);
+  *q8_bytes = (size_t)total_tokens * n_heads * head_dim;
+  *k8_bytes = units * n_heads * kFp8Unit * head_dim;
+  *vT8_bytes = *k8_bytes;
+  if (*k8_bytes > 0xffffffffULL) return VFM_ERR_SHAPE;   // the kernels address a unit with a 32-bit byte offset
+  return VFM_OK;
+}
+
+int vfm_fp8_pack(const void* q, const void* k, const void* v, const int32_t* cu_seqlens, int n_seqs,
+                 int total_tokens, int n_heads, int head_dim, float q_scale, float k_scale,
+                 float v_scale, void* q8, void* k8, void* vT8, vfm_dtype dt, void* hip_stream) {
+  if (!q || !k || !v || !cu_seqlens || !q8 || !k8 || !vT8) return VFM_ERR_NULL;
+  if (dt != VFM_BF16) return VFM_ERR_DTYPE;
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  if (st) return st;
+  for (float sc : {q_scale, k_scale, v_scale})
+    if (!(sc > 0.f) || !isfinite(sc)) return VFM_ERR_SHAPE;
+  st = check_cu(cu_seqlens, n_seqs, total_tokens);
+  if (st) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(q8) || !aligned16(k8) || !aligned16(vT8))
+    return VFM_ERR_ALIGN;
+  vfm::Fp8ClipTable clips;
+  const int units = build_fp8_tables(cu_seqlens, n_seqs, total_tokens, &clips, nullptr);
+  if ((unsigned long long)units * n_heads * kFp8Unit * head_dim > 0xffffffffULL) return VFM_ERR_SHAPE;
+  hipError_t e = vfm::launch_fp8_pack(q, k, v, clips, units, total_tokens, n_heads, head_dim, q_scale,
+                                      k_scale, v_scale, q8, k8, vT8, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+}
+
+int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const int32_t* cu_seqlens,
+                     int n_seqs, int total_tokens, int n_heads, int head_dim, float scale,
+                     float q_scale, float k_scale, float v_scale, void* out, float* lse,
+                     void* hip_stream) {
+  if (!q8 || !k8 || !vT8 || !cu_seqlens || !out || !lse) return VFM_ERR_NULL;
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  if (st) return st;
+  for (float sc : {scale, q_scale, k_scale, v_scale})
+    if (!(sc > 0.f) || !isfinite(sc)) return VFM_ERR_SHAPE;
+  st = check_cu(cu_seqlens, n_seqs, total_tokens);
+  if (st) return st;
+  if (!aligned16(q8) || !aligned16(k8) || !aligned16(vT8) || !aligned16(out) || !aligned16(lse))
+    return VFM_ERR_ALIGN;
+  if (total_tokens == 0) return VFM_OK;
+  vfm::Fp8ClipTable clips;
+  vfm::Fp8SegTable segs;
+  const int units = build_fp8_tables(cu_seqlens, n_seqs, total_tokens, &clips, &segs);
+  if ((unsigned long long)units * n_heads * kFp8Unit * head_dim > 0xffffffffULL) return VFM_ERR_SHAPE;
+  hipError_t e = vfm::launch_attn_fwd_fp8(q8, k8, vT8, segs, units, total_tokens, n_heads, head_dim,
+                                          scale / (q_scale * k_scale), 1.0f / v_scale, out, lse,
+                                          static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
 }
 

@@ -54,6 +54,25 @@ struct RopeTable {
   int w[VFM_MAX_SEQS];   // W
 };
 
+// FP8 attention: keys and values are packed in units of 64 keys that never straddle a clip.
+// Packed-order table for the packing pass ...
+struct Fp8ClipTable {
+  int n;
+  int cu[VFM_MAX_SEQS + 1];     // first packed token of clip s
+  int unit0[VFM_MAX_SEQS + 1];  // units of the clips before s
+};
+// ... and the forward kernel's schedule (non-empty clips, longest first).
+struct Fp8SegTable {
+  int n;
+  int start[VFM_MAX_SEQS];
+  int len[VFM_MAX_SEQS];
+  int unit0[VFM_MAX_SEQS];      // first unit of the clip in the packed buffers
+  __device__ __host__ int q_start(int s) const { return start[s]; }
+  __device__ __host__ int q_len(int s) const { return len[s]; }
+  __device__ __host__ int kv_start(int s) const { return start[s]; }
+  __device__ __host__ int kv_len(int s) const { return len[s]; }
+};
+
 // Clip table for temporal attention: packed token and pixel offsets of every clip.
 struct TemporalTable {
   int n;
@@ -236,6 +255,14 @@ hipError_t launch_tattn_fwd(const void* q, const void* k, const void* v, const T
 hipError_t launch_tattn_bwd(const void* q, const void* k, const void* v, const void* dout,
                             const TemporalTable& tab, int n_heads, int head_dim, float scale, void* dq,
                             void* dk, void* dv, hipStream_t stream);
+
+hipError_t launch_fp8_pack(const void* q, const void* k, const void* v, const Fp8ClipTable& clips,
+                           int n_units, int total, int n_heads, int head_dim, float qs, float ks,
+                           float vs, void* q8, void* k8, void* vT8, hipStream_t stream);
+
+hipError_t launch_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const Fp8SegTable& segs,
+                               int n_units, int total, int n_heads, int head_dim, float scale_times_descale,
+                               float v_descale, void* out, float* lse, hipStream_t stream);
 
 // Segs is SegTable (self-attention) or XSegTable (cross-attention); total_q is the number
 // of query tokens (rows of lse, Delta).
