@@ -216,8 +216,16 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
         }
     }
     f32x16 s_next;
+    // two accumulation chains (even and odd k-steps): a single chain of dependent MFMAs
+    // cannot issue back to back; the 16 extra adds cost less than the stalls they remove
+    f32x16 s_odd;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) s_next = mfma32(ka[ks], qreg[ks], ks == 0 ? zero16 : s_next);
+    for (int ks = 0; ks < KS; ks += 2) {
+      s_next = mfma32(ka[ks], qreg[ks], ks == 0 ? zero16 : s_next);
+      s_odd = mfma32(ka[ks + 1], qreg[ks + 1], ks == 0 ? zero16 : s_odd);
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s_next[r] += s_odd[r];
 
     // softmax of unit u (log2 domain), taken against the current reference point m_run
     // without looking at this unit's maximum: the result is exact after the final

@@ -156,6 +156,32 @@ def test_temporal_attention_argument_errors(lib):
     assert lib.vfm_tattn_bwd(FAKE, FAKE, FAKE, FAKE, pa, pb, 1, 8, 2, 96, 0.1, FAKE, FAKE, FAKE, 0, None) == 2
 
 
+def test_fp8_argument_errors(lib):
+    arr, cu = _i32([0, 100, 100, 165])
+    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    assert lib.vfm_fp8_pack_sizes(cu, 3, 165, 4, 128, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 0
+    # units: ceil(100/64) + 0 + ceil(65/64) = 4
+    assert a.value == 165 * 4 * 128 and b.value == 4 * 4 * 64 * 128 and c.value == b.value
+    assert lib.vfm_fp8_pack_sizes(cu, 3, 166, 4, 128, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 3
+    assert lib.vfm_fp8_pack_sizes(cu, 3, 165, 4, 96, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 2
+    assert lib.vfm_fp8_pack_sizes(cu, 3, 165, 4, 128, None, ctypes.byref(b), ctypes.byref(c)) == 1
+
+    def pack(q=FAKE, qs=32.0, q8=FAKE, dt=0):
+        return lib.vfm_fp8_pack(q, FAKE, FAKE, cu, 3, 165, 4, 128, qs, 64.0, 16.0, q8, FAKE, FAKE, dt, None)
+    assert pack(q=None) == 1
+    assert pack(qs=0.0) == 2
+    assert pack(qs=float("inf")) == 2
+    assert pack(dt=1) == 6
+    assert pack(q8=ODD) == 9
+
+    def fwd(q8=FAKE, scale=0.1, vs=16.0, lse=FAKE):
+        return lib.vfm_attn_fwd_fp8(q8, FAKE, FAKE, cu, 3, 165, 4, 128, scale, 32.0, 64.0, vs, FAKE, lse, None)
+    assert fwd(lse=None) == 1
+    assert fwd(scale=-1.0) == 2
+    assert fwd(vs=0.0) == 2
+    assert fwd(q8=ODD) == 9
+
+
 def test_tensors_beyond_32bit_byte_offsets_are_rejected(lib):
     # 131072 tokens x 128 heads x 128 x 2 bytes = 4 GiB: the kernels address tensors with 32-bit byte offsets
     arr, p = _i32([0, 131072])
