@@ -124,7 +124,8 @@ def _bench_cross(args, wl) -> int:
     out = torch.empty_like(q)
     lse = torch.empty((wl.n_heads, tq), dtype=torch.float32, device="cuda")
     dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
-    ws = torch.empty(B.vfm_attn_bwd_workspace_size(tq, wl.n_heads, wl.head_dim), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.vfm_xattn_bwd_workspace_size(tq, tk, wl.n_heads, wl.head_dim), dtype=torch.uint8,
+                     device="cuda")
 
     def step(ev=None):
         if ev: ev[0].record()

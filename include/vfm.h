@@ -193,11 +193,16 @@ VFM_API int vfm_xattn_fwd(const void* q, const void* k, const void* v,
 /*
  * Cross-attention backward: dq [total_q, ...], dk, dv [total_kv, ...] from dout,
  * with the formulas of vfm_attn_bwd, i over a sequence's queries and j over its
- * keys.  Keys of a sequence without queries get zero gradients.  workspace: as
- * for vfm_attn_bwd, sized by vfm_attn_bwd_workspace_size(total_q, n_heads,
- * head_dim).  Every output is written once, no atomics.
+ * keys.  Keys of a sequence without queries get zero gradients.  workspace:
+ * device, 256-byte aligned, at least vfm_xattn_bwd_workspace_size() bytes (the
+ * statistics of vfm_attn_bwd plus fp32 dK, dV accumulators).  dq is written
+ * once and is reproducible.  When the key ranges are short (few key tiles for
+ * many queries) the query range is split over workgroups and dK, dV are summed
+ * with fp32 atomics, so their last bits may differ from run to run; otherwise
+ * they are written once as in vfm_attn_bwd.
  * Errors: NULL, SHAPE, CU_SEQLENS, DTYPE, ALIGN, WORKSPACE, LAUNCH.
  */
+VFM_API size_t vfm_xattn_bwd_workspace_size(int total_q, int total_kv, int n_heads, int head_dim);
 VFM_API int vfm_xattn_bwd(const void* q, const void* k, const void* v, const void* out,
                   const float* lse, const void* dout,
                   const int32_t* cu_seqlens_q, const int32_t* cu_seqlens_kv, int n_seqs,

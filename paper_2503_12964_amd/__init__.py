@@ -9,4 +9,4 @@ from .binding import (VfmError, load_library, strerror, vfm_attn_bwd,  # noqa: F
                       vfm_attn_fwd_fp8, vfm_fp8_pack, vfm_fp8_pack_sizes,
                       vfm_attn_bwd_workspace_size, vfm_attn_fwd, vfm_qknorm_rope3d,
                       vfm_qknorm_rope3d_bwd, vfm_rope3d, vfm_tattn_bwd, vfm_tattn_fwd,
-                      vfm_xattn_bwd, vfm_xattn_fwd)
+                      vfm_xattn_bwd, vfm_xattn_bwd_workspace_size, vfm_xattn_fwd)

@@ -21,7 +21,7 @@ VFM_BF16 = 0
 VFM_F32 = 1
 VFM_MAX_SEQS = 256
 
-EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_xattn_fwd", "vfm_xattn_bwd", "vfm_tattn_fwd", "vfm_tattn_bwd",
+EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_xattn_fwd", "vfm_xattn_bwd_workspace_size", "vfm_xattn_bwd", "vfm_tattn_fwd", "vfm_tattn_bwd",
            "vfm_fp8_pack_sizes", "vfm_fp8_pack", "vfm_attn_fwd_fp8", "vfm_strerror")
 
 _lib = None
@@ -67,6 +67,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.vfm_xattn_fwd.restype = c_int
     lib.vfm_xattn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, p_i32, p_i32, c_int, c_int, c_int, c_int, c_int,
                                   c_float, c_void_p, c_void_p, c_int, c_void_p]
+    lib.vfm_xattn_bwd_workspace_size.restype = c_size_t
+    lib.vfm_xattn_bwd_workspace_size.argtypes = [c_int, c_int, c_int, c_int]
     lib.vfm_xattn_bwd.restype = c_int
     lib.vfm_xattn_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, p_i32, p_i32, c_int,
                                   c_int, c_int, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p, c_void_p,
@@ -236,6 +238,10 @@ def vfm_xattn_fwd(q, k, v, cu_seqlens_q, cu_seqlens_kv, scale: float, out=None, 
     return out, lse
 
 
+def vfm_xattn_bwd_workspace_size(total_q: int, total_kv: int, n_heads: int, head_dim: int) -> int:
+    return int(load_library().vfm_xattn_bwd_workspace_size(int(total_q), int(total_kv), int(n_heads), int(head_dim)))
+
+
 def vfm_xattn_bwd(q, k, v, out, lse, dout, cu_seqlens_q, cu_seqlens_kv, scale: float, dq=None, dk=None,
                   dv=None, workspace=None, stream=None) -> Tuple:
     """Cross-attention gradients: dq (shape of q), dk, dv (shape of k)."""
@@ -248,7 +254,7 @@ def vfm_xattn_bwd(q, k, v, out, lse, dout, cu_seqlens_q, cu_seqlens_kv, scale: f
     dq = torch.empty_like(q) if dq is None else dq
     dk = torch.empty_like(k) if dk is None else dk
     dv = torch.empty_like(v) if dv is None else dv
-    need = vfm_attn_bwd_workspace_size(total_q, heads, hd)
+    need = vfm_xattn_bwd_workspace_size(total_q, int(k.shape[0]), heads, hd)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
     _check(lib.vfm_xattn_bwd(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"), _dev(lse, "lse"),

@@ -19,6 +19,8 @@
 //                     dS^T = P^T o (dP^T - Delta)          (lse, Delta are per-lane scalars)
 //                     dQ^T += K^T dS^T                     (A = transposing reads of the K tile)
 //                 S and dP are recomputed here (7 GEMMs in total instead of 5).
+#include <algorithm>
+
 #include "vfm_common.h"
 
 namespace vfm {
@@ -90,7 +92,10 @@ struct BwdCfg {
   static constexpr int kBatch = 2 * kLoadsPerWave + 1;                   // loads per wave per tile
 };
 
-template <int D, class Segs>
+// SPLIT: the sequence's query range is cut into q_split chunks, one workgroup each; partial
+// dK/dV are added to zeroed fp32 accumulators (dkv32: dK, then dV) with fp32 atomics and
+// converted afterwards.  Used when a few long key tiles would otherwise leave CUs idle.
+template <int D, class Segs, bool SPLIT>
 __global__ __launch_bounds__(kBwdWaves * 64, 1)
 void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                           const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
@@ -98,7 +103,8 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                           const float* __restrict__ sentinel,   // [+inf, 0]
                           __bf16* __restrict__ dk, __bf16* __restrict__ dv,
                           const Segs segs, const UnitMap um,
-                          int total, int n_heads, float scale, float scale_log2) {
+                          int total, int n_heads, float scale, float scale_log2,
+                          float* __restrict__ dkv32, size_t kv_elems, int q_split) {
   using Cfg = BwdCfg<D>;
   constexpr int KS = D / 16;
   constexpr int DB = D / 32;
@@ -113,12 +119,20 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   if (!map_unit(um, blockIdx.x, head, tile)) return;
   // key rows [j0, j0 + kBwdBC) of the sequence's key/value range [.., kv_b); the queries it
   // walks are rows [seg_a, seg_b) of q, dout (the same range for self-attention)
+  int q_chunk = 0;
+  if constexpr (SPLIT) { q_chunk = tile % q_split; tile /= q_split; }
   int seq, tk;
   locate_tile<true>(segs, kBwdBC, tile, seq, tk);
   const int kv_b = segs.kv_start(seq) + segs.kv_len(seq);
   const int j0 = segs.kv_start(seq) + tk * kBwdBC;
-  const int seg_a = segs.q_start(seq);
-  const int seg_b = seg_a + segs.q_len(seq);
+  int qa = segs.q_start(seq), qb = qa + segs.q_len(seq);
+  if constexpr (SPLIT) {   // this workgroup's share of the query tiles
+    const int per = ((qb - qa + kBwdBQ - 1) / kBwdBQ + q_split - 1) / q_split * kBwdBQ;
+    qa += q_chunk * per;
+    qb = min(qb, qa + per);
+    if (qa >= qb) return;  // nothing to add (the accumulators start at zero)
+  }
+  const int seg_a = qa, seg_b = qb;
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -364,22 +378,49 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 
   // ---- epilogue: dK (scaled) and dV for this lane's key row
   if (jvalid) {
-    __bf16* dkp = dk + (size_t)jrow * row_stride + head_off + 4 * g;
-    __bf16* dvp = dv + (size_t)jrow * row_stride + head_off + 4 * g;
+    if constexpr (SPLIT) {
+      float* dkp = dkv32 + ((size_t)jrow * n_heads + head) * D + 4 * g;
+      float* dvp = dkp + kv_elems;
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        f32x4 a, b;
+        for (int q4 = 0; q4 < 4; ++q4)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          a[e] = dkacc[db][q4 * 4 + e] * scale;
-          b[e] = dvacc[db][q4 * 4 + e];
+          for (int e = 0; e < 4; ++e) {
+            __hip_atomic_fetch_add(dkp + db * 32 + q4 * 8 + e, dkacc[db][q4 * 4 + e] * scale, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(dvp + db * 32 + q4 * 8 + e, dvacc[db][q4 * 4 + e], __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+          }
+    } else {
+      __bf16* dkp = dk + (size_t)jrow * row_stride + head_off + 4 * g;
+      __bf16* dvp = dv + (size_t)jrow * row_stride + head_off + 4 * g;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          f32x4 a, b;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            a[e] = dkacc[db][q4 * 4 + e] * scale;
+            b[e] = dvacc[db][q4 * 4 + e];
+          }
+          *reinterpret_cast<bf16x4*>(dkp + db * 32 + q4 * 8) = to_bf16x4(a);
+          *reinterpret_cast<bf16x4*>(dvp + db * 32 + q4 * 8) = to_bf16x4(b);
         }
-        *reinterpret_cast<bf16x4*>(dkp + db * 32 + q4 * 8) = to_bf16x4(a);
-        *reinterpret_cast<bf16x4*>(dvp + db * 32 + q4 * 8) = to_bf16x4(b);
-      }
+    }
   }
+}
+
+// fp32 accumulators -> bf16 gradients (after a split dK/dV pass); also zeroes them beforehand
+__global__ void fill_zero_f32x4_kernel(f32x4* p, size_t n4) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+  if (i < n4) p[i] = z;
+}
+__global__ void f32_to_bf16_kernel(const f32x4* __restrict__ src, bf16x4* __restrict__ dst, size_t n4) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n4) dst[i] = to_bf16x4(src[i]);
 }
 
 // ---------------------------------------------------------------- dQ
@@ -606,7 +647,8 @@ template <int D, class Segs>
 static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, const void* out,
                                const float* lse, const void* dout, const Segs& segs, int total,
                                int n_heads, float scale, void* dq, void* dk, void* dv,
-                               float* delta, float* lse2, float* sentinel, hipStream_t stream) {
+                               float* delta, float* lse2, float* sentinel, float* dkv32, int total_kv,
+                               hipStream_t stream) {
   if (total > 0) {   // (with no queries at all only the keys' zero gradients remain to be written)
     constexpr int kTokPerBlock = 256 / (D / 8);
     const int grid = (total + kTokPerBlock - 1) / kTokPerBlock;
@@ -623,15 +665,47 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
     um.tiles_per_head = tiles;
     um.n_units = tiles * n_heads;
     um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
-    auto kern = attn_bwd_dkdv_kernel<D, Segs>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
-    if (e != hipSuccess) return e;
-    kern<<<um.chunk * kNumXcd, kBwdWaves * 64, Cfg::kLdsBytes, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse2, delta,
-        sentinel, (__bf16*)dk, (__bf16*)dv, segs, um, total, n_heads, scale, scale * kLog2eB);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    // Few key tiles and long query ranges (cross-attention): split the queries over workgroups.
+    int q_split = 1;
+    if (dkv32 && tiles * n_heads < 256) {
+      int max_q = 0;
+      for (int s2 = 0; s2 < segs.n; ++s2) max_q = std::max(max_q, segs.q_len(s2));
+      q_split = std::min(std::min(16, (256 + tiles * n_heads - 1) / (tiles * n_heads)), std::max(1, max_q / 512));
+    }
+    hipError_t e;
+    if (q_split > 1) {
+      const size_t kv_elems = (size_t)total_kv * n_heads * D;
+      const size_t n4 = 2 * kv_elems / 4;
+      fill_zero_f32x4_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, stream>>>((f32x4*)dkv32, n4);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+      um.tiles_per_head = tiles * q_split;
+      um.n_units = um.tiles_per_head * n_heads;
+      um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
+      auto kern = attn_bwd_dkdv_kernel<D, Segs, true>;
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+      if (e != hipSuccess) return e;
+      kern<<<um.chunk * kNumXcd, kBwdWaves * 64, Cfg::kLdsBytes, stream>>>(
+          (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse2, delta,
+          sentinel, (__bf16*)dk, (__bf16*)dv, segs, um, total, n_heads, scale, scale * kLog2eB,
+          dkv32, kv_elems, q_split);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+      const size_t h4 = kv_elems / 4;
+      f32_to_bf16_kernel<<<(unsigned)((h4 + 255) / 256), 256, 0, stream>>>((const f32x4*)dkv32, (bf16x4*)dk, h4);
+      f32_to_bf16_kernel<<<(unsigned)((h4 + 255) / 256), 256, 0, stream>>>((const f32x4*)(dkv32 + kv_elems),
+                                                                          (bf16x4*)dv, h4);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    } else {
+      auto kern = attn_bwd_dkdv_kernel<D, Segs, false>;
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+      if (e != hipSuccess) return e;
+      kern<<<um.chunk * kNumXcd, kBwdWaves * 64, Cfg::kLdsBytes, stream>>>(
+          (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse2, delta,
+          sentinel, (__bf16*)dk, (__bf16*)dv, segs, um, total, n_heads, scale, scale * kLog2eB,
+          nullptr, 0, 1);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
   }
   {
     constexpr int NI = 1;
@@ -658,16 +732,17 @@ template <class Segs>
 hipError_t launch_attn_bwd(const void* q, const void* k, const void* v, const void* out,
                            const float* lse, const void* dout, const Segs& segs, int total,
                            int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
-                           float* delta, float* lse2, float* sentinel, hipStream_t stream) {
+                           float* delta, float* lse2, float* sentinel, float* dkv32, int total_kv,
+                           hipStream_t stream) {
   if (head_dim == 128)
-    return launch_bwd_d<128>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, sentinel, stream);
-  return launch_bwd_d<64>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, sentinel, stream);
+    return launch_bwd_d<128>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, sentinel, dkv32, total_kv, stream);
+  return launch_bwd_d<64>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, sentinel, dkv32, total_kv, stream);
 }
 template hipError_t launch_attn_bwd<SegTable>(const void*, const void*, const void*, const void*, const float*,
                                               const void*, const SegTable&, int, int, int, float, void*, void*,
-                                              void*, float*, float*, float*, hipStream_t);
+                                              void*, float*, float*, float*, float*, int, hipStream_t);
 template hipError_t launch_attn_bwd<XSegTable>(const void*, const void*, const void*, const void*, const float*,
                                                const void*, const XSegTable&, int, int, int, float, void*, void*,
-                                               void*, float*, float*, float*, hipStream_t);
+                                               void*, float*, float*, float*, float*, int, hipStream_t);
 
 }  // namespace vfm

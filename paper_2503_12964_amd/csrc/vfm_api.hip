@@ -258,6 +258,13 @@ size_t vfm_attn_bwd_workspace_size(int total_tokens, int n_heads, int head_dim) 
   return 2 * align_up(rows * sizeof(float), 256) + 256;   // Delta, lse in log2 units, sentinels
 }
 
+size_t vfm_xattn_bwd_workspace_size(int total_q, int total_kv, int n_heads, int head_dim) {
+  const size_t stats = vfm_attn_bwd_workspace_size(total_q, n_heads, head_dim);
+  if (stats == 0 || check_shape(0, total_kv, n_heads, head_dim)) return 0;
+  // + fp32 dK and dV accumulators for the query-split pass
+  return stats + align_up((size_t)2 * total_kv * n_heads * head_dim * sizeof(float), 256);
+}
+
 int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
                  const void* dout, const int32_t* cu_seqlens, int n_seqs, int total_tokens,
                  int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
@@ -284,7 +291,7 @@ int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, c
   SegTable segs;
   build_seg_table(cu_seqlens, n_seqs, &segs);
   hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_tokens, n_heads,
-                                      head_dim, scale, dq, dk, dv, delta, lse2, sentinel,
+                                      head_dim, scale, dq, dk, dv, delta, lse2, sentinel, nullptr, 0,
                                       static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
 }
@@ -336,15 +343,17 @@ int vfm_xattn_bwd(const void* q, const void* k, const void* v, const void* out, 
       !aligned16(dout) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
     return VFM_ERR_ALIGN;
   if (total_kv == 0) return VFM_OK;     // then total_q is 0 too
-  const size_t need = vfm_attn_bwd_workspace_size(total_q, n_heads, head_dim);
+  const size_t stats = vfm_attn_bwd_workspace_size(total_q, n_heads, head_dim);
+  const size_t need = vfm_xattn_bwd_workspace_size(total_q, total_kv, n_heads, head_dim);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
     return VFM_ERR_WORKSPACE;
   float* delta = static_cast<float*>(workspace);
-  const size_t part = (need - 256) / 2;
+  const size_t part = (stats - 256) / 2;
   float* lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + part);
   float* sentinel = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * part);
+  float* dkv32 = reinterpret_cast<float*>(static_cast<char*>(workspace) + stats);
   hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_q, n_heads, head_dim,
-                                      scale, dq, dk, dv, delta, lse2, sentinel,
+                                      scale, dq, dk, dv, delta, lse2, sentinel, dkv32, total_kv,
                                       static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
 }

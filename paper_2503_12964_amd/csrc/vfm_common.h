@@ -275,6 +275,7 @@ template <class Segs>
 hipError_t launch_attn_bwd(const void* q, const void* k, const void* v, const void* out,
                            const float* lse, const void* dout, const Segs& segs, int total_q,
                            int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
-                           float* delta, float* lse2, float* sentinel, hipStream_t stream);
+                           float* delta, float* lse2, float* sentinel, float* dkv32, int total_kv,
+                           hipStream_t stream);   // dkv32: optional fp32 dK,dV accumulators (query-split pass)
 
 }  // namespace vfm

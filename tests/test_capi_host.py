@@ -135,6 +135,10 @@ def test_cross_attention_argument_errors(lib):
     assert xb(dk=None) == 1
     assert xb(ws=None) == 7
     assert xb(ws_bytes=16) == 7
+    n = lib.vfm_xattn_bwd_workspace_size(8, 4, 2, 128)
+    assert n % 256 == 0 and n >= lib.vfm_attn_bwd_workspace_size(8, 2, 128) + 2 * 4 * 2 * 128 * 4
+    assert xb(ws_bytes=n - 1) == 7
+    assert lib.vfm_xattn_bwd_workspace_size(8, 4, 2, 96) == 0
 
 
 def test_temporal_attention_argument_errors(lib):
