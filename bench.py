@@ -224,7 +224,7 @@ def _bench_fp8(args, wl) -> int:
     t = _device_tensors(wl)
     q, k, v = t["q"], t["k"], t["v"]
     cu = wl.cu_seqlens
-    scales = (32.0, 64.0, 16.0)
+    scales = (wl.scale, 1.0, 16.0)     # softmax scale (folded into q), k and v multipliers
     q8, k8, vT8 = B.vfm_fp8_pack(q, k, v, cu, *scales)
     out = torch.empty_like(q)
     lse = torch.empty((wl.n_heads, wl.total_tokens), dtype=torch.float32, device="cuda")
@@ -233,7 +233,7 @@ def _bench_fp8(args, wl) -> int:
         if ev: ev[0].record()
         B.vfm_fp8_pack(q, k, v, cu, *scales, q8=q8, k8=k8, vT8=vT8)
         if ev: ev[1].record()
-        B.vfm_attn_fwd_fp8(q8, k8, vT8, cu, wl.n_heads, wl.head_dim, wl.scale, *scales, out=out, lse=lse)
+        B.vfm_attn_fwd_fp8(q8, k8, vT8, cu, wl.n_heads, wl.head_dim, scales[2], out=out, lse=lse)
         if ev: ev[2].record()
     for _ in range(args.warmup):
         step()

@@ -240,11 +240,15 @@ VFM_API int vfm_tattn_bwd(const void* q, const void* k, const void* v, const voi
  * FP8 attention forward (Section 5.2 reports FP8 multi-head attention for
  * inference).  Operands are 8-bit floats in the E4M3 format of the OCP 8-bit
  * floating point specification, prepared once per (q, k, v) by vfm_fp8_pack:
- *   x8 = round_to_nearest_even(clamp(x * x_scale, -448, 448))
- * with one caller-chosen scale per tensor, into three packed buffers (per head h;
- * a "unit" is 64 consecutive keys of one clip, zero padded at the clip's end;
- * units are numbered clip by clip in packed order, clip s owning
- * ceil(len_s / 64) of them):
+ *   x8 = round_to_nearest_even(clamp(x * m_x, -448, 448))
+ * with the multipliers  m_k = k_scale,  m_v = v_scale  (caller-chosen) and
+ *   m_q = scale * log2(e) / k_scale
+ * where scale is the softmax scale: the product q8 . k8 is then the softmax
+ * exponent in log2 units, and the kernel needs no multiply before its exp2.
+ * (Keep k_scale near 1 for unit-variance inputs so that m_q q stays in E4M3's
+ * normal range, >= 2^-6.)  The three packed buffers hold, per head h (a "unit"
+ * is 64 consecutive keys of one clip, zero padded at the clip's end; units are
+ * numbered clip by clip in packed order, clip s owning ceil(len_s / 64)):
  *   q8  [n_heads][total_tokens][head_dim]
  *   k8  [n_heads][units][64][head_dim]: key row r of a unit holds its 16-byte
  *       chunk c at chunk position c ^ ((r >> 1) & 7) (head_dim 128) or
@@ -264,24 +268,24 @@ VFM_API int vfm_fp8_pack_sizes(const int32_t* cu_seqlens, int n_seqs, int total_
                        size_t* q8_bytes, size_t* k8_bytes, size_t* vT8_bytes);
 VFM_API int vfm_fp8_pack(const void* q, const void* k, const void* v,
                  const int32_t* cu_seqlens, int n_seqs, int total_tokens,
-                 int n_heads, int head_dim, float q_scale, float k_scale, float v_scale,
+                 int n_heads, int head_dim, float scale, float k_scale, float v_scale,
                  void* q8, void* k8, void* vT8, vfm_dtype dt, void* hip_stream);
 
 /*
  * out, lse as vfm_attn_fwd, computed from the packed E4M3 operands with FP8
  * matrix instructions and fp32 accumulation:
- *     S_ij = scale / (q_scale k_scale) * sum_d q8[i,d] k8[j,d]
+ *     S_ij  = ln(2) * sum_d q8[i,d] k8[j,d]        (= scale q_i . k_j up to rounding)
  *     out_i = (1 / v_scale) * sum_j softmax_j(S_ij) v8[j,:]
- * The probabilities are rounded to E4M3 (3 mantissa bits) before the second
- * product, so out carries a relative error of a few percent against the exact
- * result on the same quantised operands; lse is accumulated in fp32.  out: bf16
- * [total_tokens, n_heads, head_dim]; lse: fp32 [n_heads, total_tokens].
+ * v_scale is the one given to vfm_fp8_pack.  The probabilities are rounded to
+ * E4M3 (3 mantissa bits) before the second product, so out carries a relative
+ * error of a few percent against the exact result on the same quantised
+ * operands; lse is accumulated in fp32.  out: bf16 [total_tokens, n_heads,
+ * head_dim]; lse: fp32 [n_heads, total_tokens].
  * Errors: NULL, SHAPE, CU_SEQLENS, ALIGN, LAUNCH.
  */
 VFM_API int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8,
                      const int32_t* cu_seqlens, int n_seqs, int total_tokens,
-                     int n_heads, int head_dim, float scale,
-                     float q_scale, float k_scale, float v_scale,
+                     int n_heads, int head_dim, float v_scale,
                      void* out, float* lse, void* hip_stream);
 
 /* Static, human-readable text for a vfm_status. */

@@ -87,7 +87,7 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
                                  c_float, c_void_p, c_void_p, c_void_p, c_int, c_void_p]
     lib.vfm_attn_fwd_fp8.restype = c_int
     lib.vfm_attn_fwd_fp8.argtypes = [c_void_p, c_void_p, c_void_p, p_i32, c_int, c_int, c_int, c_int, c_float,
-                                     c_float, c_float, c_float, c_void_p, c_void_p, c_void_p]
+                                     c_void_p, c_void_p, c_void_p]
     lib.vfm_strerror.restype = ctypes.c_char_p
     lib.vfm_strerror.argtypes = [c_int]
     if path == LIB_PATH:
@@ -306,9 +306,10 @@ def vfm_fp8_pack_sizes(cu_seqlens, n_heads: int, head_dim: int) -> Tuple[int, in
     return int(a.value), int(b.value), int(c.value)
 
 
-def vfm_fp8_pack(q, k, v, cu_seqlens, q_scale: float, k_scale: float, v_scale: float, q8=None, k8=None,
+def vfm_fp8_pack(q, k, v, cu_seqlens, scale: float, k_scale: float, v_scale: float, q8=None, k8=None,
                  vT8=None, stream=None) -> Tuple:
-    """Quantise bf16 q, k, v to E4M3 in the packed layout vfm_attn_fwd_fp8 reads (uint8 device buffers)."""
+    """Quantise bf16 q, k, v to E4M3 in the packed layout vfm_attn_fwd_fp8 reads (uint8 device buffers).
+    k and v are multiplied by k_scale, v_scale; q by scale * log2(e) / k_scale (scale = softmax scale)."""
     import torch
     lib = load_library()
     cu = _host_i32(cu_seqlens)
@@ -318,13 +319,13 @@ def vfm_fp8_pack(q, k, v, cu_seqlens, q_scale: float, k_scale: float, v_scale: f
     k8 = torch.empty(max(nk, 16), dtype=torch.uint8, device=q.device) if k8 is None else k8
     vT8 = torch.empty(max(nv, 16), dtype=torch.uint8, device=q.device) if vT8 is None else vT8
     _check(lib.vfm_fp8_pack(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _i32_ptr(cu), int(cu.size - 1), int(total),
-                            int(heads), int(hd), float(q_scale), float(k_scale), float(v_scale), _dev(q8, "q8"),
+                            int(heads), int(hd), float(scale), float(k_scale), float(v_scale), _dev(q8, "q8"),
                             _dev(k8, "k8"), _dev(vT8, "vT8"), _dtype_code(q), _stream_ptr(stream)))
     return q8, k8, vT8
 
 
-def vfm_attn_fwd_fp8(q8, k8, vT8, cu_seqlens, n_heads: int, head_dim: int, scale: float, q_scale: float,
-                     k_scale: float, v_scale: float, out=None, lse=None, stream=None) -> Tuple:
+def vfm_attn_fwd_fp8(q8, k8, vT8, cu_seqlens, n_heads: int, head_dim: int, v_scale: float, out=None, lse=None,
+                     stream=None) -> Tuple:
     """FP8 attention forward on packed operands: out (bf16 [total, heads, head_dim]) and lse (fp32)."""
     import torch
     lib = load_library()
@@ -335,6 +336,6 @@ def vfm_attn_fwd_fp8(q8, k8, vT8, cu_seqlens, n_heads: int, head_dim: int, scale
     if lse is None:
         lse = torch.empty((n_heads, total), dtype=torch.float32, device=q8.device)
     _check(lib.vfm_attn_fwd_fp8(_dev(q8, "q8"), _dev(k8, "k8"), _dev(vT8, "vT8"), _i32_ptr(cu), int(cu.size - 1),
-                                total, int(n_heads), int(head_dim), float(scale), float(q_scale), float(k_scale),
-                                float(v_scale), _dev(out, "out"), _dev(lse, "lse"), _stream_ptr(stream)))
+                                total, int(n_heads), int(head_dim), float(v_scale), _dev(out, "out"),
+                                _dev(lse, "lse"), _stream_ptr(stream)))
     return out, lse

@@ -29,7 +29,6 @@ constexpr int kF8Unit = 64;
 constexpr int kF8Waves = 8;
 constexpr int kF8Rows = kF8Waves * 32;   // query rows per workgroup
 constexpr int kF8Ring = 3;
-constexpr float kF8Log2e = 1.4426950408889634f;
 constexpr float kF8Ln2 = 0.6931471805599453f;
 constexpr float kF8PShift = 6.0f;        // P is stored as 2^6 P
 constexpr float kF8SafeSum = 448.0f;     // largest finite E4M3: bounds every scaled P of the unit
@@ -157,7 +156,7 @@ __global__ __launch_bounds__(kF8Waves * 64, 2)
 void attn_fwd_fp8_kernel(const unsigned char* __restrict__ q8, const unsigned char* __restrict__ k8,
                          const unsigned char* __restrict__ vT8, __bf16* __restrict__ out,
                          float* __restrict__ lse, const Fp8SegTable segs, const UnitMap um, int total,
-                         int n_heads, int n_units, float scale_log2, float out_scale) {
+                         int n_heads, int n_units, float out_scale) {
   constexpr int KS = D / 64;            // instructions per 32-key score tile
   constexpr int DB = D / 32;            // 32-row blocks of O^T
   constexpr int UB = kF8Unit * D;       // bytes of a K unit and of a V^T unit
@@ -231,6 +230,10 @@ void attn_fwd_fp8_kernel(const unsigned char* __restrict__ q8, const unsigned ch
   f32x16 oacc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db) oacc[db] = zero16;
+  // The packed q already carries scale * log2(e) / k_scale, so the score instruction's result is
+  // the exponent in log2 units; its accumulator starts at minus the reference point, so the
+  // exponential needs no multiply-subtract at all.
+  f32x16 minit = zero16;              // -m_ref in every register
   float m_ref = 0.f, l_run = 0.f;     // reference point (log2 units, shifted) and running sum of scaled P
 
   issue_unit(0, 0);
@@ -250,7 +253,7 @@ void attn_fwd_fp8_kernel(const unsigned char* __restrict__ q8, const unsigned ch
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
-        s[t] = mfma_f8(lds_read_32b(kt, koff[t][ks][0], koff[t][ks][1]), qreg[ks], ks == 0 ? zero16 : s[t]);
+        s[t] = mfma_f8(lds_read_32b(kt, koff[t][ks][0], koff[t][ks][1]), qreg[ks], ks == 0 ? minit : s[t]);
     // V^T operands requested in the shadow of the score instructions
     i32x8 va[DB];
 #pragma unroll
@@ -264,42 +267,37 @@ void attn_fwd_fp8_kernel(const unsigned char* __restrict__ q8, const unsigned ch
         for (int r = 0; r < 16; ++r)
           if (j0 + 32 * t + 8 * (r >> 2) + 4 * g + (r & 3) >= seg_b) s[t][r] = -INFINITY;
     }
-    if (u == 0) {   // first reference point: the exact row max of unit 0
-      float mx = s[0][0];
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
-      m_ref = pair_max(mx) * scale_log2 - kF8PShift;
-    }
-
-    // ---- scaled exponentials against the current reference, packed to E4M3
+    // ---- scaled exponentials against the current reference (s already holds score - m_ref)
     float p[2][16];
     float lsum = 0.f;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        p[t][r] = fast_exp2(s[t][r] * scale_log2 - m_ref);
+        p[t][r] = fast_exp2(s[t][r]);
         lsum += p[t][r];
       }
-    // every scaled P <= lsum, so lsum <= 448 keeps all of them finite in E4M3 (overflow fails too)
-    if (__builtin_amdgcn_ballot_w64(!(lsum <= kF8SafeSum)) != 0) {
-      // rare: move the reference to the true running max, redo the unit, rescale sums and O
+    // every scaled P <= lsum, so lsum <= 448 keeps all of them finite in E4M3 (overflow fails too).
+    // Unit 0 always takes this path: it sets the first reference point from its exact row max.
+    if (u == 0 || __builtin_amdgcn_ballot_w64(!(lsum <= kF8SafeSum)) != 0) {
+      // move the reference to the running max (minus the 2^6 headroom), redo the unit, rescale sums and O
       float mx = s[0][0];
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
-      const float m_new = fmaxf(m_ref, pair_max(mx) * scale_log2 - kF8PShift);
-      const float alpha = fast_exp2(m_ref - m_new);
-      m_ref = m_new;
+      float delta = pair_max(mx) - kF8PShift;          // how far the reference has to move
+      if (u != 0) delta = fmaxf(delta, 0.f);           // it only ever moves up
+      const float alpha = fast_exp2(-delta);
+      m_ref += delta;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) minit[r] = -m_ref;
       lsum = 0.f;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          p[t][r] = fast_exp2(s[t][r] * scale_log2 - m_new);
+          p[t][r] = fast_exp2(s[t][r] - delta);
           lsum += p[t][r];
         }
       l_run *= alpha;
@@ -365,7 +363,7 @@ hipError_t launch_fp8_pack(const void* q, const void* k, const void* v, const Fp
 
 template <int D>
 static hipError_t fwd_fp8_d(const void* q8, const void* k8, const void* vT8, const Fp8SegTable& segs,
-                            int n_units, int total, int n_heads, float scale_log2, float out_scale,
+                            int n_units, int total, int n_heads, float out_scale,
                             void* out, float* lse, hipStream_t stream) {
   int tiles = 0;
   for (int s = 0; s < segs.n; ++s) tiles += (segs.len[s] + kF8Rows - 1) / kF8Rows;
@@ -381,17 +379,16 @@ static hipError_t fwd_fp8_d(const void* q8, const void* k8, const void* vT8, con
   if (e != hipSuccess) return e;
   kern<<<um.chunk * kNumXcd, kF8Waves * 64, lds, stream>>>(
       (const unsigned char*)q8, (const unsigned char*)k8, (const unsigned char*)vT8, (__bf16*)out, lse,
-      segs, um, total, n_heads, n_units, scale_log2, out_scale);
+      segs, um, total, n_heads, n_units, out_scale);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const Fp8SegTable& segs,
-                               int n_units, int total, int n_heads, int head_dim, float scale_times_descale,
-                               float v_descale, void* out, float* lse, hipStream_t stream) {
-  const float sl2 = scale_times_descale * kF8Log2e;
+                               int n_units, int total, int n_heads, int head_dim, float v_descale,
+                               void* out, float* lse, hipStream_t stream) {
   if (head_dim == 128)
-    return fwd_fp8_d<128>(q8, k8, vT8, segs, n_units, total, n_heads, sl2, v_descale, out, lse, stream);
-  return fwd_fp8_d<64>(q8, k8, vT8, segs, n_units, total, n_heads, sl2, v_descale, out, lse, stream);
+    return fwd_fp8_d<128>(q8, k8, vT8, segs, n_units, total, n_heads, v_descale, out, lse, stream);
+  return fwd_fp8_d<64>(q8, k8, vT8, segs, n_units, total, n_heads, v_descale, out, lse, stream);
 }
 
 }  // namespace vfm

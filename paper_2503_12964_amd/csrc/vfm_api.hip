@@ -417,13 +417,14 @@ int vfm_fp8_pack_sizes(const int32_t* cu_seqlens, int n_seqs, int total_tokens, 
 }
 
 int vfm_fp8_pack(const void* q, const void* k, const void* v, const int32_t* cu_seqlens, int n_seqs,
-                 int total_tokens, int n_heads, int head_dim, float q_scale, float k_scale,
+                 int total_tokens, int n_heads, int head_dim, float scale, float k_scale,
                  float v_scale, void* q8, void* k8, void* vT8, vfm_dtype dt, void* hip_stream) {
+  const float q_scale = scale * 1.4426950408889634f / k_scale;   // scores come out in log2 units
   if (!q || !k || !v || !cu_seqlens || !q8 || !k8 || !vT8) return VFM_ERR_NULL;
   if (dt != VFM_BF16) return VFM_ERR_DTYPE;
   int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
   if (st) return st;
-  for (float sc : {q_scale, k_scale, v_scale})
+  for (float sc : {scale, k_scale, v_scale, q_scale})
     if (!(sc > 0.f) || !isfinite(sc)) return VFM_ERR_SHAPE;
   st = check_cu(cu_seqlens, n_seqs, total_tokens);
   if (st) return st;
@@ -438,14 +439,12 @@ int vfm_fp8_pack(const void* q, const void* k, const void* v, const int32_t* cu_
 }
 
 int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const int32_t* cu_seqlens,
-                     int n_seqs, int total_tokens, int n_heads, int head_dim, float scale,
-                     float q_scale, float k_scale, float v_scale, void* out, float* lse,
-                     void* hip_stream) {
+                     int n_seqs, int total_tokens, int n_heads, int head_dim, float v_scale,
+                     void* out, float* lse, void* hip_stream) {
   if (!q8 || !k8 || !vT8 || !cu_seqlens || !out || !lse) return VFM_ERR_NULL;
   int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
   if (st) return st;
-  for (float sc : {scale, q_scale, k_scale, v_scale})
-    if (!(sc > 0.f) || !isfinite(sc)) return VFM_ERR_SHAPE;
+  if (!(v_scale > 0.f) || !isfinite(v_scale)) return VFM_ERR_SHAPE;
   st = check_cu(cu_seqlens, n_seqs, total_tokens);
   if (st) return st;
   if (!aligned16(q8) || !aligned16(k8) || !aligned16(vT8) || !aligned16(out) || !aligned16(lse))
@@ -456,7 +455,7 @@ int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const int3
   const int units = build_fp8_tables(cu_seqlens, n_seqs, total_tokens, &clips, &segs);
   if ((unsigned long long)units * n_heads * kFp8Unit * head_dim > 0xffffffffULL) return VFM_ERR_SHAPE;
   hipError_t e = vfm::launch_attn_fwd_fp8(q8, k8, vT8, segs, units, total_tokens, n_heads, head_dim,
-                                          scale / (q_scale * k_scale), 1.0f / v_scale, out, lse,
+                                          1.0f / v_scale, out, lse,
                                           static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
 }

@@ -261,8 +261,8 @@ hipError_t launch_fp8_pack(const void* q, const void* k, const void* v, const Fp
                            float vs, void* q8, void* k8, void* vT8, hipStream_t stream);
 
 hipError_t launch_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const Fp8SegTable& segs,
-                               int n_units, int total, int n_heads, int head_dim, float scale_times_descale,
-                               float v_descale, void* out, float* lse, hipStream_t stream);
+                               int n_units, int total, int n_heads, int head_dim, float v_descale,
+                               void* out, float* lse, hipStream_t stream);
 
 // Segs is SegTable (self-attention) or XSegTable (cross-attention); total_q is the number
 // of query tokens (rows of lse, Delta).

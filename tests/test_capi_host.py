@@ -171,17 +171,17 @@ def test_fp8_argument_errors(lib):
     assert lib.vfm_fp8_pack_sizes(cu, 3, 165, 4, 128, None, ctypes.byref(b), ctypes.byref(c)) == 1
 
     def pack(q=FAKE, qs=32.0, q8=FAKE, dt=0):
-        return lib.vfm_fp8_pack(q, FAKE, FAKE, cu, 3, 165, 4, 128, qs, 64.0, 16.0, q8, FAKE, FAKE, dt, None)
+        return lib.vfm_fp8_pack(q, FAKE, FAKE, cu, 3, 165, 4, 128, qs, 1.0, 16.0, q8, FAKE, FAKE, dt, None)
     assert pack(q=None) == 1
     assert pack(qs=0.0) == 2
     assert pack(qs=float("inf")) == 2
     assert pack(dt=1) == 6
     assert pack(q8=ODD) == 9
 
-    def fwd(q8=FAKE, scale=0.1, vs=16.0, lse=FAKE):
-        return lib.vfm_attn_fwd_fp8(q8, FAKE, FAKE, cu, 3, 165, 4, 128, scale, 32.0, 64.0, vs, FAKE, lse, None)
+    def fwd(q8=FAKE, vs=16.0, lse=FAKE):
+        return lib.vfm_attn_fwd_fp8(q8, FAKE, FAKE, cu, 3, 165, 4, 128, vs, FAKE, lse, None)
     assert fwd(lse=None) == 1
-    assert fwd(scale=-1.0) == 2
+    assert fwd(vs=-1.0) == 2
     assert fwd(vs=0.0) == 2
     assert fwd(q8=ODD) == 9
 

@@ -14,7 +14,15 @@ from tests.test_gpu_parity import SMALL, _binding
 pytestmark = pytest.mark.gpu
 
 TOL_FP8_OUT_RELRMS = 5e-2
-SCALES = (32.0, 64.0, 16.0)        # q, k, v: powers of two, N(0,1) draws stay far below 448
+LOG2E = 1.4426950408889634
+K_SCALE, V_SCALE = 1.0, 16.0       # powers of two; N(0,1) draws stay far below 448
+
+
+def _mults(wl):
+    """Multipliers the pack applies to q, k, v (q carries the softmax scale in log2 units); the q
+    multiplier is formed in fp32 exactly as the library forms it."""
+    qm = np.float32(np.float32(wl.scale) * np.float32(LOG2E)) / np.float32(K_SCALE)
+    return (float(qm), K_SCALE, V_SCALE)
 
 
 def _unpack(cu, heads, hd, q8, k8, vT8):
@@ -64,7 +72,7 @@ def _unpack(cu, heads, hd, q8, k8, vT8):
 def _pack(b, wl):
     inp = W.make_inputs(wl, tensors=("q", "k", "v"))
     dev = {n: U.to_device(inp[n]) for n in ("q", "k", "v")}
-    q8, k8, vT8 = b.vfm_fp8_pack(dev["q"], dev["k"], dev["v"], wl.cu_seqlens, *SCALES)
+    q8, k8, vT8 = b.vfm_fp8_pack(dev["q"], dev["k"], dev["v"], wl.cu_seqlens, wl.scale, K_SCALE, V_SCALE)
     return inp, (q8, k8, vT8)
 
 
@@ -78,11 +86,11 @@ def test_pack_is_bit_exact_and_attention_matches_oracle(name):
                     vT8.cpu().numpy()[:nv])
     assert codes[3], "padding keys of a unit must be zero"
     deq = {}
-    for nm, got, sc in zip(("q", "k", "v"), codes[:3], SCALES):
+    for nm, got, sc in zip(("q", "k", "v"), codes[:3], _mults(wl)):
         want = orc.fp8_e4m3_encode(W.bf16_bits_to_f32(inp[nm]) * np.float32(sc))   # fp32 product, as the kernel
         assert np.array_equal(got, want), nm
         deq[nm] = orc.fp8_e4m3_decode(got) / sc
-    out, lse = b.vfm_attn_fwd_fp8(q8, k8, vT8, wl.cu_seqlens, wl.n_heads, wl.head_dim, wl.scale, *SCALES)
+    out, lse = b.vfm_attn_fwd_fp8(q8, k8, vT8, wl.cu_seqlens, wl.n_heads, wl.head_dim, V_SCALE)
     o_ref, l_ref = orc.attn_fwd(deq["q"], deq["k"], deq["v"], wl.cu_seqlens, wl.scale)
     o = U.to_f64(out)
     assert np.all(np.isfinite(o))
@@ -102,9 +110,9 @@ def test_growing_scores_move_the_reference():
     dev = {n: U.to_device(inp[n]) for n in ("q", "k", "v")}
     ramp = torch.linspace(1.0, 12.0, wl.total_tokens, device="cuda")
     dev["k"] = (dev["k"].float() * ramp[:, None, None]).to(torch.bfloat16)
-    scales = (32.0, 4.0, 16.0)
-    q8, k8, vT8 = b.vfm_fp8_pack(dev["q"], dev["k"], dev["v"], wl.cu_seqlens, *scales)
-    out, lse = b.vfm_attn_fwd_fp8(q8, k8, vT8, wl.cu_seqlens, wl.n_heads, wl.head_dim, wl.scale, *scales)
+    scales = _mults(wl)
+    q8, k8, vT8 = b.vfm_fp8_pack(dev["q"], dev["k"], dev["v"], wl.cu_seqlens, wl.scale, K_SCALE, V_SCALE)
+    out, lse = b.vfm_attn_fwd_fp8(q8, k8, vT8, wl.cu_seqlens, wl.n_heads, wl.head_dim, V_SCALE)
     deq = {}
     for nm, sc in zip(("q", "k", "v"), scales):
         x32 = dev[nm].float().cpu().numpy() * np.float32(sc)
@@ -122,12 +130,12 @@ def test_headline_shape_sampled_rows():
     wl = W.WORKLOADS["C4"]
     b = _binding()
     inp, (q8, k8, vT8) = _pack(b, wl)
-    out, lse = b.vfm_attn_fwd_fp8(q8, k8, vT8, wl.cu_seqlens, wl.n_heads, wl.head_dim, wl.scale, *SCALES)
+    out, lse = b.vfm_attn_fwd_fp8(q8, k8, vT8, wl.cu_seqlens, wl.n_heads, wl.head_dim, V_SCALE)
     rows = np.unique(np.concatenate([[0, 255, 256, 56319], np.random.default_rng(9).integers(0, 56320, 24)]))
     err = ref = 0.0
     for h in (0, 13, 31):
         deq = {}
-        for nm, sc in zip(("q", "k", "v"), SCALES):
+        for nm, sc in zip(("q", "k", "v"), _mults(wl)):
             x32 = W.bf16_bits_to_f32(inp[nm][:, h:h + 1]) * np.float32(sc)
             deq[nm] = orc.fp8_e4m3_decode(orc.fp8_e4m3_encode(x32)) / sc
         o_ref, l_ref = orc.attn_fwd_rows(deq["q"], deq["k"], deq["v"], wl.cu_seqlens, wl.scale, 0, rows)
