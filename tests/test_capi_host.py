@@ -28,6 +28,21 @@ def test_header_symbols_are_exported(lib):
         assert hasattr(lib, name), name
 
 
+def test_header_compiles_as_c_and_cxx(tmp_path):
+    """include/vfm.h is a plain C header: it must compile on its own as C99 and as C++."""
+    import shutil
+    import subprocess
+    header = os.path.join(ROOT, "include", "vfm.h")
+    for compiler, std, suffix in (("gcc", "-std=c99", ".c"), ("g++", "-std=c++11", ".cc")):
+        if shutil.which(compiler) is None:
+            pytest.skip(f"{compiler} not available")
+        src = tmp_path / ("use_vfm" + suffix)
+        src.write_text(f'#include "{header}"\nint main(void) {{ return vfm_strerror(VFM_OK) == 0; }}\n')
+        res = subprocess.run([compiler, std, "-Wall", "-Wextra", "-pedantic", "-fsyntax-only", str(src)],
+                             capture_output=True, text=True)
+        assert res.returncode == 0 and not res.stderr.strip(), res.stderr
+
+
 def test_strerror_texts(lib):
     assert lib.vfm_strerror(0) == b"ok"
     texts = {lib.vfm_strerror(i) for i in range(10)}
