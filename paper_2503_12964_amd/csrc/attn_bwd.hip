@@ -82,6 +82,33 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const u32x4* __restric
 constexpr int kBwdRing = 4;
 constexpr int kSgValuB = 0x002, kSgMfmaB = 0x008, kSgDsReadB = 0x100;
 
+// S and dP MFMAs of the dK/dV kernel, issued as assembly: the kernel needs more than 256
+// registers, for which the compiler gives every MFMA an AGPR destination and then copies
+// each score (VALU cannot read AGPRs).  Here the destination is a VGPR tuple and the
+// loop-invariant K/V operand an AGPR tuple instead.  The compiler does not know that this
+// is an MFMA, so it inserts no wait states for readers of d: every reader must be at
+// least two MFMAs downstream in program order (the kernel reads d one iteration later).
+__device__ __forceinline__ void mfma32_v(f32x16& d, const bf16x8& a, const bf16x8& b, bool first) {
+  if (first) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+}
+// The same with three register tuples passed through unchanged.  Volatile statements keep
+// their program order, so arithmetic that reads f0/f1/f2 after this call cannot be moved
+// before the MFMA, and arithmetic that produced them cannot be moved after it: this is how
+// the VALU work is spread evenly between the MFMAs.
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ void mfma32_v(f32x16& d, const bf16x8& a, const bf16x8& b, bool first,
+                                         f32x16& f0, f32x16& f1, u32x8& f2) {
+  if (first) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %4, %5, 0"
+                          : "=&v"(d), "+v"(f0), "+v"(f1), "+v"(f2) : "v"(a), "a"(b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %4, %5, %0"
+                    : "+v"(d), "+v"(f0), "+v"(f1), "+v"(f2) : "v"(a), "a"(b));
+}
+
+// Rebinds a loaded operand to an AGPR tuple (and, like settle(), makes the compiler wait
+// for its global load here).
+__device__ __forceinline__ void to_agpr(bf16x8& x) { asm volatile("" : "=a"(x) : "0"(x)); }
+
 template <int D>
 struct BwdCfg {
   static constexpr int kTileBytes = kBwdBQ * D * 2;                      // one Q or dO tile
@@ -239,7 +266,7 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 
   // ---- prologue: tiles 0..2 requested; S(0), dP(0); row operands of block 1
 #pragma unroll
-  for (int ks = 0; ks < KS; ++ks) { settle(kreg[ks]); settle(vreg[ks]); }
+  for (int ks = 0; ks < KS; ++ks) { to_agpr(kreg[ks]); to_agpr(vreg[ks]); }
   issue_tile(0); issue_tile(1); issue_tile(2);
   wait_vmcnt<0>();
   __syncthreads();
@@ -252,8 +279,8 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     read_rows(0, 1, qa_n, da_n);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      s_cur = mfma32(q0r[ks], kreg[ks], ks == 0 ? zero16 : s_cur);
-      dp_cur = mfma32(d0r[ks], vreg[ks], ks == 0 ? zero16 : dp_cur);
+      mfma32_v(s_cur, q0r[ks], kreg[ks], ks == 0);
+      mfma32_v(dp_cur, d0r[ks], vreg[ks], ks == 0);
     }
   }
 
@@ -276,51 +303,58 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     const float* delta_s = lse_s + kBwdBQ;               // wave 1's statistics follow wave 0's
 
     // ---- phase A: S(b+1), dP(b+1) | P(b) | statistics and transposed-operand reads of block b
+    // One group per MFMA, in program order (see mfma32_v): group 0 fetches lse, every group
+    // two transposed operands (dO^T first: phase B needs it first), the last two Delta; the
+    // 16 values of P per lane are spread over groups 2.. so that lse has arrived.
+    constexpr int NG = 2 * KS;
     f32x4 l4[4], d4[4];
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) l4[q4] = *reinterpret_cast<const f32x4*>(lse_s + IB * 32 + 8 * q4 + 4 * g);
     s16x4 dlo[2][DB], dhi[2][DB], qlo[2][DB], qhi[2][DB];
+    f32x16 s_next, dp_next, p;
+    u32x8 pw;
 #pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2)
+    for (int gi = 0; gi < NG; ++gi) {
+      const int ks = gi >> 1;
+      if ((gi & 1) == 0) mfma32_v(s_next, qa_n[ks], kreg[ks], ks == 0, s_cur, p, pw);
+      else mfma32_v(dp_next, da_n[ks], vreg[ks], ks == 0, s_cur, p, pw);
+      if (gi == 0) {
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const int o0 = (tbase[0] ^ (db << 6)) + (IB * 32 + 16 * s2) * RB;
-        const int o1 = (tbase[1] ^ (db << 6)) + (IB * 32 + 16 * s2) * RB;
-        dlo[s2][db] = lds_read_tr(dot, o0);
-        dhi[s2][db] = lds_read_tr(dot, o1);
-        qlo[s2][db] = lds_read_tr(qt, o0);
-        qhi[s2][db] = lds_read_tr(qt, o1);
+        for (int q4 = 0; q4 < 4; ++q4) l4[q4] = *reinterpret_cast<const f32x4*>(lse_s + IB * 32 + 8 * q4 + 4 * g);
       }
 #pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4) d4[q4] = *reinterpret_cast<const f32x4*>(delta_s + IB * 32 + 8 * q4 + 4 * g);
-    f32x16 s_next, dp_next;
+      for (int r = 2 * gi; r < 2 * gi + 2; ++r) {
+        const int rr = r % (4 * DB), s2 = rr / (2 * DB), db = (rr >> 1) % DB, hi = rr & 1;
+        const int o = (tbase[hi] ^ (db << 6)) + (IB * 32 + 16 * s2) * RB;
+        if (r < 4 * DB) { if (hi) dhi[s2][db] = lds_read_tr(dot, o); else dlo[s2][db] = lds_read_tr(dot, o); }
+        else { if (hi) qhi[s2][db] = lds_read_tr(qt, o); else qlo[s2][db] = lds_read_tr(qt, o); }
+      }
+      if (gi >= NG - 2) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      s_next = mfma32(qa_n[ks], kreg[ks], ks == 0 ? zero16 : s_next);
-      dp_next = mfma32(da_n[ks], vreg[ks], ks == 0 ? zero16 : dp_next);
+        for (int q4 = 2 * (gi - (NG - 2)); q4 < 2 * (gi - (NG - 2)) + 2; ++q4)
+          d4[q4] = *reinterpret_cast<const f32x4*>(delta_s + IB * 32 + 8 * q4 + 4 * g);
+      }
+      // P for rows i = 8*(e/4) + 4g + e%4 of the block, column j = this lane's key; a pair
+      // is converted one group after its exponentials (no transcendental-result stall)
+#pragma unroll
+      for (int e = 1; e < 16; e += 2)
+        if (e * (NG - 2) / 16 + 3 == gi) {
+          const f32x2 pr = {p[e - 1], p[e]};
+          pw[e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+        }
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (e * (NG - 2) / 16 + 2 == gi) p[e] = fast_exp2(s_cur[e] * scale_log2 - l4[e >> 2][e & 3]);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    // P for rows i = 8*q4 + 4g + e of the block, column j = this lane's key
-    f32x16 p;
-#pragma unroll
-    for (int q4 = 0; q4 < 4; ++q4)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) p[q4 * 4 + e] = fast_exp2(s_cur[q4 * 4 + e] * scale_log2 - l4[q4][e]);
+    {
+      const f32x2 pr = {p[14], p[15]};   // the last pair's group would be NG
+      pw[7] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+    }
     bf16x8 pb[2];
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
-      f32x8 a;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) a[e] = p[8 * s2 + e];
-      pb[s2] = to_bf16x8(a);
+      const u32x4 w = {pw[4 * s2], pw[4 * s2 + 1], pw[4 * s2 + 2], pw[4 * s2 + 3]};
+      pb[s2] = __builtin_bit_cast(bf16x8, w);
     }
-    __builtin_amdgcn_sched_group_barrier(kSgDsReadB, 4, 0);
-#pragma unroll
-    for (int i = 0; i < 2 * KS; ++i) {
-      __builtin_amdgcn_sched_group_barrier(kSgMfmaB, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(kSgDsReadB, (8 * DB + 4 + 2 * KS - 1) / (2 * KS), 0);
-      __builtin_amdgcn_sched_group_barrier(kSgValuB, 3, 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);
 
     // ---- phase B: dV^T += dO(b)^T P(b) | dS(b) = P(b) o (dP(b) - Delta)
 #pragma unroll
