@@ -47,7 +47,8 @@ __device__ __forceinline__ float clamp448(float x) { return fminf(fmaxf(x, -kF8M
 
 // four floats -> four E4M3 bytes (round to nearest even; the inputs are already within +-448)
 __device__ __forceinline__ uint32_t pack_fp8x4(float a, float b, float c, float d) {
-  int v = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false);
+  // (the first conversion's "old" word is overwritten by the second: any register will do)
+  int v = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, __builtin_bit_cast(int, a), false);
   v = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, v, true);
   return (uint32_t)v;
 }
@@ -239,12 +240,13 @@ void attn_fwd_fp8_kernel(const unsigned char* __restrict__ q8, const unsigned ch
   issue_unit(0, 0);
   issue_unit(1, 1);
 
-  for (int u = 0; u < n_u; ++u) {
-    const int slot = u % kF8Ring;
+  // One unit; the ring slot is a compile-time constant so that every LDS offset is an immediate.
+  auto unit_body = [&](auto slot_c, int u) {
+    constexpr int SLOT = decltype(slot_c)::value;
     wait_vmcnt<2>();          // unit u has landed (unit u+1 may still be in flight) ...
     __syncthreads();          // ... for every wave, and every wave is done with unit u-1
-    issue_unit(u + 2, (u + 2) % kF8Ring);
-    const char* kt = smem + slot * 2 * UB;
+    issue_unit(u + 2, (SLOT + 2) % kF8Ring);
+    const char* kt = smem + SLOT * 2 * UB;
     const char* vt = kt + UB;
 
     // ---- S^T for the unit's two 32-key tiles
@@ -317,6 +319,12 @@ void attn_fwd_fp8_kernel(const unsigned char* __restrict__ q8, const unsigned ch
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int db = 0; db < DB; ++db) oacc[db] = mfma_f8(va[db], pb, oacc[db]);
+  };
+  static_assert(kF8Ring == 3, "the unit loop is unrolled over the ring");
+  for (int u = 0; u < n_u; u += 3) {
+    unit_body(IntC<0>{}, u);
+    if (u + 1 < n_u) unit_body(IntC<1>{}, u + 1);
+    if (u + 2 < n_u) unit_body(IntC<2>{}, u + 2);
   }
   wait_vmcnt<0>();   // no load may still be writing LDS when the workgroup ends
 
