@@ -74,12 +74,15 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const u32x4* __restric
 //   phase A:  S(b+1), dP(b+1) MFMAs        |  P(b)  = exp2(S(b)*scale - lse2)        (VALU)
 //   phase B:  dV^T += dO(b)^T P(b) MFMAs   |  dS(b) = P(b) o (dP(b) - Delta)         (VALU)
 //   phase C:  dK^T += Q(b)^T dS(b) MFMAs   |  row-operand reads of block b+2, tile requests
-// Q/dO tiles of 64 rows (two blocks) live in a ring of four LDS stages filled by direct
-// global->LDS loads three tiles ahead; there is one workgroup barrier per tile.
+// Q/dO tiles of 64 rows (two blocks) live in a ring of three LDS stages filled by direct
+// global->LDS loads two tiles ahead; there is one workgroup barrier per tile.  (Not further
+// ahead on purpose: a workgroup that runs ahead of the others of its head then waits for
+// its own L2 misses while the ones behind it hit, which keeps the workgroups of an XCD on
+// the same part of Q/dO; three tiles ahead was measured to quadruple the HBM fetches.)
 // Query rows past the clip end need no mask: their lse2 is fetched from a +inf sentinel
 // (so P = 0) and their Delta from a 0 sentinel.  Key rows past the clip end need none
 // either: a lane's key only feeds that lane's own dK/dV row, which is never stored.
-constexpr int kBwdRing = 4;
+constexpr int kBwdRing = 3;
 constexpr int kSgValuB = 0x002, kSgMfmaB = 0x008, kSgDsReadB = 0x100;
 
 // S and dP MFMAs of the dK/dV kernel, issued as assembly: the kernel needs more than 256
@@ -116,7 +119,6 @@ struct BwdCfg {
   static constexpr int kLdsBytes = kBwdRing * kStageBytes;
   static constexpr int kChunksPerRow = D / 8;
   static constexpr int kLoadsPerWave = kBwdBQ * kChunksPerRow / (kBwdWaves * 64);  // per tile, per tensor
-  static constexpr int kBatch = 2 * kLoadsPerWave + 1;                   // loads per wave per tile
 };
 
 // SPLIT: the sequence's query range is cut into q_split chunks, one workgroup each; partial
@@ -264,10 +266,10 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     }
   };
 
-  // ---- prologue: tiles 0..2 requested; S(0), dP(0); row operands of block 1
+  // ---- prologue: tiles 0 and 1 requested; S(0), dP(0); row operands of block 1
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) { to_agpr(kreg[ks]); to_agpr(vreg[ks]); }
-  issue_tile(0); issue_tile(1); issue_tile(2);
+  issue_tile(0); issue_tile(1);
   wait_vmcnt<0>();
   __syncthreads();
 
@@ -284,7 +286,7 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     }
   }
 
-  // One pipeline iteration; POS = b % 8 fixes every LDS stage at compile time.
+  // One pipeline iteration; POS = b % 6 fixes every LDS stage at compile time.
   auto iteration = [&](auto pos_c) {
     constexpr int POS = decltype(pos_c)::value;
     constexpr int IB = POS & 1;                          // block b within its tile
@@ -292,10 +294,10 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     constexpr int ST_ROW = ((POS + 2) / 2) % kBwdRing;   // stage of block b+2's tile
     if constexpr (IB == 0) {
       // Start of tile t = b/2: tile t+1 must have landed for every wave before anyone reads
-      // block b+2's rows, and every wave is past tile t-1, whose stage takes tile t+3.
-      wait_vmcnt<Cfg::kBatch>();
+      // block b+2's rows, and every wave is past tile t-1, whose stage takes tile t+2.
+      wait_vmcnt<0>();
       __syncthreads();
-      issue_tile((ST_CUR + 3) % kBwdRing);
+      issue_tile((ST_CUR + 2) % kBwdRing);
     }
     const char* qt = smem + ST_CUR * SB;
     const char* dot = qt + TB;
@@ -401,12 +403,12 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     for (int ks = 0; ks < KS; ++ks) { qa_n[ks] = qa_2[ks]; da_n[ks] = da_2[ks]; }
   };
 
-  for (int b = 0; b < n_blocks; b += 8) {
+  static_assert(kBwdRing == 3, "the block loop is unrolled over the ring");
+  for (int b = 0; b < n_blocks; b += 6) {
     iteration(IntC<0>{});
     iteration(IntC<1>{});
     if (b + 2 < n_blocks) { iteration(IntC<2>{}); iteration(IntC<3>{}); }
     if (b + 4 < n_blocks) { iteration(IntC<4>{}); iteration(IntC<5>{}); }
-    if (b + 6 < n_blocks) { iteration(IntC<6>{}); iteration(IntC<7>{}); }
   }
   wait_vmcnt<0>();   // no load may still be writing LDS when the workgroup ends
 
