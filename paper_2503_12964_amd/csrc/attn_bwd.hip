@@ -115,8 +115,11 @@ __device__ __forceinline__ void to_agpr(bf16x8& x) { asm volatile("" : "=a"(x) :
 template <int D>
 struct BwdCfg {
   static constexpr int kTileBytes = kBwdBQ * D * 2;                      // one Q or dO tile
-  static constexpr int kStageBytes = 2 * kTileBytes + 4 * kBwdBQ * 4;    // Q, dO, lse2, Delta (+ spare)
-  static constexpr int kLdsBytes = kBwdRing * kStageBytes;
+  static constexpr int kStageBytes = 2 * kTileBytes;                     // Q, dO tiles of one stage
+  static constexpr int kStatBytes = 4 * kBwdBQ * 4;                      // lse2, Delta (+ spare) of one stage
+  // tiles first (two stages span exactly 64 KB at head_dim 128: immediate LDS offsets), statistics behind them
+  static constexpr int kStatBase = kBwdRing * kStageBytes;
+  static constexpr int kLdsBytes = kStatBase + kBwdRing * kStatBytes;
   static constexpr int kChunksPerRow = D / 8;
   static constexpr int kLoadsPerWave = kBwdBQ * kChunksPerRow / (kBwdWaves * 64);  // per tile, per tensor
 };
@@ -220,7 +223,7 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   const uint32_t stat_head = (uint32_t)((size_t)head * total * 4u);
   const uint32_t smem_addr = lds_addr_of(smem);
   const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(smem_addr + wave * 1024);
-  const uint32_t stat_lds = __builtin_amdgcn_readfirstlane(smem_addr + 2 * TB + wave * (kBwdBQ * 4));
+  const uint32_t stat_lds = __builtin_amdgcn_readfirstlane(smem_addr + Cfg::kStatBase + wave * (kBwdBQ * 4));
   auto issue_tile = [&](int stage) {
 #pragma unroll
     for (int x = 0; x < LPW; ++x) {
@@ -231,7 +234,7 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
       st_rowoff[x] += kBwdBQ * row_bytes;
     }
     const uint32_t soff = stat_row < seg_b ? stat_head + (uint32_t)stat_row * 4u : stat_sentinel;
-    lds_dma4(stat_src, soff, stat_lds + stage * SB);
+    lds_dma4(stat_src, soff, stat_lds + stage * Cfg::kStatBytes);
     stat_row += kBwdBQ;
   };
 
@@ -248,6 +251,26 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     tbase[t] = tile_off<D>(8 * t + 4 * g + ((lane & 15) >> 2),
                            16 * ((lane >> 4) & 1) + 4 * (lane & 3));
 
+  // Every swizzled LDS address the loop uses, held in a register of its own (made opaque so
+  // that the compiler keeps them instead of recomputing them between the MFMAs): set 0 for
+  // stages 0 and 1, set 1 for stage 2, whose tiles lie beyond the 64 KB an immediate reaches.
+  uint32_t rb[2][KS], tb[2][2][DB];
+#pragma unroll
+  for (int hs = 0; hs < 2; ++hs) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      rb[hs][ks] = smem_addr + hs * 2 * SB + (rbase ^ (ks << 5));
+      asm volatile("" : "+v"(rb[hs][ks]));
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        tb[hs][t][db] = smem_addr + hs * 2 * SB + (tbase[t] ^ (db << 6));
+        asm volatile("" : "+v"(tb[hs][t][db]));
+      }
+  }
+
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   f32x16 dkacc[DB], dvacc[DB];
 #pragma unroll
@@ -257,12 +280,11 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   const int n_blocks = 2 * n_tiles;
 
   auto read_rows = [&](int stage, int ib, bf16x8 (&qa)[KS], bf16x8 (&da)[KS]) {
-    const char* qt = smem + stage * SB;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const int off = (rbase ^ (ks << 5)) + ib * 32 * RB;
-      qa[ks] = lds_read_b128(qt, off);
-      da[ks] = lds_read_b128(qt + TB, off);
+      const uint32_t a = rb[stage >> 1][ks] + (stage & 1) * SB + ib * 32 * RB;
+      qa[ks] = lds_read_b128_at(a);
+      da[ks] = lds_read_b128_at(a + TB);
     }
   };
 
@@ -299,9 +321,7 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
       __syncthreads();
       issue_tile((ST_CUR + 2) % kBwdRing);
     }
-    const char* qt = smem + ST_CUR * SB;
-    const char* dot = qt + TB;
-    const float* lse_s = reinterpret_cast<const float*>(qt + 2 * TB);
+    const float* lse_s = reinterpret_cast<const float*>(smem + Cfg::kStatBase + ST_CUR * Cfg::kStatBytes);
     const float* delta_s = lse_s + kBwdBQ;               // wave 1's statistics follow wave 0's
 
     // ---- phase A: S(b+1), dP(b+1) | P(b) | statistics and transposed-operand reads of block b
@@ -325,9 +345,9 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 #pragma unroll
       for (int r = 2 * gi; r < 2 * gi + 2; ++r) {
         const int rr = r % (4 * DB), s2 = rr / (2 * DB), db = (rr >> 1) % DB, hi = rr & 1;
-        const int o = (tbase[hi] ^ (db << 6)) + (IB * 32 + 16 * s2) * RB;
-        if (r < 4 * DB) { if (hi) dhi[s2][db] = lds_read_tr(dot, o); else dlo[s2][db] = lds_read_tr(dot, o); }
-        else { if (hi) qhi[s2][db] = lds_read_tr(qt, o); else qlo[s2][db] = lds_read_tr(qt, o); }
+        const uint32_t o = tb[ST_CUR >> 1][hi][db] + (ST_CUR & 1) * SB + (IB * 32 + 16 * s2) * RB;
+        if (r < 4 * DB) { if (hi) dhi[s2][db] = lds_read_tr_at(o + TB); else dlo[s2][db] = lds_read_tr_at(o + TB); }
+        else { if (hi) qhi[s2][db] = lds_read_tr_at(o); else qlo[s2][db] = lds_read_tr_at(o); }
       }
       if (gi >= NG - 2) {
 #pragma unroll

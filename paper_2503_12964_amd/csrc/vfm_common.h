@@ -158,6 +158,14 @@ __device__ __forceinline__ s16x4 lds_read_tr(const char* base, int off) {
       (__attribute__((address_space(3))) s16x4*)(base + off));
 }
 
+// The same two reads at an LDS byte address held as an integer (base + immediate offset).
+__device__ __forceinline__ bf16x8 lds_read_b128_at(uint32_t addr) {
+  return *reinterpret_cast<const __attribute__((address_space(3))) bf16x8*>(addr);
+}
+__device__ __forceinline__ s16x4 lds_read_tr_at(uint32_t addr) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<__attribute__((address_space(3))) s16x4*>(addr));
+}
+
 __device__ __forceinline__ bf16x8 join_tr(s16x4 lo, s16x4 hi) {
   s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(bf16x8, v);
