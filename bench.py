@@ -395,6 +395,14 @@ def main() -> int:
             "executed_frac_of_random_operand_ceiling": achieved * (1.4 if wl.backward else 1.0) / rnd if rnd > 0 else None,
             "note": "loop of MFMA instructions only, sustained; with random operands the clock drops "
                     "under the power limit, which also bounds kernels working on real data"}
+        if ceiling.get("exp2_only_tera_per_s"):
+            # secondary ceiling: one exponential per (query, key) pair per head in the forward and in
+            # each of the two backward kernels, at the measured rate of a loop of v_exp_f32 only
+            n_exp = wl.flops(False) / (4.0 * wl.head_dim) * (3.0 if wl.backward else 1.0)
+            exp_ms = n_exp / (ceiling["exp2_only_tera_per_s"] * 1e12) * 1e3
+            result["roofline"]["exp_only_measured"] = {
+                "tera_exp_per_s": ceiling["exp2_only_tera_per_s"], "exponentials_per_step": n_exp,
+                "ms_if_nothing_else_ran": exp_ms, "frac_of_step": exp_ms / ms_step}
     # Not part of the timed step: the fused per-head normalisation + RoPE (the step upstream of
     # vfm_rope3d in the paper's model, Section 4.5.1), forward and backward, on the same shapes.
     gain_d = torch.from_numpy(W.norm_gain(wl)).cuda()

@@ -4,7 +4,10 @@
 // with constant operands and once with random ones: the matrix pipe draws more power when
 // its inputs toggle, and the chip lowers its clock to stay inside its power limit, so the
 // rate an attention kernel with real data can approach is the second figure, not the
-// first.  Prints one JSON line.  Standalone program; not part of the library.
+// first.  A third loop of nothing but v_exp_f32 gives the rate of the softmax's exponentials
+// (the secondary ceiling of an attention kernel: one exponential per score, and per score
+// again in each of the two backward kernels).  Prints one JSON line.  Standalone program;
+// not part of the library.
 #include <hip/hip_runtime.h>
 
 #include <chrono>
@@ -46,6 +49,38 @@ __global__ __launch_bounds__(kThreads) void mfma_loop(const bf16x8* __restrict__
   for (int n = 0; n < 8; ++n)
     for (int r = 0; r < 16; ++r) s += acc[n][r];
   if (s == 12345.678f) sink[threadIdx.x] = s;   // keeps the loop alive; practically never true
+}
+
+// Eight independent chains of y = 2^(-y) per lane (converges to 0.64; the rate does not depend
+// on the values), two wavefronts per SIMD.
+__global__ __launch_bounds__(kThreads) void exp_loop(float* __restrict__ sink, int iters) {
+  float y[8];
+  for (int n = 0; n < 8; ++n) y[n] = 0.1f * (float)(n + 1) + 1e-3f * (float)threadIdx.x;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int n = 0; n < 8; ++n) y[n] = __builtin_amdgcn_exp2f(-y[n]);
+  }
+  float s = 0.f;
+  for (int n = 0; n < 8; ++n) s += y[n];
+  if (s == 12345.678f) sink[threadIdx.x] = s;
+}
+
+// Exponentials per second (in units of 1e12), one timed batch of launches after a warm-up.
+static double exp_rate_tera(float* sink) {
+  const int iters = 20000, grid = 2048, launches = 10;
+  hipEvent_t e0, e1;
+  CHECK(hipEventCreate(&e0));
+  CHECK(hipEventCreate(&e1));
+  exp_loop<<<grid, kThreads>>>(sink, iters);
+  CHECK(hipEventRecord(e0));
+  for (int i = 0; i < launches; ++i) exp_loop<<<grid, kThreads>>>(sink, iters);
+  CHECK(hipEventRecord(e1));
+  CHECK(hipEventSynchronize(e1));
+  float ms = 0.f;
+  CHECK(hipEventElapsedTime(&ms, e0, e1));
+  CHECK(hipEventDestroy(e0));
+  CHECK(hipEventDestroy(e1));
+  return (double)launches * grid * kThreads * iters * 8 / (ms * 1e-3) / 1e12;
 }
 
 // Sustained TFLOP/s over the second half of `seconds` of back-to-back launches.
@@ -94,8 +129,10 @@ int main(int argc, char** argv) {
     CHECK(hipMemcpy(src, host.data(), n_elems * 2, hipMemcpyHostToDevice));
     rate[random] = sustained_tflops(src, sink, seconds);
   }
-  printf("{\"constant_operands_tflops\": %.1f, \"random_operands_tflops\": %.1f, \"seconds_each\": %.2f}\n",
-         rate[0], rate[1], seconds);
+  const double exp_tera = exp_rate_tera(sink);
+  printf("{\"constant_operands_tflops\": %.1f, \"random_operands_tflops\": %.1f, \"seconds_each\": %.2f, "
+         "\"exp2_only_tera_per_s\": %.2f}\n",
+         rate[0], rate[1], seconds, exp_tera);
   CHECK(hipFree(src));
   CHECK(hipFree(sink));
   return 0;
