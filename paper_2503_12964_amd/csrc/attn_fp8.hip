@@ -28,7 +28,7 @@ namespace {
 constexpr int kF8Unit = 64;
 constexpr int kF8Waves = 8;
 constexpr int kF8Rows = kF8Waves * 32;   // query rows per workgroup
-constexpr int kF8Ring = 3;
+constexpr int kF8Ring = 4;
 constexpr float kF8Ln2 = 0.6931471805599453f;
 constexpr float kF8PShift = 6.0f;        // P is stored as 2^6 P
 constexpr float kF8SafeSum = 448.0f;     // largest finite E4M3: bounds every scaled P of the unit
@@ -240,27 +240,15 @@ void attn_fwd_fp8_kernel(const unsigned char* __restrict__ q8, const unsigned ch
   issue_unit(0, 0);
   issue_unit(1, 1);
 
-  // One unit; the ring slot is a compile-time constant so that every LDS offset is an immediate.
-  auto unit_body = [&](auto slot_c, int u) {
-    constexpr int SLOT = decltype(slot_c)::value;
-    wait_vmcnt<2>();          // unit u has landed (unit u+1 may still be in flight) ...
-    __syncthreads();          // ... for every wave, and every wave is done with unit u-1
-    issue_unit(u + 2, (SLOT + 2) % kF8Ring);
-    const char* kt = smem + SLOT * 2 * UB;
-    const char* vt = kt + UB;
-
-    // ---- S^T for the unit's two 32-key tiles
-    f32x16 s[2];
+  // ---- the three stages of a unit
+  f32x16 s[2];     // S^T(u) - m_ref for the unit's two 32-key tiles
+  i32x8 pb;        // P(u), scaled by 2^6, as E4M3
+  auto scores = [&](const char* kt, int u) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)
         s[t] = mfma_f8(lds_read_32b(kt, koff[t][ks][0], koff[t][ks][1]), qreg[ks], ks == 0 ? minit : s[t]);
-    // V^T operands requested in the shadow of the score instructions
-    i32x8 va[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db) va[db] = lds_read_32b(vt, voff[db][0], voff[db][1]);
-
     const int j0 = seg_a + u * kF8Unit;
     if (j0 + kF8Unit > seg_b) {       // keys past the clip end (last unit only)
 #pragma unroll
@@ -269,7 +257,9 @@ void attn_fwd_fp8_kernel(const unsigned char* __restrict__ q8, const unsigned ch
         for (int r = 0; r < 16; ++r)
           if (j0 + 32 * t + 8 * (r >> 2) + 4 * g + (r & 3) >= seg_b) s[t][r] = -INFINITY;
     }
-    // ---- scaled exponentials against the current reference (s already holds score - m_ref)
+  };
+  auto softmax = [&](int u) {
+    // scaled exponentials against the current reference (s already holds score - m_ref)
     float p[2][16];
     float lsum = 0.f;
 #pragma unroll
@@ -309,23 +299,62 @@ void attn_fwd_fp8_kernel(const unsigned char* __restrict__ q8, const unsigned ch
         for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
     }
     l_run += lsum;
-    i32x8 pb;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int w = 0; w < 4; ++w)
         pb[4 * t + w] = (int)pack_fp8x4(p[t][4 * w], p[t][4 * w + 1], p[t][4 * w + 2], p[t][4 * w + 3]);
-
-    // ---- O^T += V^T P^T
+  };
+  auto accumulate = [&](const char* vt) {   // O^T += V^T P^T
+    i32x8 va[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) va[db] = lds_read_32b(vt, voff[db][0], voff[db][1]);
 #pragma unroll
     for (int db = 0; db < DB; ++db) oacc[db] = mfma_f8(va[db], pb, oacc[db]);
   };
-  static_assert(kF8Ring == 3, "the unit loop is unrolled over the ring");
-  for (int u = 0; u < n_u; u += 3) {
-    unit_body(IntC<0>{}, u);
-    if (u + 1 < n_u) unit_body(IntC<1>{}, u + 1);
-    if (u + 2 < n_u) unit_body(IntC<2>{}, u + 2);
-  }
+
+  // ---- the unit loop.  A workgroup barrier per unit keeps the two wavefronts of a SIMD in step,
+  // so if both ran the stages in the same order they would want the matrix pipe at the same
+  // time and the VALU at the same time (measured: the two add up).  Instead waves 0-3
+  // ("leaders") and 4-7 ("followers", the other wave of each SIMD) run them in opposite phase
+  // between two barriers:
+  //     leader  :  PV(u-1), S(u)   [matrix pipe]   then   softmax(u)       [VALU]
+  //     follower:  softmax(u-1)    [VALU]          then   PV(u-1), S(u)    [matrix pipe]
+  // Both read K(u) and V(u-1) in interval u; the loads issued there bring unit u+2 into the
+  // slot of unit u-2 (ring of four).  SLOT = u % 4 is a compile-time constant so that every
+  // LDS offset is an immediate.
+  static_assert(kF8Ring == 4, "the unit loop is unrolled over the ring");
+  auto interval = [&](auto slot_c, auto lead_c, auto first_c, int u) {
+    constexpr int SLOT = decltype(slot_c)::value;
+    constexpr bool LEAD = decltype(lead_c)::value != 0;
+    constexpr bool FIRST = decltype(first_c)::value != 0;
+    wait_vmcnt<2>();          // unit u has landed (unit u+1 may still be in flight) ...
+    __syncthreads();          // ... for every wave, and every wave is done with unit u-2
+    issue_unit(u + 2, (SLOT + 2) % kF8Ring);
+    const char* kt = smem + SLOT * 2 * UB;
+    const char* vt_prev = smem + ((SLOT + kF8Ring - 1) % kF8Ring) * 2 * UB + UB;
+    if constexpr (LEAD) {
+      if constexpr (!FIRST) accumulate(vt_prev);
+      scores(kt, u);
+      softmax(u);
+    } else {
+      if constexpr (!FIRST) { softmax(u - 1); accumulate(vt_prev); }
+      scores(kt, u);
+    }
+  };
+  auto run = [&](auto lead_c) {
+    interval(IntC<0>{}, lead_c, IntC<1>{}, 0);
+    for (int u = 1; u < n_u; u += 4) {
+      interval(IntC<1>{}, lead_c, IntC<0>{}, u);
+      if (u + 1 < n_u) interval(IntC<2>{}, lead_c, IntC<0>{}, u + 1);
+      if (u + 2 < n_u) interval(IntC<3>{}, lead_c, IntC<0>{}, u + 2);
+      if (u + 3 < n_u) interval(IntC<0>{}, lead_c, IntC<0>{}, u + 3);
+    }
+    // drain: the last unit's remaining stages (its V unit is still in its slot)
+    if constexpr (decltype(lead_c)::value == 0) softmax(n_u - 1);
+    accumulate(smem + ((n_u - 1) % kF8Ring) * 2 * UB + UB);
+  };
+  if (wave < kF8Waves / 2) run(IntC<1>{}); else run(IntC<0>{});
   wait_vmcnt<0>();   // no load may still be writing LDS when the workgroup ends
 
   // ---- epilogue: out = O * (v dequantisation scale) / l, lse in natural-log units

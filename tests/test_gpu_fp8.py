@@ -9,7 +9,7 @@ import pytest
 from oracle import vfm_oracle as orc
 from paper_2503_12964_amd import workloads as W
 from tests import parity_utils as U
-from tests.test_gpu_parity import SMALL, _binding
+from tests.test_gpu_parity import SMALL, _binding, _custom
 
 pytestmark = pytest.mark.gpu
 
@@ -76,9 +76,16 @@ def _pack(b, wl):
     return inp, (q8, k8, vT8)
 
 
-@pytest.mark.parametrize("name", ["ragged128", "ragged64"])
+# clips of 3, 4, 6, 7, 8 and 10 key units (64 keys each): every way the unit loop, which is
+# unrolled four times after its first unit, can end; the last two span more than one query tile
+FP8_CASES = dict(SMALL)
+FP8_CASES["units_mix"] = _custom("units_mix", [(1, 10, 13), (1, 16, 16), (1, 15, 22), (1, 20, 20), (2, 16, 16),
+                                               (1, 23, 27)], 2, 128, (32, 48, 48), 21)
+
+
+@pytest.mark.parametrize("name", ["ragged128", "ragged64", "units_mix"])
 def test_pack_is_bit_exact_and_attention_matches_oracle(name):
-    wl = SMALL[name]
+    wl = FP8_CASES[name]
     b = _binding()
     inp, (q8, k8, vT8) = _pack(b, wl)
     nq, nk, nv = b.vfm_fp8_pack_sizes(wl.cu_seqlens, wl.n_heads, wl.head_dim)
