@@ -6,7 +6,7 @@ tokens: vfm_rope3d(q), vfm_rope3d(k), vfm_attn_fwd, vfm_attn_bwd.  The default
 workload is the 720p-class 121-frame latent (T,H,W = 16,44,80 -> 56,320 tokens,
 32 heads, head_dim 128, bf16).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--no-cpu-baseline] [--no-constant-run]
 
 --workload NAME-spatial (e.g. C4-spatial) runs the spatial-attention view of a workload
 (Section 4.6 of the paper): RoPE on the clips' grids, attention with one sequence per latent
@@ -274,6 +274,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mfma-ceiling", action="store_true",
                     help="skip the MFMA-only ceiling measurement (about 3 s of GPU time)")
+    ap.add_argument("--no-constant-run", action="store_true",
+                    help="skip the extra attention run on constant inputs (reported beside the roofline)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy (the known-size kernel that scales "
                          "the FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -430,6 +432,25 @@ def main() -> int:
         "fwd_frac_hbm_peak": 4 * elems / (ms_nf * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "bwd_ms": ms_nb, "bwd_gbs": 6 * elems / (ms_nb * 1e-3) / 1e9,
         "bwd_frac_hbm_peak": 6 * elems / (ms_nb * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    # Not part of the timed step either: the same attention calls on constant inputs (every element
+    # 1.0).  Nothing changes but the operand bits; the matrix pipe draws less power when its inputs
+    # do not toggle and the chip keeps its clock, so this shows how much of the gap to the published
+    # peak is the power limit and how much is the kernels' own schedule.  Skipped under a profiler
+    # (it would mix into the per-kernel averages).
+    if not args.no_constant_run and not any(name.startswith("ROCPROF") for name in os.environ):
+        for x in (q, k, v, do):
+            x.fill_(1.0)
+
+        def attn_only():
+            B.vfm_attn_fwd(q, k, v, cu_attn, wl.scale, out=out, lse=lse)
+            if wl.backward:
+                B.vfm_attn_bwd(q, k, v, out, lse, do, cu_attn, wl.scale, dq=dq, dk=dk, dv=dv, workspace=ws)
+        ms_const = _timed(attn_only, n=3)
+        result["roofline"]["constant_operand_run"] = {
+            "ms": ms_const, "tflops": f_all / (ms_const * 1e-3) / 1e12,
+            "same_calls_on_the_synthetic_data_ms": ms_fwd + ms_bwd,
+            "note": "vfm_attn_fwd (+ vfm_attn_bwd) with q = k = v = dout = 1.0: same kernels, same launch, "
+                    "only the operand bits differ"}
     del q, k, v, do, out, dq, dk, dv, ws, t
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline and not spatial:
