@@ -699,6 +699,332 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
   }
 }
 
+// ---------------------------------------------------------------- dQ, 64 query rows per wavefront
+// Same mathematics as attn_bwd_dq_kernel, built to halve its LDS operand traffic (under this
+// chip's power limit the energy per flop is what bounds the kernels, and one LDS operand read
+// per MFMA is a third of it): a wavefront owns two 32-row query blocks, so every K, V row
+// operand and every K^T operand read from LDS feeds two MFMAs.  That needs 512 registers,
+// i.e. one wavefront per SIMD, with the register classes chosen by hand: Q, dO rows (128) and
+// the dQ^T accumulators (128) live in AGPRs, which the MFMAs address directly; S^T, dP^T and
+// everything the VALU touches live in VGPRs.  All MFMAs are therefore assembly statements.
+// With a single wavefront per SIMD nothing else hides the VALU work, so the two query blocks
+// alternate ("half-steps"): while the VALU turns block IB's S^T, dP^T of key block b into
+// dS^T, the matrix pipe runs the other block's MFMAs,
+//     groups  0..15 : S^T, dP^T of the other block's next key block   (assembly, VGPR results)
+//     groups 16..23 : dQ^T += K^T dS^T of the other block's previous key block
+// one group per MFMA; register tuples passed through the statements pin one element of the
+// VALU work to each group.  The compiler inserts no wait states for readers of an assembly
+// MFMA's result: S^T, dP^T are read a half-step later (>= 8 MFMAs), the accumulators after
+// explicit wait states at the end.
+// K/V tiles of 64 keys go through a ring of three LDS stages: tile t is read from the second
+// half of key block 2t-1 to the end of key block 2t+1, the workgroup meets once per tile at
+// the start of key block 2t-1 (tile t landed, everybody done with tile t-2) and requests
+// tile t+1 there.
+constexpr int kDq2Waves = 4;
+constexpr int kDq2Ring = 3;
+
+template <int D>
+struct Dq2Cfg {
+  static constexpr int kBR = kDq2Waves * 64;                 // query rows per workgroup
+  static constexpr int kTileBytes = kDqBC * D * 2;           // one K or V tile
+  static constexpr int kStageBytes = 2 * kTileBytes;         // K tile, V tile
+  static constexpr int kLdsBytes = kDq2Ring * kStageBytes;
+  static constexpr int kChunksPerRow = D / 8;
+  static constexpr int kChunksPerThread = kDqBC * kChunksPerRow / (kDq2Waves * 64);
+};
+
+// dQ^T accumulation as assembly: accumulator in AGPRs, both operands in VGPRs; the three
+// tuples are passed through unchanged (see mfma32_v).
+__device__ __forceinline__ void mfma32_acc(f32x16& acc, const bf16x8& a, const bf16x8& b,
+                                           f32x16& f0, f32x16& f1, u32x8& f2) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %4, %5, %0"
+               : "+a"(acc), "+v"(f0), "+v"(f1), "+v"(f2) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma32_acc(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+template <int D, class Segs>
+__global__ __launch_bounds__(kDq2Waves * 64, 1)
+void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                         const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
+                         const float* __restrict__ lse2g, const float* __restrict__ delta,
+                         __bf16* __restrict__ dq, const Segs segs, const UnitMap um,
+                         int total, int n_heads, float scale, float scale_log2) {
+  using Cfg = Dq2Cfg<D>;
+  constexpr int KS = D / 16;
+  constexpr int DB = D / 32;
+  constexpr int CPT = Cfg::kChunksPerThread;
+  constexpr int RB = D * 2;
+  constexpr int TB = Cfg::kTileBytes;
+  constexpr int SB = Cfg::kStageBytes;
+  constexpr int NG = 2 * KS + 2 * DB;   // MFMAs (groups) per half-step
+  static_assert(D == 128, "tuned for head_dim 128");
+
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  int head, tile;
+  if (!map_unit(um, blockIdx.x, head, tile)) return;
+  int seq, tq;
+  locate_tile<false>(segs, Cfg::kBR, tile, seq, tq);
+  const int q_b = segs.q_start(seq) + segs.q_len(seq);
+  const int q0 = segs.q_start(seq) + tq * Cfg::kBR;
+  const int seg_a = segs.kv_start(seq);
+  const int seg_b = seg_a + segs.kv_len(seq);
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
+  const int lane = tid & 63;
+  const int c = lane & 31;
+  const int g = lane >> 5;
+  const size_t row_stride = (size_t)n_heads * D;
+  const size_t head_off = (size_t)head * D;
+  const __bf16* kbase = k + head_off;
+  const __bf16* vbase = v + head_off;
+
+  // ---- Q and dO rows of the two query blocks as B operands (AGPRs); lse, Delta per lane
+  bf16x8 qreg[2][KS], doreg[2][KS];
+  float lse2[2], dlt[2];
+  int qrow[2];
+#pragma unroll
+  for (int ib = 0; ib < 2; ++ib) {
+    qrow[ib] = q0 + (wave * 2 + ib) * 32 + c;
+    const int r = min(qrow[ib], q_b - 1);
+    const size_t off = (size_t)r * row_stride + head_off + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      qreg[ib][ks] = *reinterpret_cast<const bf16x8*>(q + off + ks * 16);
+      doreg[ib][ks] = *reinterpret_cast<const bf16x8*>(dout + off + ks * 16);
+    }
+    lse2[ib] = lse2g[(size_t)head * total + r];
+    dlt[ib] = delta[(size_t)head * total + r];
+  }
+
+  // ---- K/V staging with direct global->LDS loads; tiles are requested in sequence
+  const uint32_t row_bytes = (uint32_t)row_stride * 2u;
+  const uint32_t last_row_off = (uint32_t)(seg_b - 1) * row_bytes;
+  uint32_t st_rowoff[CPT], st_colb[CPT];
+#pragma unroll
+  for (int x = 0; x < CPT; ++x) {
+    const int p = (x * kDq2Waves + wave) * 64 + lane;
+    const int r = p / Cfg::kChunksPerRow;
+    st_rowoff[x] = (uint32_t)(seg_a + r) * row_bytes;
+    st_colb[x] = (uint32_t)(((p % Cfg::kChunksPerRow) ^ swz<D>(r)) * 16);
+  }
+  const uint32_t smem_addr = lds_addr_of(smem);
+  const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(smem_addr + wave * 1024);
+  auto issue_tile = [&](int stage) {
+#pragma unroll
+    for (int x = 0; x < CPT; ++x) {
+      const uint32_t off = min(st_rowoff[x], last_row_off) + st_colb[x];
+      const uint32_t dst = wave_lds + stage * SB + x * kDq2Waves * 1024;
+      lds_dma16(kbase, off, dst);
+      lds_dma16(vbase, off, dst + TB);
+      st_rowoff[x] += kDqBC * row_bytes;
+    }
+  };
+
+  // ---- swizzled LDS addresses, one register each (opaque, so they are kept, not recomputed)
+  uint32_t rb[KS], tb[2][DB];
+  {
+    const int rbase = tile_off<D>(c, 8 * g);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      rb[ks] = smem_addr + (rbase ^ (ks << 5));
+      asm volatile("" : "+v"(rb[ks]));
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int tbase = tile_off<D>(8 * t + 4 * g + ((lane & 15) >> 2), 16 * ((lane >> 4) & 1) + 4 * (lane & 3));
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        tb[t][db] = smem_addr + (tbase ^ (db << 6));
+        asm volatile("" : "+v"(tb[t][db]));
+      }
+    }
+  }
+
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  f32x16 dqacc[2][DB];
+#pragma unroll
+  for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) dqacc[ib][db] = zero16;
+
+  const int n_tiles = (seg_b - seg_a + kDqBC - 1) / kDqBC;
+  const int n_blocks = 2 * n_tiles;
+  const int tail_rows = seg_b - seg_a - (n_tiles - 1) * kDqBC;   // valid rows of the last tile
+
+#pragma unroll
+  for (int ib = 0; ib < 2; ++ib)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) { to_agpr(qreg[ib][ks]); to_agpr(doreg[ib][ks]); }
+#pragma unroll
+  for (int ib = 0; ib < 2; ++ib) asm volatile("" :: "v"(lse2[ib]), "v"(dlt[ib]));
+  issue_tile(0);
+  issue_tile(1);              // (re-requests the last rows when the clip has a single tile)
+  wait_vmcnt<2 * CPT>();      // tile 0 has landed
+  __syncthreads();
+
+  // ---- state carried between half-steps
+  f32x16 sacc[2], dpacc[2];   // S^T, dP^T of the current key block, per query block
+  f32x16 dsf;                 // dS^T of the half-step at hand, fp32
+  u32x8 pw[2];                // dS^T as bf16 pairs, per query block: B operands of the update
+  bf16x8 ka[KS], va[KS];      // row operands of the key block whose scores come next
+  s16x4 klo[2][DB], khi[2][DB];   // K^T operands of the key block whose update comes next
+#pragma unroll
+  for (int i = 0; i < 8; ++i) { pw[0][i] = 0u; pw[1][i] = 0u; }
+#pragma unroll
+  for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) { klo[s2][db] = s16x4{0, 0, 0, 0}; khi[s2][db] = s16x4{0, 0, 0, 0}; }
+  dsf = zero16;
+
+  // prologue: row operands of key block 0, S^T and dP^T of (key block 0, query block 0)
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    ka[ks] = lds_read_b128_at(rb[ks]);
+    va[ks] = lds_read_b128_at(rb[ks] + TB);
+  }
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    mfma32_v(sacc[0], ka[ks], qreg[0][ks], ks == 0);
+    mfma32_v(dpacc[0], va[ks], doreg[0][ks], ks == 0);
+  }
+  sacc[1] = zero16;
+  dpacc[1] = zero16;
+
+  // One half-step.  POSB = b % 6 fixes every LDS stage at compile time; IB is the query block
+  // whose dS^T the VALU forms.
+  auto half_step = [&](auto posb_c, auto ib_c, int b) {
+    constexpr int POSB = decltype(posb_c)::value;
+    constexpr int IB = decltype(ib_c)::value;
+    constexpr int OB = 1 - IB;                               // the block the matrix pipe works for
+    constexpr int ST_CUR = (POSB / 2) % kDq2Ring;            // stage of key block b
+    constexpr int ST_NEXT = ((POSB + 1) / 2) % kDq2Ring;     // stage of key block b+1
+    constexpr int JB_CUR = POSB & 1, JB_NEXT = (POSB + 1) & 1;
+    const float lse_i = lse2[IB], dlt_i = dlt[IB];
+#pragma unroll
+    for (int gi = 0; gi < NG; ++gi) {
+      // ---- matrix pipe
+      if (gi < 2 * KS) {
+        const int ks = gi >> 1;
+        if ((gi & 1) == 0) mfma32_v(sacc[OB], ka[ks], qreg[OB][ks], ks == 0, sacc[IB], dsf, pw[IB]);
+        else mfma32_v(dpacc[OB], va[ks], doreg[OB][ks], ks == 0, sacc[IB], dsf, pw[IB]);
+      } else {
+        const int s2 = (gi - 2 * KS) / DB, db = (gi - 2 * KS) % DB;
+        const u32x4 w = {pw[OB][4 * s2], pw[OB][4 * s2 + 1], pw[OB][4 * s2 + 2], pw[OB][4 * s2 + 3]};
+        mfma32_acc(dqacc[OB][db], join_tr(klo[s2][db], khi[s2][db]), __builtin_bit_cast(bf16x8, w),
+                   sacc[IB], dsf, pw[IB]);
+      }
+      // ---- LDS reads
+      if (IB == 0) {
+        // row operands of key block b+1, once the score MFMAs have consumed those of block b
+        if (gi >= 2 * KS) {
+          constexpr int per = (2 * KS) / (2 * DB);   // reads per group: 16 / 8
+#pragma unroll
+          for (int x = (gi - 2 * KS) * per; x < (gi - 2 * KS + 1) * per; ++x) {
+            const int ks = x >> 1;
+            const uint32_t a = rb[ks] + ST_NEXT * SB + JB_NEXT * 32 * RB;
+            if ((x & 1) == 0) ka[ks] = lds_read_b128_at(a); else va[ks] = lds_read_b128_at(a + TB);
+          }
+        }
+      } else {
+        // K^T operands of key block b (the updates of block b-1 were all issued a half-step ago)
+        if (gi < 2 * DB) {
+#pragma unroll
+          for (int x = 2 * gi; x < 2 * gi + 2; ++x) {
+            const int s2 = x / (2 * DB), db = (x >> 1) % DB, hi = x & 1;
+            const uint32_t a = tb[hi][db] + ST_CUR * SB + (JB_CUR * 32 + 16 * s2) * RB;
+            if (hi) khi[s2][db] = lds_read_tr_at(a); else klo[s2][db] = lds_read_tr_at(a);
+          }
+        }
+      }
+      // ---- VALU: one element of dS^T per group (keys i = 8*(e/4) + 4g + e%4 of the block, this
+      // lane's query row): the exponential in group G(e), the product one group later (no
+      // stall on the transcendental's result), the conversion of a pair one group after that
+#pragma unroll
+      for (int e = 1; e < 16; e += 2)
+        if (1 + e * (NG - 2) / 16 + 2 == gi) {
+          const f32x2 pr = {dsf[e - 1], dsf[e]};
+          pw[IB][e >> 1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pr, bf16x2));
+        }
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (1 + e * (NG - 2) / 16 + 1 == gi) dsf[e] = dsf[e] * (dpacc[IB][e] - dlt_i);
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (1 + e * (NG - 2) / 16 == gi) dsf[e] = fast_exp2(sacc[IB][e] * scale_log2 - lse_i);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  auto block = [&](auto posb_c, int b) {
+    constexpr int POSB = decltype(posb_c)::value;
+    if constexpr ((POSB & 1) == 1) {
+      // key block 2t-1: tile t has landed for every wave, every wave is done with tile t-2,
+      // whose stage takes tile t+1
+      const int t = (b + 1) >> 1;
+      if (t < n_tiles) {
+        wait_vmcnt<0>();
+        __syncthreads();
+        if (t + 1 < n_tiles) issue_tile(((POSB + 1) / 2 + 1) % kDq2Ring);
+      }
+    }
+    half_step(posb_c, IntC<0>{}, b);
+    if constexpr ((POSB & 1) == 0) {
+      // Keys past the clip's end (last tile only).  Their K, V rows were fetched as copies of
+      // the last valid row, so their S^T, dP^T are finite and so is dS^T; what keeps them out
+      // of dQ is a zero K^T column.  All row reads of this tile have been issued by now and
+      // its first K^T read follows: zero those K rows in LDS in between.
+      if (b == n_blocks - 2 && tail_rows < kDqBC) {
+        __syncthreads();
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        const int n16 = (kDqBC - tail_rows) * (RB / 16);
+        for (int i = tid; i < n16; i += kDq2Waves * 64)
+          *reinterpret_cast<__attribute__((address_space(3))) u32x4*>(
+              smem_addr + ((POSB / 2) % kDq2Ring) * SB + tail_rows * RB + i * 16) = z;
+        __syncthreads();
+      }
+    }
+    half_step(posb_c, IntC<1>{}, b);
+  };
+  for (int b = 0; b < n_blocks; b += 6) {
+    block(IntC<0>{}, b);
+    block(IntC<1>{}, b + 1);
+    if (b + 2 < n_blocks) { block(IntC<2>{}, b + 2); block(IntC<3>{}, b + 3); }
+    if (b + 4 < n_blocks) { block(IntC<4>{}, b + 4); block(IntC<5>{}, b + 5); }
+  }
+  // drain: the last key block's update for query block 1
+#pragma unroll
+  for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const u32x4 w = {pw[1][4 * s2], pw[1][4 * s2 + 1], pw[1][4 * s2 + 2], pw[1][4 * s2 + 3]};
+      mfma32_acc(dqacc[1][db], join_tr(klo[s2][db], khi[s2][db]), __builtin_bit_cast(bf16x8, w));
+    }
+  wait_vmcnt<0>();   // no load may still be writing LDS when the workgroup ends
+  // the accumulators were written by assembly: wait out the last MFMA before they are read
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+
+  // ---- epilogue: dq = bf16(scale * dQ^T)
+#pragma unroll
+  for (int ib = 0; ib < 2; ++ib) {
+    const int i = qrow[ib];
+    if (i < q_b) {
+      __bf16* op = dq + (size_t)i * row_stride + head_off + 4 * g;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          f32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = dqacc[ib][db][q4 * 4 + e] * scale;
+          *reinterpret_cast<bf16x4*>(op + db * 32 + q4 * 8) = to_bf16x4(o);
+        }
+    }
+  }
+}
+
 template <int D, class Segs>
 static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, const void* out,
                                const float* lse, const void* dout, const Segs& segs, int total,
@@ -763,7 +1089,23 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
       if ((e = hipGetLastError()) != hipSuccess) return e;
     }
   }
-  {
+  if constexpr (D == 128) {
+    using Cfg = Dq2Cfg<D>;
+    const int tiles = count_tiles<false>(segs, Cfg::kBR);
+    if (tiles == 0) return hipSuccess;
+    UnitMap um;
+    um.tiles_per_head = tiles;
+    um.n_units = tiles * n_heads;
+    um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
+    auto kern = attn_bwd_dq2_kernel<D, Segs>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+    if (e != hipSuccess) return e;
+    kern<<<um.chunk * kNumXcd, kDq2Waves * 64, Cfg::kLdsBytes, stream>>>(
+        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse2, delta,
+        (__bf16*)dq, segs, um, total, n_heads, scale, scale * kLog2eB);
+    return hipGetLastError();
+  } else {
     constexpr int NI = 1;
     constexpr int W = 8;   // 256 query rows share each staged K/V tile
     using Cfg = DqCfg<D, NI, W>;
