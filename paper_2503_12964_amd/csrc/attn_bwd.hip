@@ -85,33 +85,6 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const u32x4* __restric
 constexpr int kBwdRing = 3;
 constexpr int kSgValuB = 0x002, kSgMfmaB = 0x008, kSgDsReadB = 0x100;
 
-// S and dP MFMAs of the dK/dV kernel, issued as assembly: the kernel needs more than 256
-// registers, for which the compiler gives every MFMA an AGPR destination and then copies
-// each score (VALU cannot read AGPRs).  Here the destination is a VGPR tuple and the
-// loop-invariant K/V operand an AGPR tuple instead.  The compiler does not know that this
-// is an MFMA, so it inserts no wait states for readers of d: every reader must be at
-// least two MFMAs downstream in program order (the kernel reads d one iteration later).
-__device__ __forceinline__ void mfma32_v(f32x16& d, const bf16x8& a, const bf16x8& b, bool first) {
-  if (first) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
-  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
-}
-// The same with three register tuples passed through unchanged.  Volatile statements keep
-// their program order, so arithmetic that reads f0/f1/f2 after this call cannot be moved
-// before the MFMA, and arithmetic that produced them cannot be moved after it: this is how
-// the VALU work is spread evenly between the MFMAs.
-typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
-__device__ __forceinline__ void mfma32_v(f32x16& d, const bf16x8& a, const bf16x8& b, bool first,
-                                         f32x16& f0, f32x16& f1, u32x8& f2) {
-  if (first) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %4, %5, 0"
-                          : "=&v"(d), "+v"(f0), "+v"(f1), "+v"(f2) : "v"(a), "a"(b));
-  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %4, %5, %0"
-                    : "+v"(d), "+v"(f0), "+v"(f1), "+v"(f2) : "v"(a), "a"(b));
-}
-
-// Rebinds a loaded operand to an AGPR tuple (and, like settle(), makes the compiler wait
-// for its global load here).
-__device__ __forceinline__ void to_agpr(bf16x8& x) { asm volatile("" : "=a"(x) : "0"(x)); }
-
 template <int D>
 struct BwdCfg {
   static constexpr int kTileBytes = kBwdBQ * D * 2;                      // one Q or dO tile
@@ -733,17 +706,6 @@ struct Dq2Cfg {
   static constexpr int kChunksPerThread = kDqBC * kChunksPerRow / (kDq2Waves * 64);
 };
 
-// dQ^T accumulation as assembly: accumulator in AGPRs, both operands in VGPRs; the three
-// tuples are passed through unchanged (see mfma32_v).
-__device__ __forceinline__ void mfma32_acc(f32x16& acc, const bf16x8& a, const bf16x8& b,
-                                           f32x16& f0, f32x16& f1, u32x8& f2) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %4, %5, %0"
-               : "+a"(acc), "+v"(f0), "+v"(f1), "+v"(f2) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma32_acc(f32x16& acc, const bf16x8& a, const bf16x8& b) {
-  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
-
 template <int D, class Segs>
 __global__ __launch_bounds__(kDq2Waves * 64, 1)
 void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
@@ -1004,7 +966,8 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
     }
   wait_vmcnt<0>();   // no load may still be writing LDS when the workgroup ends
   // the accumulators were written by assembly: wait out the last MFMA before they are read
-  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+  for (int ib = 0; ib < 2; ++ib) wait_mfma_a(dqacc[ib][0], dqacc[ib][1], dqacc[ib][2], dqacc[ib][3]);
 
   // ---- epilogue: dq = bf16(scale * dQ^T)
 #pragma unroll

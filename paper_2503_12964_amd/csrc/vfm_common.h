@@ -243,6 +243,59 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// ---- MFMAs issued as assembly, for kernels that need more than 256 registers -------------
+// In such a kernel the compiler gives every MFMA it selects an AGPR destination and then
+// copies each score to a VGPR (VALU cannot read AGPRs).  Score MFMAs are therefore written as
+// assembly with a VGPR destination and the loop-invariant B operand in an AGPR tuple (which
+// an MFMA may read directly).  The compiler does not know that the statement is an MFMA, so
+// it inserts no wait states for readers of d: every reader must be at least two MFMAs
+// downstream in program order.
+__device__ __forceinline__ void mfma32_v(f32x16& d, const bf16x8& a, const bf16x8& b, bool first) {
+  if (first) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+}
+// The same with three register tuples passed through unchanged.  Volatile statements keep
+// their program order, so arithmetic that reads f0/f1/f2 after this call cannot be moved
+// before the MFMA, and arithmetic that produced them cannot be moved after it: this is how
+// the VALU work is spread evenly between the MFMAs.
+typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ void mfma32_v(f32x16& d, const bf16x8& a, const bf16x8& b, bool first,
+                                         f32x16& f0, f32x16& f1, u32x8& f2) {
+  if (first) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %4, %5, 0"
+                          : "=&v"(d), "+v"(f0), "+v"(f1), "+v"(f2) : "v"(a), "a"(b));
+  else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %4, %5, %0"
+                    : "+v"(d), "+v"(f0), "+v"(f1), "+v"(f2) : "v"(a), "a"(b));
+}
+
+// Rebinds a loaded operand to an AGPR tuple (and, like settle(), makes the compiler wait
+// for its global load here).
+__device__ __forceinline__ void to_agpr(bf16x8& x) { asm volatile("" : "=a"(x) : "0"(x)); }
+
+// Accumulation as assembly: accumulator in an AGPR tuple, both operands in VGPRs; the tuples
+// are passed through unchanged (see mfma32_v).  Readers of acc other than the next
+// accumulation into it must wait out the MFMA themselves.
+__device__ __forceinline__ void mfma32_acc(f32x16& acc, const bf16x8& a, const bf16x8& b,
+                                           f32x16& f0, f32x16& f1, u32x8& f2) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %4, %5, %0"
+               : "+a"(acc), "+v"(f0), "+v"(f1), "+v"(f2) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma32_acc(f32x16& acc, const bf16x8& a, const bf16x8& b) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+
+// Wait states after assembly MFMAs, before code the compiler generates reads their results (it
+// does not know they were MFMA results).  The tuples are passed through, so that their readers
+// cannot be scheduled above the wait.
+__device__ __forceinline__ void wait_mfma_v(f32x16& a) {
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(a));
+}
+__device__ __forceinline__ void wait_mfma_v(f32x16& a, f32x16& b) {
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void wait_mfma_a(f32x16& a, f32x16& b, f32x16& c, f32x16& d) {
+  asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(a), "+a"(b), "+a"(c), "+a"(d));
+}
+
 // ---- launchers (defined next to their kernels) -----------------------------
 hipError_t launch_rope3d(void* x, const RopeTable& tab, int total, int n_heads, int head_dim,
                          int dim_t, int dim_h, int dim_w, float theta, int inverse,
