@@ -46,7 +46,7 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel from `rocprofv3 --pmc` (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"C4": 27.22e9}
+MEASURED_TRAFFIC_BYTES = {"C4": 27.66e9}
 
 
 def _mfma_ceiling(seconds: float = 1.5):
@@ -161,7 +161,7 @@ def _bench_cross(args, wl) -> int:
                       "bwd_tflops": achieved,
                       "fwd_min_hbm_gbs": 2 * row_bytes / (ms_fwd * 1e-3) / 1e9,
                       "bwd_min_hbm_gbs": 4 * row_bytes / (ms_bwd * 1e-3) / 1e9},
-        "roofline": {"bound": "mfma", "kernel": "attn_bwd_dkdv_kernel + attn_bwd_dq_kernel (cross-attention tables)",
+        "roofline": {"bound": "mfma", "kernel": "attn_bwd_dkdv_kernel + attn_bwd_dq2_kernel (cross-attention tables)",
                      "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / BF16_MFMA_PEAK_TFLOPS, "traffic": None, "ms": ms_bwd,
                      "note": "short key ranges: the step also moves 6 x the query tensor through HBM, "
@@ -355,8 +355,8 @@ def main() -> int:
     value = f_all / (ms_step * 1e-3) / 1e12
     rope_bytes = 2 * 2 * wl.total_tokens * wl.n_heads * wl.head_dim * 2   # q and k, read + write
     if wl.backward:
-        dom, dom_flops, dom_ms = "attn_bwd_dkdv_kernel + attn_bwd_dq_kernel", f_bwd, ms_bwd
-        dom_note = ("vfm_attn_bwd call: bwd_prepare + attn_bwd_dkdv_kernel + attn_bwd_dq_kernel; "
+        dom, dom_flops, dom_ms = "attn_bwd_dkdv_kernel + attn_bwd_dq2_kernel", f_bwd, ms_bwd
+        dom_note = ("vfm_attn_bwd call: bwd_prepare + attn_bwd_dkdv_kernel + attn_bwd_dq2_kernel; "
                     "10*D algorithmic flops/pair/head (the two kernels execute 14*D)")
     else:
         dom, dom_flops, dom_ms = "attn_fwd_kernel", f_fwd, ms_fwd
