@@ -26,6 +26,9 @@ SMALL = {
                          (32, 48, 48), 11),
     # ragged clips at head_dim 64
     "ragged64": _custom("ragged64", [(2, 9, 15), (1, 5, 13), (1, 1, 2)], 2, 64, (16, 24, 24), 12),
+    # clip lengths around the kernels' 32-key blocks and 64-key tiles: 32, 64, 96, 128, 33, 65, 31, 63
+    "block_edges": _custom("block_edges", [(1, 4, 8), (1, 8, 8), (1, 8, 12), (2, 8, 8), (1, 3, 11), (1, 5, 13),
+                                           (1, 1, 31), (1, 7, 9)], 2, 128, (32, 48, 48), 13),
 }
 
 
