@@ -685,8 +685,8 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
 // dS^T, the matrix pipe runs the other block's MFMAs,
 //     groups  0..15 : S^T, dP^T of the other block's next key block   (assembly, VGPR results)
 //     groups 16..23 : dQ^T += K^T dS^T of the other block's previous key block
-// one group per MFMA; register tuples passed through the statements pin one element of the
-// VALU work to each group.  The compiler inserts no wait states for readers of an assembly
+// one group per MFMA; register tuples passed through the statements (the block's S^T, so that
+// nothing reads it early, and the VALU's results) pin one element of the VALU work to each group.  The compiler inserts no wait states for readers of an assembly
 // MFMA's result: S^T, dP^T are read a half-step later (>= 8 MFMAs), the accumulators after
 // explicit wait states at the end.
 // K/V tiles of 64 keys go through a ring of three LDS stages: tile t is read from the second
@@ -865,7 +865,12 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
     constexpr int ST_CUR = (POSB / 2) % kDq2Ring;            // stage of key block b
     constexpr int ST_NEXT = ((POSB + 1) / 2) % kDq2Ring;     // stage of key block b+1
     constexpr int JB_CUR = POSB & 1, JB_NEXT = (POSB + 1) & 1;
-    const float lse_i = lse2[IB], dlt_i = dlt[IB];
+    const float lse_i = lse2[IB];
+    // Delta is made a new value here: the subtractions dP - Delta then cannot be moved up into the
+    // previous half-step, where the MFMAs that produce dP are still running (dP itself is not
+    // passed through the statements)
+    float dlt_i = dlt[IB];
+    asm volatile("" : "+v"(dlt_i));
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
       // ---- matrix pipe
