@@ -44,7 +44,7 @@ extern "C" {
 
 #define VFM_MAX_SEQS 256    /* clips per call, self-attention and RoPE */
 #define VFM_MAX_XSEQS 128   /* sequences per call, cross-attention */
-#define VFM_MAX_TEMPORAL 16 /* latent frames per clip, temporal attention */
+#define VFM_MAX_TEMPORAL 32 /* latent frames per clip, temporal attention */
 
 #define VFM_API __attribute__((visibility("default")))
 

@@ -1,6 +1,7 @@
 // Temporal attention for gfx950: one sequence per (clip, pixel) made of that pixel's token
-// in every latent frame (T <= 16 rows, H*W tokens apart in the packed buffer), per head.
-// HBM-bound: the whole problem of one (pixel, head) is a 16 x 16 score tile.
+// in every latent frame (T <= 32 rows, H*W tokens apart in the packed buffer), per head.
+// HBM-bound: the whole problem of one (pixel, head) is a 16 x 16 score tile (a 32 x 32 one,
+// further down, when a clip has more than 16 frames).
 //
 // One wavefront owns one (pixel, head).  It gathers the T rows of q, k, v (and dout) into a
 // wave-private LDS tile with direct global->LDS loads (16-byte chunks, 256-byte rows, the same
@@ -15,6 +16,8 @@
 // it gets by issuing the score MFMAs twice with the operands swapped.
 // Rows past T are clamped copies of row T-1: as keys they are masked, as queries their
 // results are not stored and their P is zeroed where it would be summed into dK/dV.
+#include <algorithm>
+
 #include "vfm_common.h"
 
 namespace vfm {
@@ -268,24 +271,272 @@ __global__ __launch_bounds__(kTWaves * 64) void tattn_bwd_kernel(const __bf16* _
   }
 }
 
+// ---------------------------------------------------------------- 17..32 frames
+// The same scheme on a 32 x 32 score tile with the 32x32x16 MFMA (lane layouts as in the packed
+// attention kernels: an operand lane holds row l%32, columns ks*16 + 8*(l/32)..+7; an accumulator
+// lane holds column l%32, rows 8*(r/4) + 4*(l/32) + r%4 in its sixteen registers; a transposed
+// operand comes from two transposing LDS reads).  Used when some clip of the call has T > 16.
+namespace {
+
+constexpr int kT2Rows = 32;
+
+template <int D>
+struct T2Cfg {
+  static constexpr int kTileBytes = kT2Rows * D * 2;
+  static constexpr int kChunksPerRow = D / 8;
+  static constexpr int kLoadsPerTile = kT2Rows * kChunksPerRow / 64;
+};
+
+template <int D>
+__device__ __forceinline__ void gather_tile32(const __bf16* base, const TUnit& u, uint32_t row_bytes,
+                                              uint32_t lds_tile, int lane) {
+  using Cfg = T2Cfg<D>;
+#pragma unroll
+  for (int x = 0; x < Cfg::kLoadsPerTile; ++x) {
+    const int p = x * 64 + lane;
+    const int r = p / Cfg::kChunksPerRow;
+    const int chunk = (p % Cfg::kChunksPerRow) ^ swz<D>(r);
+    const uint32_t off = (uint32_t)(u.first_row + min(r, u.T - 1) * u.hw) * row_bytes +
+                         (uint32_t)(u.head * D * 2 + chunk * 16);
+    lds_dma16(base, off, lds_tile + x * 1024);
+  }
+}
+
+// Row operands: lane l holds row l%32, columns ks*16 + 8*(l/32)..+7.
+template <int D>
+__device__ __forceinline__ void read_rows32(const char* tile, int lane, bf16x8 (&f)[D / 16]) {
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) f[ks] = lds_read_b128(tile, tile_off<D>(lane & 31, ks * 16 + 8 * (lane >> 5)));
+}
+
+// Transposed operand X^T[d = db*32 + ..][rows 16*s2 ..] of a tile, for the contraction over rows.
+template <int D>
+__device__ __forceinline__ bf16x8 read_tr32(const char* tile, int lane, int db, int s2) {
+  const int g = lane >> 5;
+  const int col = db * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  const int row = 16 * s2 + 4 * g + ((lane & 15) >> 2);
+  return join_tr(lds_read_tr(tile, tile_off<D>(row, col)), lds_read_tr(tile, tile_off<D>(row + 8, col)));
+}
+
+// Store an accumulator tile C[d = db*32 + 8*(r/4) + 4*(l/32) + r%4][token = l%32] as bf16 of row `token`.
+template <int D>
+__device__ __forceinline__ void store_tile32(__bf16* base, const TUnit& u, size_t row_stride, int lane,
+                                             int db, const f32x16& c, float mul) {
+  if ((lane & 31) < u.T) {
+    const size_t row = (size_t)(u.first_row + (lane & 31) * u.hw);
+    __bf16* p = base + row * row_stride + (size_t)u.head * D + db * 32 + 4 * (lane >> 5);
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      f32x4 o = {c[4 * q4] * mul, c[4 * q4 + 1] * mul, c[4 * q4 + 2] * mul, c[4 * q4 + 3] * mul};
+      *reinterpret_cast<bf16x4*>(p + 8 * q4) = to_bf16x4(o);
+    }
+  }
+}
+
+__device__ __forceinline__ bf16x8 half_to_bf16(const f32x16& x, int s2) {
+  f32x8 a;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) a[e] = x[8 * s2 + e];
+  return to_bf16x8(a);
+}
+
+}  // namespace
+
+template <int D>
+__global__ __launch_bounds__(kTWaves * 64) void tattn32_fwd_kernel(const __bf16* __restrict__ q,
+                                                                   const __bf16* __restrict__ k,
+                                                                   const __bf16* __restrict__ v,
+                                                                   __bf16* __restrict__ out,
+                                                                   const TemporalTable tab, int n_heads,
+                                                                   float scale_log2) {
+  using Cfg = T2Cfg<D>;
+  constexpr int TB = Cfg::kTileBytes;
+  constexpr int KS = D / 16, DB = D / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  TUnit u;
+  if (!temporal_unit(tab, n_heads, u)) return;   // whole wavefronts leave; there are no barriers
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int g = lane >> 5;
+  const size_t row_stride = (size_t)n_heads * D;
+  const uint32_t row_bytes = (uint32_t)row_stride * 2u;
+  char* mine = smem + wave * 3 * TB;
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(mine));
+  gather_tile32<D>(q, u, row_bytes, lds0, lane);
+  gather_tile32<D>(k, u, row_bytes, lds0 + TB, lane);
+  gather_tile32<D>(v, u, row_bytes, lds0 + 2 * TB, lane);
+  wait_vmcnt<0>();
+
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  bf16x8 qf[KS], kf[KS];
+  read_rows32<D>(mine, lane, qf);
+  read_rows32<D>(mine + TB, lane, kf);
+  f32x16 st = zero16;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) st = mfma32(kf[ks], qf[ks], st);
+  // lane: query l%32; register r: key 8*(r/4) + 4g + r%4
+  float mx = -INFINITY;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    if (8 * (r >> 2) + 4 * g + (r & 3) >= u.T) st[r] = -INFINITY;
+    mx = fmaxf(mx, st[r]);
+  }
+  const float m2 = pair_max(mx) * scale_log2;
+  f32x16 p;
+  float sum = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    p[r] = fast_exp2(st[r] * scale_log2 - m2);
+    sum += p[r];
+  }
+  const float inv = 1.0f / pair_sum(sum);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) p[r] *= inv;
+  const bf16x8 pb0 = half_to_bf16(p, 0), pb1 = half_to_bf16(p, 1);
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    f32x16 o = mfma32(read_tr32<D>(mine + 2 * TB, lane, db, 0), pb0, zero16);
+    o = mfma32(read_tr32<D>(mine + 2 * TB, lane, db, 1), pb1, o);
+    store_tile32<D>(out, u, row_stride, lane, db, o, 1.0f);
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(kTWaves * 64) void tattn32_bwd_kernel(const __bf16* __restrict__ q,
+                                                                   const __bf16* __restrict__ k,
+                                                                   const __bf16* __restrict__ v,
+                                                                   const __bf16* __restrict__ dout,
+                                                                   __bf16* __restrict__ dq,
+                                                                   __bf16* __restrict__ dk,
+                                                                   __bf16* __restrict__ dv,
+                                                                   const TemporalTable tab, int n_heads,
+                                                                   float scale, float scale_log2) {
+  using Cfg = T2Cfg<D>;
+  constexpr int TB = Cfg::kTileBytes;
+  constexpr int KS = D / 16, DB = D / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  TUnit u;
+  if (!temporal_unit(tab, n_heads, u)) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int g = lane >> 5;
+  const size_t row_stride = (size_t)n_heads * D;
+  const uint32_t row_bytes = (uint32_t)row_stride * 2u;
+  char* qt = smem + wave * 4 * TB;
+  char* kt = qt + TB;
+  char* vt = qt + 2 * TB;
+  char* dot = qt + 3 * TB;
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(qt));
+  gather_tile32<D>(q, u, row_bytes, lds0, lane);
+  gather_tile32<D>(k, u, row_bytes, lds0 + TB, lane);
+  gather_tile32<D>(v, u, row_bytes, lds0 + 2 * TB, lane);
+  gather_tile32<D>(dout, u, row_bytes, lds0 + 3 * TB, lane);
+  wait_vmcnt<0>();
+
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  bf16x8 qf[KS], kf[KS], vf[KS], df[KS];
+  read_rows32<D>(qt, lane, qf);
+  read_rows32<D>(kt, lane, kf);
+  read_rows32<D>(vt, lane, vf);
+  read_rows32<D>(dot, lane, df);
+  // "A": lane = query, registers = keys (S^T, dP^T);  "B": lane = key, registers = queries (S, dP)
+  f32x16 sA = zero16, dpA = zero16;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    sA = mfma32(kf[ks], qf[ks], sA);
+    dpA = mfma32(vf[ks], df[ks], dpA);
+  }
+  // softmax statistics per query, in orientation A
+  float mx = -INFINITY;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    if (8 * (r >> 2) + 4 * g + (r & 3) >= u.T) sA[r] = -INFINITY;
+    mx = fmaxf(mx, sA[r]);
+  }
+  const float m2 = pair_max(mx) * scale_log2;
+  f32x16 pA;
+  float sum = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    pA[r] = fast_exp2(sA[r] * scale_log2 - m2);
+    sum += pA[r];
+  }
+  sum = pair_sum(sum);
+  const float lse2 = m2 + __log2f(sum);      // P = exp2(s*scale_log2 - lse2)
+  const float inv = 1.0f / sum;
+  float dl = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    pA[r] *= inv;
+    dl += pA[r] * dpA[r];
+  }
+  const float delta = pair_sum(dl);          // Delta_i = sum_j P_ij dP_ij
+  f32x16 dsA;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) dsA[r] = pA[r] * (dpA[r] - delta);
+  {
+    // dQ^T[d, i] = scale sum_j K[j, d] dS^T[j, i]
+    const bf16x8 d0 = half_to_bf16(dsA, 0), d1 = half_to_bf16(dsA, 1);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      f32x16 o = mfma32(read_tr32<D>(kt, lane, db, 0), d0, zero16);
+      o = mfma32(read_tr32<D>(kt, lane, db, 1), d1, o);
+      store_tile32<D>(dq, u, row_stride, lane, db, o, scale);
+    }
+  }
+  // orientation B: register r belongs to query i = 8*(r/4) + 4g + r%4, whose statistics lane i holds
+  f32x16 sB = zero16, dpB = zero16;
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    sB = mfma32(qf[ks], kf[ks], sB);
+    dpB = mfma32(df[ks], vf[ks], dpB);
+  }
+  f32x16 pB, dsB;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int i = 8 * (r >> 2) + 4 * g + (r & 3);
+    const float l2 = __shfl(lse2, i);
+    const float dd = __shfl(delta, i);
+    const float pv = (i < u.T) ? fast_exp2(sB[r] * scale_log2 - l2) : 0.f;   // padded queries add nothing
+    pB[r] = pv;
+    dsB[r] = pv * (dpB[r] - dd);
+  }
+  const bf16x8 p0 = half_to_bf16(pB, 0), p1 = half_to_bf16(pB, 1);
+  const bf16x8 s0 = half_to_bf16(dsB, 0), s1 = half_to_bf16(dsB, 1);
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    // dV^T[d, j] = sum_i dO[i, d] P[i, j];  dK^T[d, j] = scale sum_i Q[i, d] dS[i, j]
+    f32x16 o = mfma32(read_tr32<D>(dot, lane, db, 0), p0, zero16);
+    o = mfma32(read_tr32<D>(dot, lane, db, 1), p1, o);
+    store_tile32<D>(dv, u, row_stride, lane, db, o, 1.0f);
+    o = mfma32(read_tr32<D>(qt, lane, db, 0), s0, zero16);
+    o = mfma32(read_tr32<D>(qt, lane, db, 1), s1, o);
+    store_tile32<D>(dk, u, row_stride, lane, db, o, scale);
+  }
+}
+
 template <int D>
 static hipError_t launch_t(const void* q, const void* k, const void* v, const void* dout,
                            const TemporalTable& tab, int n_heads, float scale, void* o0, void* o1,
                            void* o2, hipStream_t stream) {
   const long long n_units = (long long)tab.pix_cu[tab.n] * n_heads;
   if (n_units == 0) return hipSuccess;
+  int max_t = 0;
+  for (int s = 0; s < tab.n; ++s)
+    if (tab.hw[s] > 0) max_t = std::max(max_t, (tab.cu[s + 1] - tab.cu[s]) / tab.hw[s]);
+  const bool big = max_t > kTRows;     // some clip has more than 16 frames: 32-row tiles for the call
   const int grid = (int)((n_units + kTWaves - 1) / kTWaves);
   const int tiles = dout ? 4 : 3;
-  const int lds = kTWaves * tiles * TCfg<D>::kTileBytes;
+  const int lds = kTWaves * tiles * (big ? T2Cfg<D>::kTileBytes : TCfg<D>::kTileBytes);
   if (!dout) {
-    auto kern = tattn_fwd_kernel<D>;
+    auto kern = big ? tattn32_fwd_kernel<D> : tattn_fwd_kernel<D>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
     kern<<<grid, kTWaves * 64, lds, stream>>>((const __bf16*)q, (const __bf16*)k, (const __bf16*)v,
                                               (__bf16*)o0, tab, n_heads, scale * kLog2eT);
   } else {
-    auto kern = tattn_bwd_kernel<D>;
+    auto kern = big ? tattn32_bwd_kernel<D> : tattn_bwd_kernel<D>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;

@@ -169,7 +169,7 @@ const char* vfm_strerror(int status) {
     case VFM_ERR_NULL: return "a required pointer is NULL";
     case VFM_ERR_SHAPE: return "total_tokens, n_heads, head_dim (64 or 128), n_seqs (<= 256), scale or theta (> 0, finite) or eps (>= 0) out of range, or dx aliases x";
     case VFM_ERR_CU_SEQLENS: return "cu_seqlens must start at 0, be non-decreasing and end at total_tokens";
-    case VFM_ERR_THW: return "each clip needs positive T, H, W with T*H*W equal to its length (temporal attention: T <= 16)";
+    case VFM_ERR_THW: return "each clip needs positive T, H, W with T*H*W equal to its length (temporal attention: T <= 32)";
     case VFM_ERR_SPLIT: return "dim_t + dim_h + dim_w must equal head_dim, each part even and >= 0";
     case VFM_ERR_DTYPE: return "unsupported element type (only bf16)";
     case VFM_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or smaller than vfm_attn_bwd_workspace_size()";

@@ -20,6 +20,11 @@ CASES = {
     # frame counts 1, 2, 7, 16 and an empty clip; pixel counts that are not multiples of the 4 waves
     "t128": W.Workload("t128", ((16, 3, 5), (1, 2, 3), (0, 1, 1), (7, 1, 1), (2, 5, 5)), 3, 128, (32, 48, 48), seed=31),
     "t64": W.Workload("t64", ((5, 3, 3), (16, 1, 2), (3, 4, 1)), 2, 64, (16, 24, 24), seed=32),
+    # more than 16 frames (the 32-row tile): 17, 24, 32 frames mixed with short clips, an empty one and
+    # a single-frame one in the same call
+    "t128_long": W.Workload("t128_long", ((17, 2, 3), (4, 3, 3), (32, 1, 5), (0, 1, 1), (24, 2, 2), (1, 3, 1)), 3, 128,
+                            (32, 48, 48), seed=33),
+    "t64_long": W.Workload("t64_long", ((32, 3, 1), (9, 2, 2), (20, 1, 1)), 2, 64, (16, 24, 24), seed=34),
 }
 
 
@@ -31,7 +36,7 @@ def _check(wl, gpu, dev, heads=None):
     g_ref = orc.temporal_attn_bwd(host["q"], host["k"], host["v"], host["dout"], wl.thw, wl.cu_seqlens, wl.scale)
     o = U.to_f64(out[:, hs, :])
     assert np.all(np.isfinite(o))
-    # at most 16 keys: outputs are O(|v|), so the absolute bound is taken relative to max(1, |ref|)
+    # at most 32 keys: outputs are O(|v|), so the absolute bound is taken relative to max(1, |ref|)
     assert np.max(np.abs(o - o_ref) / np.maximum(1.0, np.abs(o_ref))) <= U.TOL_OUT_MAXABS
     assert U.rel_rms(o, o_ref) <= U.TOL_OUT_RELRMS
     for nm, g, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), g_ref):
@@ -65,12 +70,22 @@ def test_single_frame_clip_copies_values_and_has_zero_qk_gradients():
     assert np.array_equal(U.to_bits(dv[a:b]), U.to_bits(dev["dout"][a:b]))
 
 
-def test_more_than_sixteen_frames_is_an_error():
+def test_more_than_thirty_two_frames_is_an_error():
     import torch
     b = _binding()
-    x = torch.zeros((17 * 4, 1, 64), dtype=torch.bfloat16, device="cuda")
+    x = torch.zeros((33 * 4, 1, 64), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(b.VfmError):
-        b.vfm_tattn_fwd(x, x, x, [(17, 2, 2)], [0, 68], 0.125)
+        b.vfm_tattn_fwd(x, x, x, [(33, 2, 2)], [0, 132], 0.125)
+
+
+def test_single_frame_clip_in_a_long_call():
+    # the 32-row kernels serve every clip of a call that has a long one
+    wl = CASES["t128_long"]
+    dev, (out, dq, dk, dv) = _run(_binding(), wl)
+    a, b = int(wl.cu_seqlens[5]), int(wl.cu_seqlens[6])      # the (1,3,1) clip
+    assert np.array_equal(U.to_bits(out[a:b]), U.to_bits(dev["v"][a:b]))
+    assert not np.any(U.to_f64(dq[a:b])) and not np.any(U.to_f64(dk[a:b]))
+    assert np.array_equal(U.to_bits(dv[a:b]), U.to_bits(dev["dout"][a:b]))
 
 
 def test_full_size_c4_every_element():
