@@ -6,7 +6,9 @@ import numpy as np
 from paper_2503_12964_amd import workloads as W
 
 # Tolerances of the target statement: forward out max-abs <= 1e-2 and relative RMS <= 5e-3;
-# dq, dk, dv relative RMS <= 1.5e-2.  lse and RoPE bounds are derived in the design doc.
+# dq, dk, dv relative RMS <= 1.5e-2.  lse is accumulated in fp32 from exact bf16 inputs, so 1e-3
+# absolute is ample; a RoPE output is the fp64 value rounded once to bf16 (half an ulp, 2^-9
+# relative at most), hence a relative RMS of at most 2.5e-3.
 TOL_OUT_MAXABS = 1e-2
 TOL_OUT_RELRMS = 5e-3
 TOL_GRAD_RELRMS = 1.5e-2
