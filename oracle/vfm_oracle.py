@@ -45,7 +45,10 @@ norms, is the identity at the origin, inverts exactly, is shift-invariant in
 the scores, and reduces to textbook complex-number 1-D RoPE; softmax row
 sums; sum of dK over a segment is zero; key/value permutation invariance;
 central finite differences; a dense masked brute force written with Python
-loops; PyTorch fp64 autograd as a third opinion.
+loops; PyTorch fp64 autograd as a third opinion.  tests/oracle_mutants.py
+plants some fifty single mistakes in a copy of this file (dropped terms and
+factors, wrong signs, indices and axes, transposed operands) and
+tests/test_oracle_mutations.py checks that the pins reject each of them.
 """
 from __future__ import annotations
 

@@ -10,6 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # tests/test_oracle_mutations.py starts child runs of the pin tests with a planted mistake
+    mutant = os.environ.get("VFM_ORACLE_MUTANT")
+    if mutant:
+        from tests import oracle_mutants
+        oracle_mutants.install(mutant)
 
 
 def _gpu_available() -> bool:
