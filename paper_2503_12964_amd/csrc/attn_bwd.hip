@@ -421,22 +421,43 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
             __hip_atomic_fetch_add(dvp + db * 32 + q4 * 8 + e, dvacc[db][q4 * 4 + e], __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
           }
-    } else {
-      __bf16* dkp = dk + (size_t)jrow * row_stride + head_off + 4 * g;
-      __bf16* dvp = dv + (size_t)jrow * row_stride + head_off + 4 * g;
+    }
+  }
+  if constexpr (!SPLIT) {
+    // Whole rows leave the workgroup: a wavefront's 32 x D tile is turned through its own
+    // piece of LDS (the ring is free now; 16-byte chunk x of row r at chunk x ^ (r mod
+    // chunks)), so every store instruction writes complete rows instead of 16 bytes of each.
+    __syncthreads();
+    constexpr int CPR = Cfg::kChunksPerRow;
+    char* turn = smem + wave * (32 * RB);
+    const int rr = lane / CPR, cx = lane % CPR;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+      __bf16* dst = pass == 0 ? dk : dv;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 a, b;
+          f32x4 a;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            a[e] = dkacc[db][q4 * 4 + e] * scale;
-            b[e] = dvacc[db][q4 * 4 + e];
-          }
-          *reinterpret_cast<bf16x4*>(dkp + db * 32 + q4 * 8) = to_bf16x4(a);
-          *reinterpret_cast<bf16x4*>(dvp + db * 32 + q4 * 8) = to_bf16x4(b);
+          for (int e = 0; e < 4; ++e)
+            a[e] = pass == 0 ? dkacc[db][q4 * 4 + e] * scale : dvacc[db][q4 * 4 + e];
+          *reinterpret_cast<bf16x4*>(turn + c * RB + (((db * 4 + q4) ^ (c & (CPR - 1))) << 4) + 8 * g) = to_bf16x4(a);
         }
+      // the tile is private to the wavefront, whose LDS accesses complete in program order:
+      // only the compiler has to be kept from moving the reads over the writes
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int i = 0; i < 32 * CPR / 64; ++i) {
+        const int r = i * (64 / CPR) + rr;
+        const u32x4 w = *reinterpret_cast<const u32x4*>(turn + r * RB + ((cx ^ (r & (CPR - 1))) << 4));
+        const int row = j0 + wave * 32 + r;
+        if (row < kv_b)
+          *reinterpret_cast<u32x4*>(dst + (size_t)row * row_stride + head_off + cx * 8) = w;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
   }
 }
