@@ -424,41 +424,11 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
     }
   }
   if constexpr (!SPLIT) {
-    // Whole rows leave the workgroup: a wavefront's 32 x D tile is turned through its own
-    // piece of LDS (the ring is free now; 16-byte chunk x of row r at chunk x ^ (r mod
-    // chunks)), so every store instruction writes complete rows instead of 16 bytes of each.
-    __syncthreads();
-    constexpr int CPR = Cfg::kChunksPerRow;
+    __syncthreads();   // the ring is free: each wavefront turns its tiles through a piece of it
     char* turn = smem + wave * (32 * RB);
-    const int rr = lane / CPR, cx = lane % CPR;
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-      __bf16* dst = pass == 0 ? dk : dv;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 a;
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            a[e] = pass == 0 ? dkacc[db][q4 * 4 + e] * scale : dvacc[db][q4 * 4 + e];
-          *reinterpret_cast<bf16x4*>(turn + c * RB + (((db * 4 + q4) ^ (c & (CPR - 1))) << 4) + 8 * g) = to_bf16x4(a);
-        }
-      // the tile is private to the wavefront, whose LDS accesses complete in program order:
-      // only the compiler has to be kept from moving the reads over the writes
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int i = 0; i < 32 * CPR / 64; ++i) {
-        const int r = i * (64 / CPR) + rr;
-        const u32x4 w = *reinterpret_cast<const u32x4*>(turn + r * RB + ((cx ^ (r & (CPR - 1))) << 4));
-        const int row = j0 + wave * 32 + r;
-        if (row < kv_b)
-          *reinterpret_cast<u32x4*>(dst + (size_t)row * row_stride + head_off + cx * 8) = w;
-      }
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-    }
+    const int row0 = j0 + wave * 32;
+    store_tile_rows<D>(turn, dkacc, scale, dk + (size_t)row0 * row_stride + head_off, row_stride, kv_b - row0);
+    store_tile_rows<D>(turn, dvacc, 1.0f, dv + (size_t)row0 * row_stride + head_off, row_stride, kv_b - row0);
   }
 }
 
@@ -995,22 +965,13 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
 #pragma unroll
   for (int ib = 0; ib < 2; ++ib) wait_mfma_a(dqacc[ib][0], dqacc[ib][1], dqacc[ib][2], dqacc[ib][3]);
 
-  // ---- epilogue: dq = bf16(scale * dQ^T)
+  // ---- epilogue: dq = bf16(scale * dQ^T), whole rows per store
+  __syncthreads();   // the ring is free: each wavefront turns its tiles through a piece of it
 #pragma unroll
   for (int ib = 0; ib < 2; ++ib) {
-    const int i = qrow[ib];
-    if (i < q_b) {
-      __bf16* op = dq + (size_t)i * row_stride + head_off + 4 * g;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          f32x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = dqacc[ib][db][q4 * 4 + e] * scale;
-          *reinterpret_cast<bf16x4*>(op + db * 32 + q4 * 8) = to_bf16x4(o);
-        }
-    }
+    const int row0 = q0 + (wave * 2 + ib) * 32;
+    store_tile_rows<D>(smem + wave * (32 * D * 2), dqacc[ib], scale,
+                       dq + (size_t)row0 * row_stride + head_off, row_stride, q_b - row0);
   }
 }
 

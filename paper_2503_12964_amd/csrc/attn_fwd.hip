@@ -339,19 +339,11 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   // ---- epilogue: normalise, write out (bf16) and lse (natural log)
   const float l_tot = pair_sum(l_run);
   const float inv = 1.0f / l_tot;
-  if (qrow < q_b) {
-    __bf16* op = out + (size_t)qrow * row_stride + (size_t)head * D + 4 * g;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        f32x4 o;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) o[e] = oacc[db][q4 * 4 + e] * inv;
-        *reinterpret_cast<bf16x4*>(op + db * 32 + q4 * 8) = to_bf16x4(o);
-      }
-    if (g == 0) lse[(size_t)head * total + qrow] = (m_run + __log2f(l_tot)) * kLn2;
-  }
+  if (qrow < q_b && g == 0) lse[(size_t)head * total + qrow] = (m_run + __log2f(l_tot)) * kLn2;
+  __syncthreads();   // the rings are free: each wavefront turns its tile through a piece of them
+  const int row0 = q0 + wave * 32;
+  store_tile_rows<D>(smem + wave * (32 * RB), oacc, inv,
+                     out + (size_t)row0 * row_stride + (size_t)head * D, row_stride, q_b - row0);
 }
 
 template <int D, int W, class Segs>

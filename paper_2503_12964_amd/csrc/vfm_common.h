@@ -200,6 +200,41 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 __device__ __forceinline__ bf16x8 to_bf16x8(f32x8 v) { return __builtin_convertvector(v, bf16x8); }
 __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) { return __builtin_convertvector(v, bf16x4); }
 
+// Stores a wavefront's 32 x D fp32 tile, held in the 32x32 MFMA accumulator layout (lane: row
+// lane & 31; register q4*4 + e of block db: column db*32 + q4*8 + 4*(lane >> 5) + e), as bf16
+// rows.  The tile is turned through 32*D*2 bytes of LDS that belong to the wavefront (16-byte
+// chunk x of row r kept at chunk x ^ (r mod chunks-per-row)), so that every store instruction
+// writes complete rows instead of 16 bytes of each of 32 rows.  mul scales this lane's row;
+// dst points at row 0 of the tile (first column of the head); rows >= rows_valid are not
+// written.  A wavefront's LDS accesses complete in program order, so only the compiler has
+// to be kept from moving the reads over the writes.
+template <int D>
+__device__ __forceinline__ void store_tile_rows(char* turn, const f32x16 (&acc)[D / 32], float mul,
+                                                __bf16* dst, size_t row_stride, int rows_valid) {
+  constexpr int CPR = D / 8, RB = D * 2;
+  const int lane = threadIdx.x & 63, c = lane & 31, g = lane >> 5;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      f32x4 a;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) a[e] = acc[db][q4 * 4 + e] * mul;
+      *reinterpret_cast<bf16x4*>(turn + c * RB + (((db * 4 + q4) ^ (c & (CPR - 1))) << 4) + 8 * g) = to_bf16x4(a);
+    }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  const int rr = lane / CPR, cx = lane % CPR;
+#pragma unroll
+  for (int i = 0; i < 32 * CPR / 64; ++i) {
+    const int r = i * (64 / CPR) + rr;
+    const u32x4 w = *reinterpret_cast<const u32x4*>(turn + r * RB + ((cx ^ (r & (CPR - 1))) << 4));
+    if (r < rows_valid) *reinterpret_cast<u32x4*>(dst + (size_t)r * row_stride + cx * 8) = w;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
 // ---- direct global -> LDS loads, issued as inline assembly ------------------
 // The compiler orders every LDS read that follows a compiler-visible LDS-writing load
 // behind a full vmcnt(0) wait, which would expose the whole global latency each tile.
