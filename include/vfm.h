@@ -291,6 +291,12 @@ VFM_API int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8,
 /* Static, human-readable text for a vfm_status. */
 VFM_API const char* vfm_strerror(int status);
 
+/* The HIP runtime's text for the error behind the calling thread's most recent
+ * VFM_ERR_LAUNCH ("no error" if there was none).  Errors that other code left
+ * pending in the runtime before a call into this library are discarded by the
+ * library and never reported as its own. */
+VFM_API const char* vfm_last_hip_error(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ VFM_F32 = 1
 VFM_MAX_SEQS = 256
 
 EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_xattn_fwd", "vfm_xattn_bwd_workspace_size", "vfm_xattn_bwd", "vfm_tattn_fwd", "vfm_tattn_bwd",
-           "vfm_fp8_pack_sizes", "vfm_fp8_pack", "vfm_attn_fwd_fp8", "vfm_strerror")
+           "vfm_fp8_pack_sizes", "vfm_fp8_pack", "vfm_attn_fwd_fp8", "vfm_strerror", "vfm_last_hip_error")
 
 _lib = None
 
@@ -90,6 +90,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
                                      c_void_p, c_void_p, c_void_p]
     lib.vfm_strerror.restype = ctypes.c_char_p
     lib.vfm_strerror.argtypes = [c_int]
+    lib.vfm_last_hip_error.restype = ctypes.c_char_p
+    lib.vfm_last_hip_error.argtypes = []
     if path == LIB_PATH:
         _lib = lib
     return lib
@@ -99,9 +101,19 @@ def strerror(status: int) -> str:
     return load_library().vfm_strerror(int(status)).decode()
 
 
+def vfm_last_hip_error() -> str:
+    return load_library().vfm_last_hip_error().decode()
+
+
+VFM_ERR_LAUNCH = 8
+
+
 def _check(status: int) -> None:
     if status != 0:
-        raise VfmError(status, strerror(status))
+        text = strerror(status)
+        if status == VFM_ERR_LAUNCH:
+            text += " (" + vfm_last_hip_error() + ")"
+        raise VfmError(status, text)
 
 
 def _host_i32(a) -> np.ndarray:

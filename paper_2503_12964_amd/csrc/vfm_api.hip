@@ -159,9 +159,26 @@ int check_rope_args(const int32_t* thw, const int32_t* cu_seqlens, int n_seqs, i
   return VFM_OK;
 }
 
+// The HIP error behind this thread's most recent VFM_ERR_LAUNCH.
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+// hipGetLastError() reports the last error of ANY earlier runtime call of the thread, including
+// harmless ones of other libraries (a "not ready" from polling an event, a failed pointer
+// query on pageable host memory).  Such leftovers are dropped before the library launches, so
+// that what is read after the launches is the launches' own.
+inline void forget_foreign_errors() { (void)hipGetLastError(); }
+
+inline int launch_status(hipError_t e) {
+  if (e == hipSuccess) return VFM_OK;
+  g_last_hip_error = e;
+  return VFM_ERR_LAUNCH;
+}
+
 }  // namespace
 
 extern "C" {
+
+const char* vfm_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 const char* vfm_strerror(int status) {
   switch (status) {
@@ -189,9 +206,10 @@ int vfm_rope3d(void* x, const int32_t* thw, const int32_t* cu_seqlens, int n_seq
   if (st) return st;
   if (!aligned16(x)) return VFM_ERR_ALIGN;
   if (total_tokens == 0) return VFM_OK;
+  forget_foreign_errors();
   hipError_t e = vfm::launch_rope3d(x, tab, total_tokens, n_heads, head_dim, dim_t, dim_h, dim_w,
                                     theta, inverse, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 int vfm_qknorm_rope3d(const void* x, const float* gain, float eps, void* y, const int32_t* thw,
@@ -206,10 +224,11 @@ int vfm_qknorm_rope3d(const void* x, const float* gain, float eps, void* y, cons
   if (!(eps >= 0.f) || !isfinite(eps)) return VFM_ERR_SHAPE;
   if (!aligned16(x) || !aligned16(y) || (reinterpret_cast<uintptr_t>(gain) & 3u)) return VFM_ERR_ALIGN;
   if (total_tokens == 0) return VFM_OK;
+  forget_foreign_errors();
   hipError_t e = vfm::launch_qknorm_rope3d(x, y, gain, eps, tab, total_tokens, n_heads, head_dim,
                                            dim_t, dim_h, dim_w, theta,
                                            static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 int vfm_qknorm_rope3d_bwd(const void* x, const float* gain, float eps, const void* dy, void* dx,
@@ -226,10 +245,11 @@ int vfm_qknorm_rope3d_bwd(const void* x, const float* gain, float eps, const voi
       ((reinterpret_cast<uintptr_t>(gain) | reinterpret_cast<uintptr_t>(dgain)) & 3u))
     return VFM_ERR_ALIGN;
   if (dx == x) return VFM_ERR_SHAPE;   // dx may overwrite dy, never x
+  forget_foreign_errors();
   hipError_t e = vfm::launch_qknorm_rope3d_bwd(x, dy, dx, gain, eps, dgain, tab, total_tokens,
                                                n_heads, head_dim, dim_t, dim_h, dim_w, theta,
                                                static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 int vfm_attn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
@@ -247,9 +267,10 @@ int vfm_attn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_
   if (total_tokens == 0) return VFM_OK;
   SegTable segs;
   build_seg_table(cu_seqlens, n_seqs, &segs);
+  forget_foreign_errors();
   hipError_t e = vfm::launch_attn_fwd(q, k, v, segs, total_tokens, n_heads, head_dim, scale, out,
                                       lse, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 size_t vfm_attn_bwd_workspace_size(int total_tokens, int n_heads, int head_dim) {
@@ -290,10 +311,11 @@ int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, c
   float* sentinel = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * part);
   SegTable segs;
   build_seg_table(cu_seqlens, n_seqs, &segs);
+  forget_foreign_errors();
   hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_tokens, n_heads,
                                       head_dim, scale, dq, dk, dv, delta, lse2, sentinel, nullptr, 0,
                                       static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 int vfm_xattn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_q,
@@ -315,9 +337,10 @@ int vfm_xattn_fwd(const void* q, const void* k, const void* v, const int32_t* cu
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
     return VFM_ERR_ALIGN;
   if (total_q == 0) return VFM_OK;
+  forget_foreign_errors();
   hipError_t e = vfm::launch_attn_fwd(q, k, v, segs, total_q, n_heads, head_dim, scale, out, lse,
                                       static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 int vfm_xattn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
@@ -352,10 +375,11 @@ int vfm_xattn_bwd(const void* q, const void* k, const void* v, const void* out, 
   float* lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + part);
   float* sentinel = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * part);
   float* dkv32 = reinterpret_cast<float*>(static_cast<char*>(workspace) + stats);
+  forget_foreign_errors();
   hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_q, n_heads, head_dim,
                                       scale, dq, dk, dv, delta, lse2, sentinel, dkv32, total_kv,
                                       static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 int vfm_tattn_fwd(const void* q, const void* k, const void* v, const int32_t* thw,
@@ -373,9 +397,10 @@ int vfm_tattn_fwd(const void* q, const void* k, const void* v, const int32_t* th
   if (st) return st;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return VFM_ERR_ALIGN;
   if (total_tokens == 0) return VFM_OK;
+  forget_foreign_errors();
   hipError_t e = vfm::launch_tattn_fwd(q, k, v, tab, n_heads, head_dim, scale, out,
                                        static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 int vfm_tattn_bwd(const void* q, const void* k, const void* v, const void* dout, const int32_t* thw,
@@ -395,9 +420,10 @@ int vfm_tattn_bwd(const void* q, const void* k, const void* v, const void* dout,
       !aligned16(dk) || !aligned16(dv))
     return VFM_ERR_ALIGN;
   if (total_tokens == 0) return VFM_OK;
+  forget_foreign_errors();
   hipError_t e = vfm::launch_tattn_bwd(q, k, v, dout, tab, n_heads, head_dim, scale, dq, dk, dv,
                                        static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 int vfm_fp8_pack_sizes(const int32_t* cu_seqlens, int n_seqs, int total_tokens, int n_heads,
@@ -433,9 +459,10 @@ int vfm_fp8_pack(const void* q, const void* k, const void* v, const int32_t* cu_
   vfm::Fp8ClipTable clips;
   const int units = build_fp8_tables(cu_seqlens, n_seqs, total_tokens, &clips, nullptr);
   if ((unsigned long long)units * n_heads * kFp8Unit * head_dim > 0xffffffffULL) return VFM_ERR_SHAPE;
+  forget_foreign_errors();
   hipError_t e = vfm::launch_fp8_pack(q, k, v, clips, units, total_tokens, n_heads, head_dim, q_scale,
                                       k_scale, v_scale, q8, k8, vT8, static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const int32_t* cu_seqlens,
@@ -454,10 +481,11 @@ int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const int3
   vfm::Fp8SegTable segs;
   const int units = build_fp8_tables(cu_seqlens, n_seqs, total_tokens, &clips, &segs);
   if ((unsigned long long)units * n_heads * kFp8Unit * head_dim > 0xffffffffULL) return VFM_ERR_SHAPE;
+  forget_foreign_errors();
   hipError_t e = vfm::launch_attn_fwd_fp8(q8, k8, vT8, segs, units, total_tokens, n_heads, head_dim,
                                           1.0f / v_scale, out, lse,
                                           static_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? VFM_OK : VFM_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 }  // extern "C"

@@ -48,6 +48,8 @@ def test_strerror_texts(lib):
     texts = {lib.vfm_strerror(i) for i in range(10)}
     assert len(texts) == 10 and b"unknown status" not in texts
     assert lib.vfm_strerror(99) == b"unknown status"
+    # no launch has failed in this process: the runtime's text for "success"
+    assert lib.vfm_last_hip_error() == b"no error"
 
 
 FAKE = ctypes.c_void_p(0x10000)      # never dereferenced: validation precedes any launch
