@@ -30,7 +30,14 @@
  *     (cu_seqlens[s] == cu_seqlens[s+1]) are legal and do no work.
  *   - Every function returns a vfm_status; 0 is success.  Argument errors are
  *     detected before anything is launched and leave all outputs untouched.
- *   - Re-entrant: no global mutable state.
+ *   - Re-entrant: no global mutable state (beyond the calling thread's last
+ *     launch error, see vfm_last_hip_error).
+ *   - The library uses the HIP runtime (libamdhip64) of the process it is
+ *     loaded into, and that must be the runtime that owns the pointers and
+ *     the stream handed over.  A process that holds two copies of the runtime
+ *     (for example a framework that ships its own, loaded AFTER this library
+ *     had already pulled in the system's) gets VFM_ERR_LAUNCH, "no ROCm-capable
+ *     device is detected": load the framework first.
  */
 #ifndef VFM_H
 #define VFM_H

@@ -42,6 +42,12 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
         raise FileNotFoundError(
             f"{path} not found: build it first (python -m paper_2503_12964_amd.build); "
             "there is no CPU fallback")
+    # The library and PyTorch must share ONE HIP runtime: the tensors and streams handed over
+    # belong to PyTorch's.  libvfm.so asks for the runtime by its soname; with PyTorch (which
+    # ships its own copy under that soname) loaded first, the dynamic linker gives the library
+    # that copy.  Loaded the other way round, the library would bring in the system's copy as a
+    # second runtime in the process, and a second runtime finds no device.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(path)
     c_int, c_float, c_void_p, c_size_t = ctypes.c_int, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t
     p_i32 = ctypes.POINTER(ctypes.c_int32)

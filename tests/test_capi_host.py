@@ -3,6 +3,8 @@ and rejects bad arguments before launching anything (so no GPU is needed)."""
 import ctypes
 import os
 import re
+import subprocess
+import sys
 
 import numpy as np
 import pytest
@@ -226,6 +228,19 @@ def test_bwd_argument_errors_and_workspace(lib):
     assert bwd(ws_bytes=16) == 7
     assert bwd(ws=ctypes.c_void_p(0x10010)) == 7                # not 256-byte aligned
     assert bwd(total=9) == 3
+
+
+def test_library_shares_pytorchs_hip_runtime():
+    # A process that loads the library before it ever imported torch must still end up with a
+    # single HIP runtime (a second copy of the runtime finds no device on a GPU machine).
+    code = ("from paper_2503_12964_amd import binding\n"
+            "binding.load_library()\n"
+            "import torch\n"
+            "libs = {l.split()[-1] for l in open('/proc/self/maps') if 'libamdhip64' in l}\n"
+            "print(len(libs))\n")
+    r = subprocess.run([sys.executable, "-c", code], cwd=ROOT, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stderr[-1000:]
+    assert r.stdout.strip().splitlines()[-1] == "1", r.stdout
 
 
 def test_missing_library_fails_loudly(tmp_path):
