@@ -42,6 +42,32 @@ def test_random_packed_shapes(seed):
     _assert_parity(wl, gpu, host, relative_maxabs=True)
 
 
+def _random_long_workload(seed):
+    """A few clips of arbitrary length up to 6,000 tokens (many ring turns and every remainder of
+    the unrolled loops), some of them empty, tiny, or a token or two around a tile multiple."""
+    rng = np.random.default_rng(1000 + seed)
+    hd = 128 if seed % 4 else 64
+    grids = []
+    for _ in range(int(rng.integers(1, 12))):
+        kind = rng.integers(0, 5)
+        if kind == 0:
+            n = int(rng.integers(0, 3))
+        elif kind == 1:
+            n = int(rng.choice([32, 64, 96, 128, 192, 256, 384, 512, 768, 1024])) + int(rng.integers(-2, 3))
+        else:
+            n = int(rng.integers(1, 6000))
+        grids.append((1, 1, n) if n else (0, 1, 1))
+    dims = (16, 24, 24) if hd == 64 else (32, 48, 48)
+    return W.Workload(f"long{seed}", tuple(grids), int(rng.choice([1, 2, 3])), hd, dims, seed=5000 + seed)
+
+
+@pytest.mark.parametrize("seed", [201, 203, 228, 237])
+def test_random_long_clips(seed):
+    wl = _random_long_workload(seed)
+    gpu, host = _run_fwd_bwd(wl, rope=True)
+    _assert_parity(wl, gpu, host, relative_maxabs=True)
+
+
 def test_maximum_number_of_clips():
     # 256 clips (the table's capacity) of 1..40 tokens
     rng = np.random.default_rng(7)
