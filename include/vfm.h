@@ -295,6 +295,24 @@ VFM_API int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8,
                      int n_heads, int head_dim, float v_scale,
                      void* out, float* lse, void* hip_stream);
 
+/*
+ * The tile scheduler, on the host (nothing is launched): which rows each
+ * workgroup of a launch takes.  Section 3.1's packed clips are cut into tiles of
+ * rows_per_tile rows that never straddle a clip (so blocks between different
+ * clips are never enumerated), clips longest first, and the (head, tile) units
+ * are dealt to the grid so that the workgroups of one XCD (workgroup index mod
+ * 8) take consecutive tiles of the same head.  The attention kernels use this
+ * very mapping with rows_per_tile = 256 (forward and dQ; 128 in the forward at
+ * head_dim 64) over query rows and 128 (dK/dV) over key rows.
+ * For workgroup b < *n_blocks: units[3b] = head (-1: the workgroup is grid
+ * padding and exits), units[3b+1] = first packed row, units[3b+2] = rows
+ * (1..rows_per_tile).  units is a HOST int32 [capacity][3] array; *n_blocks is
+ * always set; SHAPE if capacity < *n_blocks.
+ */
+VFM_API int vfm_schedule_units(const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                       int n_heads, int rows_per_tile, int32_t* units, int capacity,
+                       int* n_blocks);
+
 /* Static, human-readable text for a vfm_status. */
 VFM_API const char* vfm_strerror(int status);
 

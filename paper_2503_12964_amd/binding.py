@@ -22,7 +22,7 @@ VFM_F32 = 1
 VFM_MAX_SEQS = 256
 
 EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_xattn_fwd", "vfm_xattn_bwd_workspace_size", "vfm_xattn_bwd", "vfm_tattn_fwd", "vfm_tattn_bwd",
-           "vfm_fp8_pack_sizes", "vfm_fp8_pack", "vfm_attn_fwd_fp8", "vfm_strerror", "vfm_last_hip_error")
+           "vfm_fp8_pack_sizes", "vfm_fp8_pack", "vfm_attn_fwd_fp8", "vfm_strerror", "vfm_last_hip_error", "vfm_schedule_units")
 
 _lib = None
 
@@ -96,6 +96,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
                                      c_void_p, c_void_p, c_void_p]
     lib.vfm_strerror.restype = ctypes.c_char_p
     lib.vfm_strerror.argtypes = [c_int]
+    lib.vfm_schedule_units.restype = c_int
+    lib.vfm_schedule_units.argtypes = [p_i32, c_int, c_int, c_int, c_int, p_i32, c_int, ctypes.POINTER(c_int)]
     lib.vfm_last_hip_error.restype = ctypes.c_char_p
     lib.vfm_last_hip_error.argtypes = []
     if path == LIB_PATH:
@@ -120,6 +122,22 @@ def _check(status: int) -> None:
         if status == VFM_ERR_LAUNCH:
             text += " (" + vfm_last_hip_error() + ")"
         raise VfmError(status, text)
+
+
+def vfm_schedule_units(cu_seqlens, n_heads: int, rows_per_tile: int) -> np.ndarray:
+    """(head, first packed row, rows) of every workgroup of a launch that cuts rows_per_tile-row
+    tiles from the clips; head -1 marks grid padding.  Host only."""
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    n = ctypes.c_int(0)
+    st = lib.vfm_schedule_units(_i32_ptr(cu), int(cu.size - 1), int(cu[-1]), int(n_heads), int(rows_per_tile),
+                                None, 0, ctypes.byref(n))
+    if st not in (0, 2):          # SHAPE only says "capacity too small" here
+        _check(st)
+    units = np.zeros((max(n.value, 1), 3), dtype=np.int32)
+    _check(lib.vfm_schedule_units(_i32_ptr(cu), int(cu.size - 1), int(cu[-1]), int(n_heads), int(rows_per_tile),
+                                  _i32_ptr(units), int(units.shape[0]), ctypes.byref(n)))
+    return units[:n.value]
 
 
 def _host_i32(a) -> np.ndarray:

@@ -993,10 +993,7 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
     using Cfg = BwdCfg<D>;
     const int tiles = count_tiles<true>(segs, kBwdBC);
     if (tiles == 0) return hipSuccess;
-    UnitMap um;
-    um.tiles_per_head = tiles;
-    um.n_units = tiles * n_heads;
-    um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
+    UnitMap um = make_unit_map(tiles, n_heads);
     // Few key tiles and long query ranges (cross-attention): split the queries over workgroups.
     int q_split = 1;
     if (dkv32 && tiles * n_heads < 256) {
@@ -1010,9 +1007,7 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
       const size_t n4 = 2 * kv_elems / 4;
       fill_zero_f32x4_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, stream>>>((f32x4*)dkv32, n4);
       if ((e = hipGetLastError()) != hipSuccess) return e;
-      um.tiles_per_head = tiles * q_split;
-      um.n_units = um.tiles_per_head * n_heads;
-      um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
+      um = make_unit_map(tiles * q_split, n_heads);
       auto kern = attn_bwd_dkdv_kernel<D, Segs, true>;
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
@@ -1043,10 +1038,7 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
     using Cfg = Dq2Cfg<D>;
     const int tiles = count_tiles<false>(segs, Cfg::kBR);
     if (tiles == 0) return hipSuccess;
-    UnitMap um;
-    um.tiles_per_head = tiles;
-    um.n_units = tiles * n_heads;
-    um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
+    UnitMap um = make_unit_map(tiles, n_heads);
     auto kern = attn_bwd_dq2_kernel<D, Segs>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
@@ -1061,10 +1053,7 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
     using Cfg = DqCfg<D, NI, W>;
     const int tiles = count_tiles<false>(segs, Cfg::kBR);
     if (tiles == 0) return hipSuccess;
-    UnitMap um;
-    um.tiles_per_head = tiles;
-    um.n_units = tiles * n_heads;
-    um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
+    UnitMap um = make_unit_map(tiles, n_heads);
     auto kern = attn_bwd_dq_kernel<D, NI, W, Segs>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);

@@ -404,10 +404,7 @@ static hipError_t fwd_fp8_d(const void* q8, const void* k8, const void* vT8, con
   int tiles = 0;
   for (int s = 0; s < segs.n; ++s) tiles += (segs.len[s] + kF8Rows - 1) / kF8Rows;
   if (tiles == 0) return hipSuccess;
-  UnitMap um;
-  um.tiles_per_head = tiles;
-  um.n_units = tiles * n_heads;
-  um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
+  UnitMap um = make_unit_map(tiles, n_heads);
   constexpr int lds = kF8Ring * 2 * kF8Unit * D;
   auto kern = attn_fwd_fp8_kernel<D>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),

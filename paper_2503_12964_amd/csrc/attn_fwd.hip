@@ -353,10 +353,7 @@ static hipError_t launch_fwd_cfg(const void* q, const void* k, const void* v, co
   using Cfg = FwdCfg<D, W>;
   const int tiles = count_tiles<false>(segs, Cfg::kRows);
   if (tiles == 0) return hipSuccess;
-  UnitMap um;
-  um.tiles_per_head = tiles;
-  um.n_units = tiles * n_heads;
-  um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
+  UnitMap um = make_unit_map(tiles, n_heads);
   const int grid = um.chunk * kNumXcd;
   auto kern = attn_fwd_kernel<D, W, Segs>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),

@@ -273,6 +273,38 @@ int vfm_attn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_
   return launch_status(e);
 }
 
+int vfm_schedule_units(const int32_t* cu_seqlens, int n_seqs, int total_tokens, int n_heads,
+                       int rows_per_tile, int32_t* units, int capacity, int* n_blocks) {
+  if (!cu_seqlens || !n_blocks || (!units && capacity > 0)) return VFM_ERR_NULL;
+  if (n_seqs < 0 || n_seqs > VFM_MAX_SEQS || total_tokens < 0 || n_heads < 1 || n_heads > 65535 ||
+      rows_per_tile < 1 || capacity < 0)
+    return VFM_ERR_SHAPE;
+  if (int st = check_cu(cu_seqlens, n_seqs, total_tokens)) return st;
+  SegTable segs;
+  build_seg_table(cu_seqlens, n_seqs, &segs);
+  // exactly what the launchers and kernels do: count the tiles, build the unit map, and ask
+  // the kernels' own mapping which unit each workgroup of the grid takes
+  const vfm::UnitMap um = vfm::make_unit_map(vfm::count_tiles<false>(segs, rows_per_tile), n_heads);
+  const int grid = um.chunk * vfm::kNumXcd;
+  *n_blocks = grid;
+  if (grid > capacity) return VFM_ERR_SHAPE;
+  for (int b = 0; b < grid; ++b) {
+    int head, tile;
+    if (!vfm::map_unit(um, b, head, tile)) {
+      units[3 * b] = -1;
+      units[3 * b + 1] = units[3 * b + 2] = 0;
+      continue;
+    }
+    int s, t;
+    vfm::locate_tile<false>(segs, rows_per_tile, tile, s, t);
+    const int first = segs.q_start(s) + t * rows_per_tile;
+    units[3 * b] = head;
+    units[3 * b + 1] = first;
+    units[3 * b + 2] = std::min(rows_per_tile, segs.q_start(s) + segs.q_len(s) - first);
+  }
+  return VFM_OK;
+}
+
 size_t vfm_attn_bwd_workspace_size(int total_tokens, int n_heads, int head_dim) {
   if (check_shape(0, total_tokens, n_heads, head_dim)) return 0;
   const size_t rows = (size_t)total_tokens * n_heads;

@@ -90,7 +90,19 @@ struct UnitMap {
   int chunk;  // ceil(n_units / kNumXcd)
 };
 
-__device__ __forceinline__ bool map_unit(const UnitMap& um, int block, int& head, int& tile) {
+// The launch geometry of a kernel that takes one (head, tile) unit per workgroup: units are
+// numbered head-major and cut into kNumXcd contiguous chunks; workgroup b belongs to XCD
+// b % kNumXcd and takes unit (b % kNumXcd) * chunk + b / kNumXcd, so that the workgroups
+// sharing an L2 walk neighbouring tiles of the same head.  Grid = chunk * kNumXcd.
+__host__ inline UnitMap make_unit_map(int tiles_per_head, int n_heads) {
+  UnitMap um;
+  um.tiles_per_head = tiles_per_head;
+  um.n_units = tiles_per_head * n_heads;
+  um.chunk = (um.n_units + kNumXcd - 1) / kNumXcd;
+  return um;
+}
+
+__host__ __device__ __forceinline__ bool map_unit(const UnitMap& um, int block, int& head, int& tile) {
   const int xcd = block % kNumXcd;
   const int local = block / kNumXcd;
   const int u = xcd * um.chunk + local;
@@ -104,7 +116,7 @@ __device__ __forceinline__ bool map_unit(const UnitMap& um, int block, int& head
 // Tiles are cut from the query ranges (KV = false) or from the key/value ranges (KV = true);
 // rows_per_tile is the tile height.
 template <bool KV, class Segs>
-__device__ __forceinline__ void locate_tile(const Segs& segs, int rows_per_tile, int tile, int& s,
+__host__ __device__ __forceinline__ void locate_tile(const Segs& segs, int rows_per_tile, int tile, int& s,
                                             int& t) {
   s = 0;
   for (; s < segs.n - 1; ++s) {
