@@ -166,6 +166,19 @@ def test_forward_is_bitwise_reproducible():
     assert np.array_equal(l1.cpu().numpy(), l2.cpu().numpy())
 
 
+def test_backward_is_bitwise_reproducible():
+    # no atomics anywhere in the self-attention backward: two calls give identical bits
+    wl = SMALL["ragged128"]
+    b = _binding()
+    inp = W.make_inputs(wl)
+    q, k, v, do = (U.to_device(inp[n]) for n in ("q", "k", "v", "dout"))
+    out, lse = b.vfm_attn_fwd(q, k, v, wl.cu_seqlens, wl.scale)
+    g1 = b.vfm_attn_bwd(q, k, v, out, lse, do, wl.cu_seqlens, wl.scale)
+    g2 = b.vfm_attn_bwd(q, k, v, out, lse, do, wl.cu_seqlens, wl.scale)
+    for a, c in zip(g1, g2):
+        assert np.array_equal(U.to_bits(a), U.to_bits(c))
+
+
 def test_closed_forms_on_gpu():
     import torch
     b = _binding()
