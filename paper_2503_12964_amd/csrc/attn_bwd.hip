@@ -268,6 +268,21 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   wait_vmcnt<0>();
   __syncthreads();
 
+  // A wavefront whose 32 key rows all lie past the end of the sequence (ragged last tile) has
+  // nothing to compute.  It still fetches its share of every Q/dO tile and meets every
+  // barrier, in the order of the loop below: per tile the wait, the barrier, the request;
+  // then the final wait (and the epilogue's barrier).
+  if (j0 + wave * 32 >= kv_b) {
+    for (int t = 0; t < n_tiles; ++t) {
+      wait_vmcnt<0>();
+      __syncthreads();
+      issue_tile((t + 2) % kBwdRing);
+    }
+    wait_vmcnt<0>();
+    if constexpr (!SPLIT) __syncthreads();
+    return;
+  }
+
   bf16x8 qa_n[KS], da_n[KS];      // row operands of block b+1
   f32x16 s_cur, dp_cur;           // S(b), dP(b)
   {
@@ -818,6 +833,31 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
   issue_tile(1);              // (re-requests the last rows when the clip has a single tile)
   wait_vmcnt<2 * CPT>();      // tile 0 has landed
   __syncthreads();
+
+  // A wavefront whose 64 query rows all lie past the end of the sequence (ragged last tile)
+  // has nothing to compute.  It still fetches its share of every K/V tile, takes part in
+  // zeroing the last tile's tail rows and meets every barrier, in the order of the loop
+  // below: from the second tile on the wait, the barrier, the request; the two barriers
+  // around the zeroing; the epilogue's wait and barrier.
+  if (q0 + wave * 64 >= q_b) {
+    for (int t = 1; t < n_tiles; ++t) {
+      wait_vmcnt<0>();
+      __syncthreads();
+      if (t + 1 < n_tiles) issue_tile((t + 1) % kDq2Ring);
+    }
+    if (tail_rows < kDqBC) {
+      __syncthreads();
+      const u32x4 z = {0u, 0u, 0u, 0u};
+      const int n16 = (kDqBC - tail_rows) * (RB / 16);
+      for (int i = tid; i < n16; i += kDq2Waves * 64)
+        *reinterpret_cast<__attribute__((address_space(3))) u32x4*>(
+            smem_addr + ((n_tiles - 1) % kDq2Ring) * SB + tail_rows * RB + i * 16) = z;
+      __syncthreads();
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+    return;
+  }
 
   // ---- state carried between half-steps
   f32x16 sacc[2], dpacc[2];   // S^T, dP^T of the current key block, per query block
