@@ -829,17 +829,17 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
     for (int ks = 0; ks < KS; ++ks) { to_agpr(qreg[ib][ks]); to_agpr(doreg[ib][ks]); }
 #pragma unroll
   for (int ib = 0; ib < 2; ++ib) asm volatile("" :: "v"(lse2[ib]), "v"(dlt[ib]));
-  issue_tile(0);
-  issue_tile(1);              // (re-requests the last rows when the clip has a single tile)
-  wait_vmcnt<2 * CPT>();      // tile 0 has landed
-  __syncthreads();
-
   // A wavefront whose 64 query rows all lie past the end of the sequence (ragged last tile)
   // has nothing to compute.  It still fetches its share of every K/V tile, takes part in
   // zeroing the last tile's tail rows and meets every barrier, in the order of the loop
-  // below: from the second tile on the wait, the barrier, the request; the two barriers
+  // below: the prologue's requests, wait and barrier; from the second tile on the wait, the
+  // barrier, the request; the two barriers
   // around the zeroing; the epilogue's wait and barrier.
   if (q0 + wave * 64 >= q_b) {
+    issue_tile(0);
+    issue_tile(1);
+    wait_vmcnt<2 * CPT>();
+    __syncthreads();
     for (int t = 1; t < n_tiles; ++t) {
       wait_vmcnt<0>();
       __syncthreads();
@@ -858,6 +858,11 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
     __syncthreads();
     return;
   }
+
+  issue_tile(0);
+  issue_tile(1);              // (re-requests the last rows when the clip has a single tile)
+  wait_vmcnt<2 * CPT>();      // tile 0 has landed
+  __syncthreads();
 
   // ---- state carried between half-steps
   f32x16 sacc[2], dpacc[2];   // S^T, dP^T of the current key block, per query block

@@ -162,6 +162,29 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
     }
   };
 
+  // A wavefront whose 32 query rows all lie past the end of the sequence (the ragged last
+  // tile of a clip) has nothing to compute.  It still fetches its share of every K/V unit
+  // and meets every barrier, in the order of the code below: the prologue's requests, wait and
+  // two barriers; per unit the two requests, the
+  // wait, the barrier; then the epilogue's wait and barrier.
+  if (q0 + wave * 32 >= q_b) {
+    issue_k(0); issue_k(1); issue_k(2); issue_k(3);
+    issue_v(0); issue_v(1);
+    wait_vmcnt<0>();
+    __syncthreads();
+    __syncthreads();
+    issue_k(0);
+    for (int u = 0; u < n_units; ++u) {
+      issue_k((u + 1) % kFwdRing);
+      issue_v((u + 2) % kFwdRing);
+      wait_vmcnt<kInFlight>();
+      __syncthreads();
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+    return;
+  }
+
   // ---- prologue: K units 0..3 and V units 0..1 requested; S(0); operands of K(1)
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) settle(qreg[ks]);
@@ -190,22 +213,6 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   }
   __syncthreads();            // every wave holds K(0), K(1) in registers: slots 0, 1 are free
   issue_k(0);                 // K unit 4
-
-  // A wavefront whose 32 query rows all lie past the end of the sequence (the ragged last
-  // tile of a clip) has nothing to compute.  It still fetches its share of every K/V unit
-  // and meets every barrier, in the order of the loop below: per unit the two requests, the
-  // wait, the barrier; then the epilogue's wait and barrier.
-  if (q0 + wave * 32 >= q_b) {
-    for (int u = 0; u < n_units; ++u) {
-      issue_k((u + 1) % kFwdRing);
-      issue_v((u + 2) % kFwdRing);
-      wait_vmcnt<kInFlight>();
-      __syncthreads();
-    }
-    wait_vmcnt<0>();
-    __syncthreads();
-    return;
-  }
 
   bf16x8 pb_prev[2];          // P(u-1), set by the first iteration before any use
   pb_prev[0] = pb_prev[1] = bf16x8{};
