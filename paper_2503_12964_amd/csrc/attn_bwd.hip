@@ -793,13 +793,16 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
   };
 
   // ---- swizzled LDS addresses, one register each (opaque, so they are kept, not recomputed)
-  uint32_t rb[KS], tb[2][DB];
+  // (a second set for the third stage, which lies beyond the 64 KB an immediate offset
+  // reaches: without it every read of that stage costs a v_add_u32, 16 per key block)
+  uint32_t rb[KS], tb[2][DB], rb2[KS], tb2[2][DB];
   {
     const int rbase = tile_off<D>(c, 8 * g);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       rb[ks] = smem_addr + (rbase ^ (ks << 5));
-      asm volatile("" : "+v"(rb[ks]));
+      rb2[ks] = rb[ks] + 2 * SB;
+      asm volatile("" : "+v"(rb[ks]), "+v"(rb2[ks]));
     }
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -807,7 +810,8 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         tb[t][db] = smem_addr + (tbase ^ (db << 6));
-        asm volatile("" : "+v"(tb[t][db]));
+        tb2[t][db] = tb[t][db] + 2 * SB;
+        asm volatile("" : "+v"(tb[t][db]), "+v"(tb2[t][db]));
       }
     }
   }
@@ -928,7 +932,7 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
 #pragma unroll
           for (int x = (gi - 2 * KS) * per; x < (gi - 2 * KS + 1) * per; ++x) {
             const int ks = x >> 1;
-            const uint32_t a = rb[ks] + ST_NEXT * SB + JB_NEXT * 32 * RB;
+            const uint32_t a = (ST_NEXT == 2 ? rb2[ks] : rb[ks] + ST_NEXT * SB) + JB_NEXT * 32 * RB;
             if ((x & 1) == 0) ka[ks] = lds_read_b128_at(a); else va[ks] = lds_read_b128_at(a + TB);
           }
         }
@@ -938,7 +942,7 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
 #pragma unroll
           for (int x = 2 * gi; x < 2 * gi + 2; ++x) {
             const int s2 = x / (2 * DB), db = (x >> 1) % DB, hi = x & 1;
-            const uint32_t a = tb[hi][db] + ST_CUR * SB + (JB_CUR * 32 + 16 * s2) * RB;
+            const uint32_t a = (ST_CUR == 2 ? tb2[hi][db] : tb[hi][db] + ST_CUR * SB) + (JB_CUR * 32 + 16 * s2) * RB;
             if (hi) khi[s2][db] = lds_read_tr_at(a); else klo[s2][db] = lds_read_tr_at(a);
           }
         }
