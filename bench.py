@@ -46,7 +46,7 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel from `rocprofv3 --pmc` (FETCH_SIZE and
 # WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"C4": 24.92e9}
+MEASURED_TRAFFIC_BYTES = {"C4": 24.96e9}
 
 
 def _mfma_ceiling(seconds: float = 1.5):
