@@ -52,6 +52,7 @@ extern "C" {
 #define VFM_MAX_SEQS 256    /* clips per call, self-attention and RoPE */
 #define VFM_MAX_XSEQS 128   /* sequences per call, cross-attention */
 #define VFM_MAX_TEMPORAL 32 /* latent frames per clip, temporal attention */
+#define VFM_NOALLOC_MAX_ROWS (1 << 21) /* n_heads * total_tokens, vfm_attn_bwd_noalloc */
 
 #define VFM_API __attribute__((visibility("default")))
 
@@ -65,7 +66,8 @@ typedef enum {
   VFM_ERR_DTYPE = 6,       /* unsupported element type */
   VFM_ERR_WORKSPACE = 7,   /* workspace NULL, misaligned or too small */
   VFM_ERR_LAUNCH = 8,      /* the HIP runtime refused a launch */
-  VFM_ERR_ALIGN = 9        /* a tensor pointer is not 16-byte aligned */
+  VFM_ERR_ALIGN = 9,       /* a tensor pointer is not 16-byte aligned */
+  VFM_ERR_SCRATCH = 10     /* sizes beyond the built-in scratch of vfm_attn_bwd_noalloc */
 } vfm_status;
 
 typedef enum { VFM_BF16 = 0, VFM_F32 = 1 /* not implemented: VFM_ERR_DTYPE */ } vfm_dtype;
@@ -176,6 +178,31 @@ VFM_API int vfm_attn_bwd(const void* q, const void* k, const void* v, const void
                  int n_seqs, int total_tokens, int n_heads, int head_dim, float scale,
                  void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
                  vfm_dtype dt, void* hip_stream);
+
+/*
+ * vfm_attn_bwd for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments (minus the workspace), same kernels and
+ * bitwise the same dq, dk, dv as vfm_attn_bwd.  The statistics vfm_attn_bwd keeps
+ * in its workspace live in an array built into the library's device code instead:
+ * 2 * VFM_NOALLOC_MAX_ROWS * 4 + 256 bytes (16 MiB) that every GPU the library runs
+ * on holds from the first use until the process ends.  Limit:
+ * n_heads * total_tokens <= VFM_NOALLOC_MAX_ROWS (the 56,320-token, 32-head
+ * latent fits); larger calls return VFM_ERR_SCRATCH and launch nothing.
+ * The call allocates and frees nothing, on the device or through any library; it
+ * looks up the array's device address once per device (the device that is
+ * current at the call must be the one that owns the stream and the tensors) and
+ * enqueues the kernels on hip_stream.  All calls on one GPU share that GPU's
+ * array: calls that may overlap in time on one GPU (different streams, or
+ * different threads) race on it and must be serialised by the caller; calls on
+ * one stream are safe.  Nothing in the array has to be cleared between calls
+ * (every call first rewrites what it later reads).
+ * Errors: NULL, SHAPE, CU_SEQLENS, DTYPE, ALIGN, SCRATCH, LAUNCH.
+ */
+VFM_API int vfm_attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* out,
+                         const float* lse, const void* dout, const int32_t* cu_seqlens,
+                         int n_seqs, int total_tokens, int n_heads, int head_dim, float scale,
+                         void* dq, void* dk, void* dv, vfm_dtype dt, void* hip_stream);
 
 /*
  * Cross-attention forward (Section 4.2: in every transformer block the video

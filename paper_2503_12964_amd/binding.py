@@ -21,7 +21,7 @@ VFM_BF16 = 0
 VFM_F32 = 1
 VFM_MAX_SEQS = 256
 
-EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_xattn_fwd", "vfm_xattn_bwd_workspace_size", "vfm_xattn_bwd", "vfm_tattn_fwd", "vfm_tattn_bwd",
+EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_attn_bwd_noalloc", "vfm_xattn_fwd", "vfm_xattn_bwd_workspace_size", "vfm_xattn_bwd", "vfm_tattn_fwd", "vfm_tattn_bwd",
            "vfm_fp8_pack_sizes", "vfm_fp8_pack", "vfm_attn_fwd_fp8", "vfm_strerror", "vfm_last_hip_error", "vfm_schedule_units")
 
 _lib = None
@@ -70,6 +70,10 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.vfm_attn_bwd.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, p_i32, c_int,
                                  c_int, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p, c_void_p,
                                  c_size_t, c_int, c_void_p]
+    lib.vfm_attn_bwd_noalloc.restype = c_int
+    lib.vfm_attn_bwd_noalloc.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, p_i32, c_int,
+                                         c_int, c_int, c_int, c_float, c_void_p, c_void_p, c_void_p, c_int,
+                                         c_void_p]
     lib.vfm_xattn_fwd.restype = c_int
     lib.vfm_xattn_fwd.argtypes = [c_void_p, c_void_p, c_void_p, p_i32, p_i32, c_int, c_int, c_int, c_int, c_int,
                                   c_float, c_void_p, c_void_p, c_int, c_void_p]
@@ -253,6 +257,19 @@ def vfm_attn_bwd(q, k, v, out, lse, dout, cu_seqlens, scale: float, dq=None, dk=
                             float(scale), _dev(dq, "dq"), _dev(dk, "dk"), _dev(dv, "dv"),
                             _dev(workspace, "workspace"), int(workspace.numel() * workspace.element_size()),
                             _dtype_code(q), _stream_ptr(stream)))
+    return dq, dk, dv
+
+
+def vfm_attn_bwd_noalloc(q, k, v, out, lse, dout, cu_seqlens, scale: float, dq, dk, dv, stream=None) -> Tuple:
+    """vfm_attn_bwd without a workspace (the library's built-in scratch holds the statistics).
+    The caller passes every output; nothing is allocated here or in the library."""
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    total, heads, hd = q.shape
+    _check(lib.vfm_attn_bwd_noalloc(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(out, "out"), _dev(lse, "lse"),
+                                    _dev(dout, "dout"), _i32_ptr(cu), int(cu.size - 1), int(total), int(heads),
+                                    int(hd), float(scale), _dev(dq, "dq"), _dev(dk, "dk"), _dev(dv, "dv"),
+                                    _dtype_code(q), _stream_ptr(stream)))
     return dq, dk, dv
 
 

@@ -3,6 +3,8 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <atomic>
+#include <mutex>
 
 #include "vfm_common.h"
 
@@ -174,6 +176,43 @@ inline int launch_status(hipError_t e) {
   return VFM_ERR_LAUNCH;
 }
 
+// ---- built-in scratch of the entry point that allocates nothing ---------------------------
+// vfm_attn_bwd_noalloc keeps the backward's statistics (Delta, lse in log2 units, sentinels)
+// here instead of in a caller workspace.  Every GPU the library runs on holds its own copy
+// of the array at its own address until the process ends.  `scratch` itself is only a
+// host-side handle: host code never passes it anywhere, it asks the runtime once per device
+// for the device address and uses that.
+constexpr size_t kNoallocRows = VFM_NOALLOC_MAX_ROWS;                  // n_heads * total_tokens
+constexpr size_t kNoallocPart = kNoallocRows * sizeof(float);         // one statistics array
+constexpr size_t kNoallocBytes = 2 * kNoallocPart + 256;
+static __device__ __align__(256) unsigned char scratch[kNoallocBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of `scratch` (looked up on the first call on
+// that device, then cached).
+hipError_t scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+    if (!p) {
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return e;
+      if (!p || (reinterpret_cast<uintptr_t>(p) & 255u)) return hipErrorInvalidSymbol;
+      g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+  }
+  *out = p;
+  return hipSuccess;
+}
+
 }  // namespace
 
 extern "C" {
@@ -192,6 +231,7 @@ const char* vfm_strerror(int status) {
     case VFM_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or smaller than vfm_attn_bwd_workspace_size()";
     case VFM_ERR_LAUNCH: return "the HIP runtime refused a kernel launch";
     case VFM_ERR_ALIGN: return "tensor pointers must be 16-byte aligned";
+    case VFM_ERR_SCRATCH: return "n_heads * total_tokens exceeds VFM_NOALLOC_MAX_ROWS, the capacity of the built-in scratch of vfm_attn_bwd_noalloc (use vfm_attn_bwd with a workspace)";
     default: return "unknown status";
   }
 }
@@ -347,6 +387,39 @@ int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, c
   hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_tokens, n_heads,
                                       head_dim, scale, dq, dk, dv, delta, lse2, sentinel, nullptr, 0,
                                       static_cast<hipStream_t>(hip_stream));
+  return launch_status(e);
+}
+
+int vfm_attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* out,
+                         const float* lse, const void* dout, const int32_t* cu_seqlens, int n_seqs,
+                         int total_tokens, int n_heads, int head_dim, float scale, void* dq, void* dk,
+                         void* dv, vfm_dtype dt, void* hip_stream) {
+  if (!q || !k || !v || !out || !lse || !dout || !cu_seqlens || !dq || !dk || !dv)
+    return VFM_ERR_NULL;
+  if (dt != VFM_BF16) return VFM_ERR_DTYPE;
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  if (st) return st;
+  if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
+  st = check_cu(cu_seqlens, n_seqs, total_tokens);
+  if (st) return st;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse) ||
+      !aligned16(dout) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
+    return VFM_ERR_ALIGN;
+  if ((size_t)total_tokens * (size_t)n_heads > kNoallocRows) return VFM_ERR_SCRATCH;
+  if (total_tokens == 0) return VFM_OK;
+  void* base = nullptr;
+  hipError_t e = scratch_of_current_device(&base);
+  if (e != hipSuccess) return launch_status(e);
+  // the same three regions vfm_attn_bwd cuts from its workspace, at fixed places
+  float* delta = static_cast<float*>(base);
+  float* lse2 = reinterpret_cast<float*>(static_cast<char*>(base) + kNoallocPart);
+  float* sentinel = reinterpret_cast<float*>(static_cast<char*>(base) + 2 * kNoallocPart);
+  SegTable segs;
+  build_seg_table(cu_seqlens, n_seqs, &segs);
+  forget_foreign_errors();
+  e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_tokens, n_heads, head_dim, scale, dq,
+                           dk, dv, delta, lse2, sentinel, nullptr, 0,
+                           static_cast<hipStream_t>(hip_stream));
   return launch_status(e);
 }
 

@@ -47,8 +47,8 @@ def test_header_compiles_as_c_and_cxx(tmp_path):
 
 def test_strerror_texts(lib):
     assert lib.vfm_strerror(0) == b"ok"
-    texts = {lib.vfm_strerror(i) for i in range(10)}
-    assert len(texts) == 10 and b"unknown status" not in texts
+    texts = {lib.vfm_strerror(i) for i in range(11)}
+    assert len(texts) == 11 and b"unknown status" not in texts
     assert lib.vfm_strerror(99) == b"unknown status"
     # no launch has failed in this process: the runtime's text for "success"
     assert lib.vfm_last_hip_error() == b"no error"
