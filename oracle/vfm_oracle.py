@@ -234,7 +234,7 @@ def attn_fwd(q, k, v, cu_seqlens, scale: float):
     return out, lse
 
 
-def attn_bwd(q, k, v, dout, cu_seqlens, scale: float):
+def attn_bwd(q, k, v, dout, cu_seqlens, scale: float, out=None):
     """Gradients of  sum(out * dout)  with respect to q, k, v.
 
     The softmax-attention gradient written out (no gradient flows into lse):
@@ -244,12 +244,20 @@ def attn_bwd(q, k, v, dout, cu_seqlens, scale: float):
         dS_ij   = P_ij (dP_ij - Delta_i)
         dQ_i    = scale * sum_j dS_ij K_j
         dK_j    = scale * sum_i dS_ij Q_i
-    P is recomputed from this module's own forward.  Returns dq, dk, dv with
-    the shape of q, fp64.
+    P is recomputed from this module's own forward, and so is O: the result is
+    the exact gradient.  The backward call of the method is handed the
+    forward's output as an argument and forms Delta = rowsum(dO o O) from it;
+    `out` (same shape as q), when given, takes that place in Delta and nowhere
+    else, so that tests can tell the rounding of a handed-over bf16 `out`
+    (which shows where dS cancels: peaky softmax, clips of a few tokens) from
+    damage.  Returns dq, dk, dv with the shape of q, fp64.
     """
     q, k, v, dout = _as_f64(q), _as_f64(k), _as_f64(v), _as_f64(dout)
     total, H, D = q.shape
     cu = _check_cu(cu_seqlens, total)
+    given = None if out is None else _as_f64(out)
+    if given is not None and given.shape != q.shape:
+        raise ValueError("out must have the shape of q")
     dq = np.zeros_like(q)
     dk = np.zeros_like(k)
     dv = np.zeros_like(v)
@@ -260,7 +268,7 @@ def attn_bwd(q, k, v, dout, cu_seqlens, scale: float):
         for h in range(H):
             Q, K, V, dO = q[a:b, h, :], k[a:b, h, :], v[a:b, h, :], dout[a:b, h, :]
             P, _ = _softmax_rows(scale * (Q @ K.T))
-            O = P @ V
+            O = P @ V if given is None else given[a:b, h, :]
             delta = (dO * O).sum(axis=1, keepdims=True)
             dv[a:b, h, :] = P.T @ dO
             dP = dO @ V.T

@@ -49,6 +49,9 @@ MUTANTS = {
     "bwd_delta_dropped": ("dS = P * (dP - delta)\n            dq[a:b", "dS = P * dP\n            dq[a:b", 0),
     "bwd_delta_sign": ("dS = P * (dP - delta)\n            dq[a:b", "dS = P * (dP + delta)\n            dq[a:b", 0),
     "bwd_delta_from_v": ("delta = (dO * O).sum(axis=1, keepdims=True)\n            dv[a:b", "delta = (dO * V).sum(axis=1, keepdims=True)\n            dv[a:b", 0),
+    "bwd_given_out_ignored": ("O = P @ V if given is None else given[a:b, h, :]", "O = P @ V", 0),
+    "bwd_given_out_of_head_zero": ("O = P @ V if given is None else given[a:b, h, :]",
+                                   "O = P @ V if given is None else given[a:b, 0, :]", 0),
     "bwd_dq_scale_dropped": ("dq[a:b, h, :] = scale * (dS @ K)", "dq[a:b, h, :] = (dS @ K)", 0),
     "bwd_dk_not_transposed": ("dk[a:b, h, :] = scale * (dS.T @ Q)", "dk[a:b, h, :] = scale * (dS @ Q)", 0),
     "bwd_dq_transposed": ("dq[a:b, h, :] = scale * (dS @ K)", "dq[a:b, h, :] = scale * (dS.T @ K)", 0),

@@ -235,6 +235,46 @@ def test_against_torch_autograd_fp64():
     np.testing.assert_allclose(dv, tv.grad.numpy(), atol=1e-13)
 
 
+# ---------------------------------------------------------- Delta from a handed-over out
+def test_backward_with_the_forwards_own_out_is_the_exact_gradient():
+    lens = [9, 0, 5, 1]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    q, k, v, do = _inputs(cu, 3, 8, 130)
+    out, _ = orc.attn_fwd(q, k, v, cu, 0.4)
+    for a, b in zip(orc.attn_bwd(q, k, v, do, cu, 0.4), orc.attn_bwd(q, k, v, do, cu, 0.4, out=out)):
+        np.testing.assert_allclose(a, b, atol=1e-15)
+    with pytest.raises(ValueError):
+        orc.attn_bwd(q, k, v, do, cu, 0.4, out=out[:, :2])
+
+
+def test_a_perturbed_out_moves_the_gradients_through_delta_alone():
+    # Closed form, written with plain loops: with out + E handed over, Delta_i grows by
+    # e_i = sum_d dO_id E_id, hence dS_ij falls by P_ij e_i:
+    #   dQ_i falls by scale * e_i * sum_j P_ij K_j,  dK_j by scale * sum_i P_ij e_i Q_i,  dV is unchanged.
+    lens = [6, 4]
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    H, D, scale = 2, 4, 0.7
+    q, k, v, do = _inputs(cu, H, D, 131)
+    out, _ = orc.attn_fwd(q, k, v, cu, scale)
+    E = 0.05 * np.random.default_rng(132).standard_normal(out.shape)
+    base = orc.attn_bwd(q, k, v, do, cu, scale)
+    moved = orc.attn_bwd(q, k, v, do, cu, scale, out=out + E)
+    want_dq, want_dk = np.zeros_like(q), np.zeros_like(k)
+    for s in range(len(lens)):
+        a, b = int(cu[s]), int(cu[s + 1])
+        for h in range(H):
+            for i in range(a, b):
+                w = np.array([np.exp(scale * float(q[i, h] @ k[j, h])) for j in range(a, b)])
+                p = w / w.sum()
+                e = float(do[i, h] @ E[i, h])
+                for jj, j in enumerate(range(a, b)):
+                    want_dq[i, h] -= scale * e * p[jj] * k[j, h]
+                    want_dk[j, h] -= scale * e * p[jj] * q[i, h]
+    np.testing.assert_allclose(moved[0] - base[0], want_dq, atol=1e-13)
+    np.testing.assert_allclose(moved[1] - base[1], want_dk, atol=1e-13)
+    np.testing.assert_allclose(moved[2], base[2], atol=1e-15)
+
+
 # ---------------------------------------------------------- row-subset helpers
 def test_row_helpers_match_full_functions():
     lens = [13, 0, 6, 21]
