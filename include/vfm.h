@@ -26,8 +26,15 @@
  *   - cu_seqlens and thw are HOST int32 arrays, read before the call returns
  *     (they fix the launch geometry and travel to the kernels by value).
  *   - Element type is bf16 (VFM_BF16).  Accumulation is fp32.
- *   - head_dim is 64 or 128.  n_seqs is at most VFM_MAX_SEQS.  Empty clips
- *     (cu_seqlens[s] == cu_seqlens[s+1]) are legal and do no work.
+ *   - head_dim is 64 or 128.  Empty clips (cu_seqlens[s] == cu_seqlens[s+1]) are
+ *     legal and do no work.  n_seqs is not limited (Section 3.1 packs images and
+ *     videos together, and the spatial view of Section 4.6 makes every latent
+ *     frame a sequence): the clip tables travel to the kernels by value and hold
+ *     VFM_MAX_SEQS clips, so a call with more is cut, inside the library, into
+ *     consecutive launches on hip_stream over runs of VFM_MAX_SEQS clips in
+ *     packed order (VFM_MAX_XSEQS sequences for cross-attention).  Clips are
+ *     independent, so the result does not depend on where the runs are cut.
+ *     (Exception: the FP8 entry points take at most VFM_MAX_SEQS clips per call.)
  *   - Every function returns a vfm_status; 0 is success.  Argument errors are
  *     detected before anything is launched and leave all outputs untouched.
  *   - Re-entrant: no global mutable state (beyond the calling thread's last
@@ -49,8 +56,8 @@
 extern "C" {
 #endif
 
-#define VFM_MAX_SEQS 256    /* clips per call, self-attention and RoPE */
-#define VFM_MAX_XSEQS 128   /* sequences per call, cross-attention */
+#define VFM_MAX_SEQS 256    /* clips per launch (run), self-attention, RoPE, temporal attention */
+#define VFM_MAX_XSEQS 128   /* sequences per launch (run), cross-attention */
 #define VFM_MAX_TEMPORAL 32 /* latent frames per clip, temporal attention */
 #define VFM_NOALLOC_MAX_ROWS (1 << 21) /* n_heads * total_tokens, vfm_attn_bwd_noalloc */
 
@@ -59,7 +66,7 @@ extern "C" {
 typedef enum {
   VFM_OK = 0,
   VFM_ERR_NULL = 1,        /* a required pointer is NULL */
-  VFM_ERR_SHAPE = 2,       /* total_tokens/n_heads/head_dim/n_seqs out of range */
+  VFM_ERR_SHAPE = 2,       /* total_tokens/n_heads/head_dim/n_seqs/scale/theta/eps out of range */
   VFM_ERR_CU_SEQLENS = 3,  /* not starting at 0, decreasing, or not ending at total_tokens */
   VFM_ERR_THW = 4,         /* T*H*W differs from the clip length, or a non-positive extent */
   VFM_ERR_SPLIT = 5,       /* dim_t+dim_h+dim_w != head_dim, or an odd/negative part */
@@ -171,6 +178,14 @@ VFM_API size_t vfm_attn_bwd_workspace_size(int total_tokens, int n_heads, int he
  * accumulated into).  workspace: device, 256-byte aligned, at least
  * vfm_attn_bwd_workspace_size() bytes.  No atomics are used: dq, dk and dv are
  * bitwise reproducible from run to run.
+ * Accuracy: Delta_i = sum_d dout[i,d] out[i,d] is formed from the bf16 `out`
+ * handed in, whose rounding (2^-9 relative) is harmless once a clip has a few
+ * dozen keys (|out| shrinks like 1/sqrt(keys)) but would reach several percent
+ * of dq, dk in clips of two to eight tokens, where dS cancels almost completely.
+ * For clips of at most 32 keys the library therefore recomputes Delta_i as
+ * sum_j P_ij (dout_i . v_j), the same quantity without the rounded `out`; with
+ * it dq, dk, dv stay within 1.5e-2 relative RMS of the exact gradients for every
+ * clip length.
  * Errors: NULL, SHAPE, CU_SEQLENS, DTYPE, ALIGN, WORKSPACE, LAUNCH.
  */
 VFM_API int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out,
@@ -213,7 +228,7 @@ VFM_API int vfm_attn_bwd_noalloc(const void* q, const void* k, const void* v, co
  *     S_ij  = scale * sum_d q[i,h,d] k[j,h,d]
  *     out_i = sum_j softmax_j(S_ij) v[j,h,:],   lse_i = ln sum_j exp(S_ij)
  * out: bf16 [total_q, n_heads, head_dim]; lse: fp32 [n_heads, total_q].  Both
- * cu arrays are host int32 [n_seqs+1], n_seqs <= VFM_MAX_XSEQS.  A sequence
+ * cu arrays are host int32 [n_seqs+1].  A sequence
  * with queries must have at least one key (CU_SEQLENS); one with keys and no
  * queries is legal.  Same kernels, arithmetic and reproducibility as
  * vfm_attn_fwd, which is the case of equal ranges.
@@ -329,16 +344,29 @@ VFM_API int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8,
  * clips are never enumerated), clips longest first, and the (head, tile) units
  * are dealt to the grid so that the workgroups of one XCD (workgroup index mod
  * 8) take consecutive tiles of the same head.  The attention kernels use this
- * very mapping with rows_per_tile = 256 (forward and dQ; 128 in the forward at
- * head_dim 64) over query rows and 128 (dK/dV) over key rows.
+ * very mapping over query rows with rows_per_tile = 256 in the dQ kernel and
+ * vfm_attn_fwd_tile_rows() in the forward, and over key rows with 128 (dK/dV).
  * For workgroup b < *n_blocks: units[3b] = head (-1: the workgroup is grid
  * padding and exits), units[3b+1] = first packed row, units[3b+2] = rows
- * (1..rows_per_tile).  units is a HOST int32 [capacity][3] array; *n_blocks is
- * always set; SHAPE if capacity < *n_blocks.
+ * (1..rows_per_tile).  With more than VFM_MAX_SEQS clips the call is one launch
+ * per run of VFM_MAX_SEQS clips; the grids of the launches follow one another in
+ * units (each a multiple of 8 workgroups).  units is a HOST int32 [capacity][3]
+ * array; *n_blocks is always set; SHAPE if capacity < *n_blocks.
  */
 VFM_API int vfm_schedule_units(const int32_t* cu_seqlens, int n_seqs, int total_tokens,
                        int n_heads, int rows_per_tile, int32_t* units, int capacity,
                        int* n_blocks);
+
+/*
+ * Query rows per workgroup that vfm_attn_fwd uses for run `run` (0-based; a call
+ * with at most VFM_MAX_SEQS clips has the single run 0) of these clips, on the
+ * host: 256 at head_dim 128 when the run's longest clip has more than 1,024
+ * tokens, otherwise 128 (two workgroups per compute unit, whose prologues and
+ * epilogues overlap each other's loops); always 128 at head_dim 64.
+ * Errors: NULL, SHAPE (also: no such run), CU_SEQLENS.
+ */
+VFM_API int vfm_attn_fwd_tile_rows(const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                           int head_dim, int run, int* rows_per_tile);
 
 /* Static, human-readable text for a vfm_status. */
 VFM_API const char* vfm_strerror(int status);

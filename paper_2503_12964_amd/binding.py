@@ -22,7 +22,8 @@ VFM_F32 = 1
 VFM_MAX_SEQS = 256
 
 EXPORTS = ("vfm_rope3d", "vfm_qknorm_rope3d", "vfm_qknorm_rope3d_bwd", "vfm_attn_fwd", "vfm_attn_bwd_workspace_size", "vfm_attn_bwd", "vfm_attn_bwd_noalloc", "vfm_xattn_fwd", "vfm_xattn_bwd_workspace_size", "vfm_xattn_bwd", "vfm_tattn_fwd", "vfm_tattn_bwd",
-           "vfm_fp8_pack_sizes", "vfm_fp8_pack", "vfm_attn_fwd_fp8", "vfm_strerror", "vfm_last_hip_error", "vfm_schedule_units")
+           "vfm_fp8_pack_sizes", "vfm_fp8_pack", "vfm_attn_fwd_fp8", "vfm_strerror", "vfm_last_hip_error", "vfm_schedule_units",
+           "vfm_attn_fwd_tile_rows")
 
 _lib = None
 
@@ -102,6 +103,8 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
     lib.vfm_strerror.argtypes = [c_int]
     lib.vfm_schedule_units.restype = c_int
     lib.vfm_schedule_units.argtypes = [p_i32, c_int, c_int, c_int, c_int, p_i32, c_int, ctypes.POINTER(c_int)]
+    lib.vfm_attn_fwd_tile_rows.restype = c_int
+    lib.vfm_attn_fwd_tile_rows.argtypes = [p_i32, c_int, c_int, c_int, c_int, ctypes.POINTER(c_int)]
     lib.vfm_last_hip_error.restype = ctypes.c_char_p
     lib.vfm_last_hip_error.argtypes = []
     if path == LIB_PATH:
@@ -142,6 +145,16 @@ def vfm_schedule_units(cu_seqlens, n_heads: int, rows_per_tile: int) -> np.ndarr
     _check(lib.vfm_schedule_units(_i32_ptr(cu), int(cu.size - 1), int(cu[-1]), int(n_heads), int(rows_per_tile),
                                   _i32_ptr(units), int(units.shape[0]), ctypes.byref(n)))
     return units[:n.value]
+
+
+def vfm_attn_fwd_tile_rows(cu_seqlens, head_dim: int, run: int = 0) -> int:
+    """Query rows per workgroup the forward uses for run `run` of these clips.  Host only."""
+    lib = load_library()
+    cu = _host_i32(cu_seqlens)
+    rows = ctypes.c_int(0)
+    _check(lib.vfm_attn_fwd_tile_rows(_i32_ptr(cu), int(cu.size - 1), int(cu[-1]), int(head_dim), int(run),
+                                      ctypes.byref(rows)))
+    return rows.value
 
 
 def _host_i32(a) -> np.ndarray:

@@ -68,6 +68,59 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const u32x4* __restric
   }
 }
 
+// ---------------------------------------------------------------- Delta for short key ranges
+// Delta_i = sum_d dO_id O_id is taken from the bf16 `out` the call is given.  In a sequence
+// with a handful of keys |O| is as large as |V|, dS_ij = P_ij (dP_ij - Delta_i) is small by
+// cancellation, and the rounding of `out` (2^-9 relative) shows in dQ and dK: up to 13% of the
+// tensor in a two-token clip, below 0.1% from 32 keys on.  For sequences with at most
+// kShortKeys keys Delta is therefore recomputed here in its other form,
+//     Delta_i = sum_j P_ij dP_ij,   P_ij = exp(scale q_i.k_j - lse_i),   dP_ij = dO_i.v_j,
+// in fp32 from the bf16 operands (the two forms are the same quantity for the exact O).
+// One lane per query row; the key loop is uniform across the wavefront.  A negligible amount
+// of work (at most 32 keys per query), launched only when the call has such a sequence.
+constexpr int kShortKeys = 32;
+
+template <int D, class Segs>
+__global__ __launch_bounds__(64) void bwd_short_delta_kernel(
+    const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
+    const __bf16* __restrict__ dout, const float* __restrict__ lse, float* __restrict__ delta,
+    const Segs segs, int total, int n_heads, float scale) {
+  int seq, t;
+  locate_tile<false>(segs, 64, blockIdx.x, seq, t);
+  const int nk = segs.kv_len(seq);
+  if (nk > kShortKeys) return;
+  const int head = blockIdx.y;
+  const int i = segs.q_start(seq) + t * 64 + (int)threadIdx.x;
+  if (i >= segs.q_start(seq) + segs.q_len(seq)) return;
+  const size_t row_stride = (size_t)n_heads * D;
+  const u32x4* qi = reinterpret_cast<const u32x4*>(q + (size_t)i * row_stride + (size_t)head * D);
+  const u32x4* di = reinterpret_cast<const u32x4*>(dout + (size_t)i * row_stride + (size_t)head * D);
+  u32x4 qw[D / 8], dw[D / 8];     // packed bf16 pairs, widened on use
+#pragma unroll
+  for (int c = 0; c < D / 8; ++c) { qw[c] = qi[c]; dw[c] = di[c]; }
+  const float lse_i = lse[(size_t)head * total + i];
+  float acc = 0.f;
+  for (int j = 0; j < nk; ++j) {
+    const size_t off = (size_t)(segs.kv_start(seq) + j) * row_stride + (size_t)head * D;
+    const u32x4* kj = reinterpret_cast<const u32x4*>(k + off);
+    const u32x4* vj = reinterpret_cast<const u32x4*>(v + off);
+    float s = 0.f, dp = 0.f;
+#pragma unroll
+    for (int c = 0; c < D / 8; ++c) {
+      const u32x4 kw = kj[c], vw = vj[c];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        s += __builtin_bit_cast(float, qw[c][e] << 16) * __builtin_bit_cast(float, kw[e] << 16);
+        s += __builtin_bit_cast(float, qw[c][e] & 0xffff0000u) * __builtin_bit_cast(float, kw[e] & 0xffff0000u);
+        dp += __builtin_bit_cast(float, dw[c][e] << 16) * __builtin_bit_cast(float, vw[e] << 16);
+        dp += __builtin_bit_cast(float, dw[c][e] & 0xffff0000u) * __builtin_bit_cast(float, vw[e] & 0xffff0000u);
+      }
+    }
+    acc += fast_exp2((s * scale - lse_i) * kLog2eB) * dp;
+  }
+  delta[(size_t)head * total + i] = acc;
+}
+
 // ---------------------------------------------------------------- dK, dV
 // Software pipelined over query blocks of 32 rows so that a single wavefront per SIMD
 // always has independent MFMA and VALU work: iteration b runs
@@ -1029,14 +1082,18 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
                                const float* lse, const void* dout, const Segs& segs, int total,
                                int n_heads, float scale, void* dq, void* dk, void* dv,
                                float* delta, float* lse2, float* sentinel, float* dkv32, int total_kv,
-                               hipStream_t stream) {
+                               int kv_lo, int kv_hi, hipStream_t stream) {
+  const __bf16 *qb = (const __bf16*)q, *kb = (const __bf16*)k, *vb = (const __bf16*)v, *dob = (const __bf16*)dout;
+  hipError_t e;
   if (total > 0) {   // (with no queries at all only the keys' zero gradients remain to be written)
-    constexpr int kTokPerBlock = 256 / (D / 8);
-    const int grid = (total + kTokPerBlock - 1) / kTokPerBlock;
-    bwd_prepare_kernel<D><<<grid, 256, 0, stream>>>((const u32x4*)out, (const u32x4*)dout, lse,
-                                                    delta, lse2, sentinel, total, n_heads);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    bool any_short = false;
+    for (int s2 = 0; s2 < segs.n; ++s2)
+      any_short |= segs.q_len(s2) > 0 && segs.kv_len(s2) > 0 && segs.kv_len(s2) <= kShortKeys;
+    if (any_short) {   // sequences with a handful of keys: Delta in its cancellation-free form
+      e = launch(bwd_short_delta_kernel<D, Segs>, dim3(count_tiles<false>(segs, 64), n_heads), dim3(64), 0,
+                 stream, qb, kb, vb, dob, lse, delta, segs, total, n_heads, scale);
+      if (e != hipSuccess) return e;
+    }
   }
   {
     using Cfg = BwdCfg<D>;
@@ -1050,37 +1107,40 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
       for (int s2 = 0; s2 < segs.n; ++s2) max_q = std::max(max_q, segs.q_len(s2));
       q_split = std::min(std::min(16, (256 + tiles * n_heads - 1) / (tiles * n_heads)), std::max(1, max_q / 512));
     }
-    hipError_t e;
     if (q_split > 1) {
+      // the accumulators and the conversion cover this run's key rows [kv_lo, kv_hi) only:
+      // other runs of the same call own the rest of dk, dv
       const size_t kv_elems = (size_t)total_kv * n_heads * D;
-      const size_t n4 = 2 * kv_elems / 4;
-      fill_zero_f32x4_kernel<<<(unsigned)((n4 + 255) / 256), 256, 0, stream>>>((f32x4*)dkv32, n4);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
+      const size_t lo4 = (size_t)kv_lo * n_heads * D / 4, h4 = (size_t)(kv_hi - kv_lo) * n_heads * D / 4;
+      const dim3 cgrid((unsigned)((h4 + 255) / 256));
+      f32x4* acc_k = (f32x4*)dkv32 + lo4;
+      f32x4* acc_v = (f32x4*)(dkv32 + kv_elems) + lo4;
+      e = launch(fill_zero_f32x4_kernel, cgrid, dim3(256), 0, stream, acc_k, h4);
+      if (e != hipSuccess) return e;
+      e = launch(fill_zero_f32x4_kernel, cgrid, dim3(256), 0, stream, acc_v, h4);
+      if (e != hipSuccess) return e;
       um = make_unit_map(tiles * q_split, n_heads);
       auto kern = attn_bwd_dkdv_kernel<D, Segs, true>;
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
       if (e != hipSuccess) return e;
-      kern<<<um.chunk * kNumXcd, kBwdWaves * 64, Cfg::kLdsBytes, stream>>>(
-          (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse2, delta,
-          sentinel, (__bf16*)dk, (__bf16*)dv, segs, um, total, n_heads, scale, scale * kLog2eB,
-          dkv32, kv_elems, q_split);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
-      const size_t h4 = kv_elems / 4;
-      f32_to_bf16_kernel<<<(unsigned)((h4 + 255) / 256), 256, 0, stream>>>((const f32x4*)dkv32, (bf16x4*)dk, h4);
-      f32_to_bf16_kernel<<<(unsigned)((h4 + 255) / 256), 256, 0, stream>>>((const f32x4*)(dkv32 + kv_elems),
-                                                                          (bf16x4*)dv, h4);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
+      e = launch(kern, dim3(um.chunk * kNumXcd), dim3(kBwdWaves * 64), Cfg::kLdsBytes, stream, qb, kb, vb, dob,
+                 lse2, delta, sentinel, (__bf16*)dk, (__bf16*)dv, segs, um, total, n_heads, scale,
+                 scale * kLog2eB, dkv32, kv_elems, q_split);
+      if (e != hipSuccess) return e;
+      e = launch(f32_to_bf16_kernel, cgrid, dim3(256), 0, stream, (const f32x4*)acc_k, (bf16x4*)dk + lo4, h4);
+      if (e != hipSuccess) return e;
+      e = launch(f32_to_bf16_kernel, cgrid, dim3(256), 0, stream, (const f32x4*)acc_v, (bf16x4*)dv + lo4, h4);
+      if (e != hipSuccess) return e;
     } else {
       auto kern = attn_bwd_dkdv_kernel<D, Segs, false>;
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
       if (e != hipSuccess) return e;
-      kern<<<um.chunk * kNumXcd, kBwdWaves * 64, Cfg::kLdsBytes, stream>>>(
-          (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse2, delta,
-          sentinel, (__bf16*)dk, (__bf16*)dv, segs, um, total, n_heads, scale, scale * kLog2eB,
-          nullptr, 0, 1);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
+      e = launch(kern, dim3(um.chunk * kNumXcd), dim3(kBwdWaves * 64), Cfg::kLdsBytes, stream, qb, kb, vb, dob,
+                 lse2, delta, sentinel, (__bf16*)dk, (__bf16*)dv, segs, um, total, n_heads, scale,
+                 scale * kLog2eB, (float*)nullptr, (size_t)0, 1);
+      if (e != hipSuccess) return e;
     }
   }
   if constexpr (D == 128) {
@@ -1089,13 +1149,11 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
     if (tiles == 0) return hipSuccess;
     UnitMap um = make_unit_map(tiles, n_heads);
     auto kern = attn_bwd_dq2_kernel<D, Segs>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
-    kern<<<um.chunk * kNumXcd, kDq2Waves * 64, Cfg::kLdsBytes, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse2, delta,
-        (__bf16*)dq, segs, um, total, n_heads, scale, scale * kLog2eB);
-    return hipGetLastError();
+    return launch(kern, dim3(um.chunk * kNumXcd), dim3(kDq2Waves * 64), Cfg::kLdsBytes, stream, qb, kb, vb, dob,
+                  lse2, delta, (__bf16*)dq, segs, um, total, n_heads, scale, scale * kLog2eB);
   } else {
     constexpr int NI = 1;
     constexpr int W = 8;   // 256 query rows share each staged K/V tile
@@ -1104,14 +1162,26 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
     if (tiles == 0) return hipSuccess;
     UnitMap um = make_unit_map(tiles, n_heads);
     auto kern = attn_bwd_dq_kernel<D, NI, W, Segs>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
-    kern<<<um.chunk * kNumXcd, W * 64, Cfg::kLdsBytes, stream>>>(
-        (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (const __bf16*)dout, lse2, delta,
-        (__bf16*)dq, segs, um, total, n_heads, scale, scale * kLog2eB);
-    return hipGetLastError();
+    return launch(kern, dim3(um.chunk * kNumXcd), dim3(W * 64), Cfg::kLdsBytes, stream, qb, kb, vb, dob, lse2,
+                  delta, (__bf16*)dq, segs, um, total, n_heads, scale, scale * kLog2eB);
   }
+}
+
+// Delta, lse in log2 units and the sentinels for all `total` query tokens of a call (once per
+// call, before the runs of clips).
+hipError_t launch_bwd_prepare(const void* out, const void* dout, const float* lse, float* delta, float* lse2,
+                              float* sentinel, int total, int n_heads, int head_dim, hipStream_t stream) {
+  if (total == 0) return hipSuccess;
+  const int tok_per_block = 256 / (head_dim / 8);
+  const dim3 grid((total + tok_per_block - 1) / tok_per_block);
+  if (head_dim == 128)
+    return launch(bwd_prepare_kernel<128>, grid, dim3(256), 0, stream, (const u32x4*)out, (const u32x4*)dout, lse,
+                  delta, lse2, sentinel, total, n_heads);
+  return launch(bwd_prepare_kernel<64>, grid, dim3(256), 0, stream, (const u32x4*)out, (const u32x4*)dout, lse,
+                delta, lse2, sentinel, total, n_heads);
 }
 
 template <class Segs>
@@ -1119,16 +1189,16 @@ hipError_t launch_attn_bwd(const void* q, const void* k, const void* v, const vo
                            const float* lse, const void* dout, const Segs& segs, int total,
                            int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
                            float* delta, float* lse2, float* sentinel, float* dkv32, int total_kv,
-                           hipStream_t stream) {
+                           int kv_lo, int kv_hi, hipStream_t stream) {
   if (head_dim == 128)
-    return launch_bwd_d<128>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, sentinel, dkv32, total_kv, stream);
-  return launch_bwd_d<64>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, sentinel, dkv32, total_kv, stream);
+    return launch_bwd_d<128>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, sentinel, dkv32, total_kv, kv_lo, kv_hi, stream);
+  return launch_bwd_d<64>(q, k, v, out, lse, dout, segs, total, n_heads, scale, dq, dk, dv, delta, lse2, sentinel, dkv32, total_kv, kv_lo, kv_hi, stream);
 }
 template hipError_t launch_attn_bwd<SegTable>(const void*, const void*, const void*, const void*, const float*,
                                               const void*, const SegTable&, int, int, int, float, void*, void*,
-                                              void*, float*, float*, float*, float*, int, hipStream_t);
+                                              void*, float*, float*, float*, float*, int, int, int, hipStream_t);
 template hipError_t launch_attn_bwd<XSegTable>(const void*, const void*, const void*, const void*, const float*,
                                                const void*, const XSegTable&, int, int, int, float, void*, void*,
-                                               void*, float*, float*, float*, float*, int, hipStream_t);
+                                               void*, float*, float*, float*, float*, int, int, int, hipStream_t);
 
 }  // namespace vfm

@@ -380,13 +380,11 @@ static hipError_t pack_d(const void* q, const void* k, const void* v, const Fp8C
                          int n_units, int total, int n_heads, float qs, float ks, float vs, void* q8,
                          void* k8, void* vT8, hipStream_t stream) {
   const long long chunks = (long long)total * n_heads * (D / 16);
-  fp8_pack_q_kernel<D><<<(int)((chunks + 255) / 256), 256, 0, stream>>>((const u32x4*)q, (u32x4*)q8, qs, total,
-                                                                        n_heads);
-  hipError_t e = hipGetLastError();
+  hipError_t e = launch(fp8_pack_q_kernel<D>, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, stream,
+                        (const u32x4*)q, (u32x4*)q8, qs, total, n_heads);
   if (e != hipSuccess) return e;
-  fp8_pack_kv_kernel<D><<<dim3(n_units, n_heads), 256, 0, stream>>>(
-      (const u32x4*)k, (const u32x4*)v, (u32x4*)k8, (u32x4*)vT8, ks, vs, clips, n_units, n_heads);
-  return hipGetLastError();
+  return launch(fp8_pack_kv_kernel<D>, dim3(n_units, n_heads), dim3(256), 0, stream, (const u32x4*)k,
+                (const u32x4*)v, (u32x4*)k8, (u32x4*)vT8, ks, vs, clips, n_units, n_heads);
 }
 
 hipError_t launch_fp8_pack(const void* q, const void* k, const void* v, const Fp8ClipTable& clips,
@@ -410,10 +408,9 @@ static hipError_t fwd_fp8_d(const void* q8, const void* k8, const void* vT8, con
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds);
   if (e != hipSuccess) return e;
-  kern<<<um.chunk * kNumXcd, kF8Waves * 64, lds, stream>>>(
-      (const unsigned char*)q8, (const unsigned char*)k8, (const unsigned char*)vT8, (__bf16*)out, lse,
-      segs, um, total, n_heads, n_units, out_scale);
-  return hipGetLastError();
+  return launch(kern, dim3(um.chunk * kNumXcd), dim3(kF8Waves * 64), lds, stream, (const unsigned char*)q8,
+                (const unsigned char*)k8, (const unsigned char*)vT8, (__bf16*)out, lse, segs, um, total,
+                n_heads, n_units, out_scale);
 }
 
 hipError_t launch_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const Fp8SegTable& segs,

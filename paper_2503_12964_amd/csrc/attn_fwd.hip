@@ -382,10 +382,8 @@ static hipError_t launch_fwd_cfg(const void* q, const void* k, const void* v, co
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
   if (e != hipSuccess) return e;
-  kern<<<grid, W * 64, Cfg::kLdsBytes, stream>>>(
-      (const __bf16*)q, (const __bf16*)k, (const __bf16*)v, (__bf16*)out, lse, segs, um, total,
-      n_heads, scale * kLog2e);
-  return hipGetLastError();
+  return launch(kern, dim3(grid), dim3(W * 64), Cfg::kLdsBytes, stream, (const __bf16*)q, (const __bf16*)k,
+                (const __bf16*)v, (__bf16*)out, lse, segs, um, total, n_heads, scale * kLog2e);
 }
 
 template <class Segs>
@@ -393,15 +391,7 @@ hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, const Se
                            int total, int n_heads, int head_dim, float scale, void* out,
                            float* lse, hipStream_t stream) {
   if (head_dim == 128) {
-    // Few keys per sequence (cross-attention on a text prompt, packs of images): a workgroup's
-    // loop is short against its prologue and epilogue, so 128-row workgroups are used, two of
-    // which share a CU and overlap one's loads and stores with the other's loop (0.59 -> 0.55
-    // ms for 56,320 queries x 512 keys x 32 heads; +3-5% on packs of 256- to 484-token clips).
-    // Each wavefront's arithmetic is the same.  With longer sequences the 256-row workgroup's
-    // halved K/V staging traffic wins.
-    int longest_kv = 0;
-    for (int s = 0; s < segs.n; ++s) longest_kv = max(longest_kv, segs.kv_len(s));
-    if (longest_kv <= 1024)
+    if (fwd_tile_rows(segs, head_dim) == 128)
       return launch_fwd_cfg<128, 4>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
     return launch_fwd_cfg<128, 8>(q, k, v, segs, total, n_heads, scale, out, lse, stream);
   }

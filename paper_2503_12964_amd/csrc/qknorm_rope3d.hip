@@ -53,12 +53,12 @@ template <int D>
 __global__ __launch_bounds__(256) void qknorm_rope3d_kernel(const u32x4* x, u32x4* y,
                                                             const float* __restrict__ gain, float eps,
                                                             const RopeTable tab, const RopeFreq fr,
-                                                            int total, int n_heads) {
+                                                            int tok0, int tok_end, int n_heads) {
   constexpr int kLanesPerTok = D / 8;
   constexpr int kTokPerBlock = 256 / kLanesPerTok;
-  const int tok = blockIdx.x * kTokPerBlock + threadIdx.x / kLanesPerTok;
+  const int tok = tok0 + blockIdx.x * kTokPerBlock + threadIdx.x / kLanesPerTok;   // the clips of tab
   const int chunk = threadIdx.x % kLanesPerTok;
-  if (tok >= total) return;   // whole groups leave together
+  if (tok >= tok_end) return;   // whole groups leave together
 
   float cs[4], sn[4];
   rope_cos_sin(tab, fr, tok, chunk, 0, cs, sn);
@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void qknorm_rope3d_bwd_kernel(const u32x4* __r
                                                                 const float* __restrict__ gain, float eps,
                                                                 float* __restrict__ dgain,
                                                                 const RopeTable tab, const RopeFreq fr,
-                                                                int total, int n_heads) {
+                                                                int tok0, int tok_end, int n_heads) {
   constexpr int kLanesPerTok = D / 8;
   constexpr int kTokPerBlock = 256 / kLanesPerTok;
   __shared__ float red[kTokPerBlock][D];
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void qknorm_rope3d_bwd_kernel(const u32x4* __r
   for (int e = 0; e < 8; ++e) { g[e] = gain[chunk * 8 + e]; dg[e] = 0.f; }
 
   // whole groups iterate together; nobody returns before the barrier below
-  for (int tok = blockIdx.x * kTokPerBlock + group; tok < total; tok += gridDim.x * kTokPerBlock) {
+  for (int tok = tok0 + blockIdx.x * kTokPerBlock + group; tok < tok_end; tok += gridDim.x * kTokPerBlock) {
     float cs[4], sn[4];
     rope_cos_sin(tab, fr, tok, chunk, 1, cs, sn);   // transpose rotation
     const size_t base = ((size_t)tok * n_heads) * kLanesPerTok + chunk;
@@ -179,39 +179,39 @@ __global__ __launch_bounds__(256) void qknorm_rope3d_bwd_kernel(const u32x4* __r
 }
 
 hipError_t launch_qknorm_rope3d(const void* x, void* y, const float* gain, float eps,
-                                const RopeTable& tab, int total, int n_heads, int head_dim,
+                                const RopeTable& tab, int n_heads, int head_dim,
                                 int dim_t, int dim_h, int dim_w, float theta, hipStream_t stream) {
-  if (total == 0) return hipSuccess;
+  const int tok0 = tab.cu[0], tok_end = tab.cu[tab.n], count = tok_end - tok0;
+  if (count == 0) return hipSuccess;
   const RopeFreq fr = make_rope_freq(dim_t, dim_h, dim_w, theta);
-  if (head_dim == 128) {
-    qknorm_rope3d_kernel<128><<<(total + 15) / 16, 256, 0, stream>>>(
-        (const u32x4*)x, (u32x4*)y, gain, eps, tab, fr, total, n_heads);
-  } else {
-    qknorm_rope3d_kernel<64><<<(total + 31) / 32, 256, 0, stream>>>(
-        (const u32x4*)x, (u32x4*)y, gain, eps, tab, fr, total, n_heads);
-  }
-  return hipGetLastError();
+  if (head_dim == 128)
+    return launch(qknorm_rope3d_kernel<128>, dim3((count + 15) / 16), dim3(256), 0, stream, (const u32x4*)x,
+                  (u32x4*)y, gain, eps, tab, fr, tok0, tok_end, n_heads);
+  return launch(qknorm_rope3d_kernel<64>, dim3((count + 31) / 32), dim3(256), 0, stream, (const u32x4*)x,
+                (u32x4*)y, gain, eps, tab, fr, tok0, tok_end, n_heads);
 }
 
+hipError_t launch_zero_f32(float* p, int n, hipStream_t stream) {
+  return launch(zero_f32_kernel, dim3((n + 127) / 128), dim3(128), 0, stream, p, n);
+}
+
+// dgain is accumulated into (zeroed by the caller with launch_zero_f32 before the first run of clips)
 hipError_t launch_qknorm_rope3d_bwd(const void* x, const void* dy, void* dx, const float* gain,
-                                    float eps, float* dgain, const RopeTable& tab, int total,
+                                    float eps, float* dgain, const RopeTable& tab,
                                     int n_heads, int head_dim, int dim_t, int dim_h, int dim_w,
                                     float theta, hipStream_t stream) {
-  zero_f32_kernel<<<1, 128, 0, stream>>>(dgain, head_dim);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess || total == 0) return e;
+  const int tok0 = tab.cu[0], tok_end = tab.cu[tab.n], count = tok_end - tok0;
+  if (count == 0) return hipSuccess;
   const RopeFreq fr = make_rope_freq(dim_t, dim_h, dim_w, theta);
   constexpr int kMaxGrid = 4096;   // bounds the number of atomics; more tokens loop
   if (head_dim == 128) {
-    const int grid = min((total + 15) / 16, kMaxGrid);
-    qknorm_rope3d_bwd_kernel<128><<<grid, 256, 0, stream>>>(
-        (const u32x4*)x, (const u32x4*)dy, (u32x4*)dx, gain, eps, dgain, tab, fr, total, n_heads);
-  } else {
-    const int grid = min((total + 31) / 32, kMaxGrid);
-    qknorm_rope3d_bwd_kernel<64><<<grid, 256, 0, stream>>>(
-        (const u32x4*)x, (const u32x4*)dy, (u32x4*)dx, gain, eps, dgain, tab, fr, total, n_heads);
+    const int grid = min((count + 15) / 16, kMaxGrid);
+    return launch(qknorm_rope3d_bwd_kernel<128>, dim3(grid), dim3(256), 0, stream, (const u32x4*)x,
+                  (const u32x4*)dy, (u32x4*)dx, gain, eps, dgain, tab, fr, tok0, tok_end, n_heads);
   }
-  return hipGetLastError();
+  const int grid = min((count + 31) / 32, kMaxGrid);
+  return launch(qknorm_rope3d_bwd_kernel<64>, dim3(grid), dim3(256), 0, stream, (const u32x4*)x,
+                (const u32x4*)dy, (u32x4*)dx, gain, eps, dgain, tab, fr, tok0, tok_end, n_heads);
 }
 
 }  // namespace vfm

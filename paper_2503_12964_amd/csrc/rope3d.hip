@@ -12,13 +12,15 @@ namespace vfm {
 
 template <int D>
 __global__ __launch_bounds__(256) void rope3d_kernel(u32x4* __restrict__ x, const RopeTable tab,
-                                                     const RopeFreq fr, int total, int n_heads,
-                                                     int inverse) {
+                                                     const RopeFreq fr, int tok0, int tok_end,
+                                                     int n_heads, int inverse) {
+  // tokens [tok0, tok_end): the clips of tab (a call with more clips than a table holds is cut
+  // into consecutive launches over runs of clips)
   constexpr int kLanesPerTok = D / 8;
   constexpr int kTokPerBlock = 256 / kLanesPerTok;
-  const int tok = blockIdx.x * kTokPerBlock + threadIdx.x / kLanesPerTok;
+  const int tok = tok0 + blockIdx.x * kTokPerBlock + threadIdx.x / kLanesPerTok;
   const int chunk = threadIdx.x % kLanesPerTok;
-  if (tok >= total) return;
+  if (tok >= tok_end) return;
 
   float cs[4], sn[4];
   rope_cos_sin(tab, fr, tok, chunk, inverse, cs, sn);
@@ -61,19 +63,17 @@ __global__ __launch_bounds__(256) void rope3d_kernel(u32x4* __restrict__ x, cons
   }
 }
 
-hipError_t launch_rope3d(void* x, const RopeTable& tab, int total, int n_heads, int head_dim,
+hipError_t launch_rope3d(void* x, const RopeTable& tab, int n_heads, int head_dim,
                          int dim_t, int dim_h, int dim_w, float theta, int inverse,
                          hipStream_t stream) {
   const RopeFreq fr = make_rope_freq(dim_t, dim_h, dim_w, theta);
-  if (total == 0) return hipSuccess;
-  if (head_dim == 128) {
-    const int grid = (total + 15) / 16;
-    rope3d_kernel<128><<<grid, 256, 0, stream>>>((u32x4*)x, tab, fr, total, n_heads, inverse);
-  } else {
-    const int grid = (total + 31) / 32;
-    rope3d_kernel<64><<<grid, 256, 0, stream>>>((u32x4*)x, tab, fr, total, n_heads, inverse);
-  }
-  return hipGetLastError();
+  const int tok0 = tab.cu[0], tok_end = tab.cu[tab.n], count = tok_end - tok0;
+  if (count == 0) return hipSuccess;
+  if (head_dim == 128)
+    return launch(rope3d_kernel<128>, dim3((count + 15) / 16), dim3(256), 0, stream, (u32x4*)x, tab, fr, tok0,
+                  tok_end, n_heads, inverse);
+  return launch(rope3d_kernel<64>, dim3((count + 31) / 32), dim3(256), 0, stream, (u32x4*)x, tab, fr, tok0,
+                tok_end, n_heads, inverse);
 }
 
 }  // namespace vfm

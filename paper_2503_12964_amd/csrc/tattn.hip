@@ -533,18 +533,17 @@ static hipError_t launch_t(const void* q, const void* k, const void* v, const vo
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
-    kern<<<grid, kTWaves * 64, lds, stream>>>((const __bf16*)q, (const __bf16*)k, (const __bf16*)v,
-                                              (__bf16*)o0, tab, n_heads, scale * kLog2eT);
+    return launch(kern, dim3(grid), dim3(kTWaves * 64), lds, stream, (const __bf16*)q, (const __bf16*)k,
+                  (const __bf16*)v, (__bf16*)o0, tab, n_heads, scale * kLog2eT);
   } else {
     auto kern = big ? tattn32_bwd_kernel<D> : tattn_bwd_kernel<D>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
-    kern<<<grid, kTWaves * 64, lds, stream>>>((const __bf16*)q, (const __bf16*)k, (const __bf16*)v,
-                                              (const __bf16*)dout, (__bf16*)o0, (__bf16*)o1, (__bf16*)o2,
-                                              tab, n_heads, scale, scale * kLog2eT);
+    return launch(kern, dim3(grid), dim3(kTWaves * 64), lds, stream, (const __bf16*)q, (const __bf16*)k,
+                  (const __bf16*)v, (const __bf16*)dout, (__bf16*)o0, (__bf16*)o1, (__bf16*)o2, tab, n_heads,
+                  scale, scale * kLog2eT);
   }
-  return hipGetLastError();
 }
 
 hipError_t launch_tattn_fwd(const void* q, const void* k, const void* v, const TemporalTable& tab,

@@ -16,8 +16,9 @@ using vfm::XSegTable;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-int check_shape(int n_seqs, int total_tokens, int n_heads, int head_dim) {
-  if (n_seqs < 0 || n_seqs > VFM_MAX_SEQS || total_tokens < 0 || n_heads < 1 || n_heads > 65535)
+// max_seqs < 0: any number of clips (the call is cut into runs, see below)
+int check_shape(int n_seqs, int total_tokens, int n_heads, int head_dim, int max_seqs = -1) {
+  if (n_seqs < 0 || (max_seqs >= 0 && n_seqs > max_seqs) || total_tokens < 0 || n_heads < 1 || n_heads > 65535)
     return VFM_ERR_SHAPE;
   if (head_dim != 64 && head_dim != 128) return VFM_ERR_SHAPE;
   // the direct-to-LDS loads address a tensor with 32-bit byte offsets
@@ -32,6 +33,14 @@ int check_cu(const int32_t* cu, int n_seqs, int total_tokens) {
   if (cu[n_seqs] != total_tokens) return VFM_ERR_CU_SEQLENS;
   return VFM_OK;
 }
+
+// Runs.  The clip tables travel to the kernels by value, in kernel-argument memory, and hold
+// VFM_MAX_SEQS clips (VFM_MAX_XSEQS cross-attention sequences).  A call with more clips is cut
+// into consecutive launches on the caller's stream over runs of at most that many clips in
+// packed order: clips are independent of each other, a run's tokens are one contiguous
+// range, and every output row belongs to exactly one run.  The builders below therefore take
+// a pointer to the run's first boundary (values stay absolute packed positions) and the
+// run's number of clips.
 
 // Non-empty clips, longest first (ties keep packed order): the tile scheduler
 // hands out the most expensive tiles first.
@@ -51,16 +60,21 @@ void build_seg_table(const int32_t* cu, int n_seqs, SegTable* t) {
   for (int i = n; i < VFM_MAX_SEQS; ++i) { t->start[i] = 0; t->len[i] = 0; }
 }
 
-// Cross-attention sequences, most (query x key) pairs first.  Sequences with neither queries
-// nor keys are dropped; one with queries and no keys is an error.
-int build_xseg_table(const int32_t* cu_q, const int32_t* cu_kv, int n_seqs, XSegTable* t) {
+// Cross-attention: a sequence with queries needs at least one key (checked over the whole call
+// before anything is launched).
+int check_xseqs(const int32_t* cu_q, const int32_t* cu_kv, int n_seqs) {
+  for (int s = 0; s < n_seqs; ++s)
+    if (cu_q[s + 1] > cu_q[s] && cu_kv[s + 1] == cu_kv[s]) return VFM_ERR_CU_SEQLENS;
+  return VFM_OK;
+}
+
+// Cross-attention sequences of one run, most (query x key) pairs first.  Sequences with neither
+// queries nor keys are dropped.
+void build_xseg_table(const int32_t* cu_q, const int32_t* cu_kv, int n_seqs, XSegTable* t) {
   int order[VFM_MAX_XSEQS];
   int n = 0;
-  for (int s = 0; s < n_seqs; ++s) {
-    const int nq = cu_q[s + 1] - cu_q[s], nk = cu_kv[s + 1] - cu_kv[s];
-    if (nq > 0 && nk == 0) return VFM_ERR_CU_SEQLENS;
-    if (nq > 0 || nk > 0) order[n++] = s;
-  }
+  for (int s = 0; s < n_seqs; ++s)
+    if (cu_q[s + 1] > cu_q[s] || cu_kv[s + 1] > cu_kv[s]) order[n++] = s;
   auto pairs = [&](int s) { return (long long)(cu_q[s + 1] - cu_q[s]) * (cu_kv[s + 1] - cu_kv[s]); };
   std::stable_sort(order, order + n, [&](int a, int b) { return pairs(a) > pairs(b); });
   t->n = n;
@@ -71,31 +85,38 @@ int build_xseg_table(const int32_t* cu_q, const int32_t* cu_kv, int n_seqs, XSeg
     t->ks[i] = live ? cu_kv[order[i]] : 0;
     t->kl[i] = live ? cu_kv[order[i] + 1] - cu_kv[order[i]] : 0;
   }
-  return VFM_OK;
 }
 
-// Temporal attention: per-clip grids must match the clip lengths and have at most
-// VFM_MAX_TEMPORAL frames.
-int build_temporal_table(const int32_t* thw, const int32_t* cu, int n_seqs, int total,
-                         vfm::TemporalTable* t) {
-  t->n = n_seqs;
-  int pix = 0;
+// Per-clip grids must match the clip lengths (an empty clip may have any grid with a zero
+// extent); max_frames > 0 also bounds T (temporal attention).
+int check_grids(const int32_t* thw, const int32_t* cu, int n_seqs, int max_frames) {
   for (int s = 0; s < n_seqs; ++s) {
     const long long T = thw[3 * s], H = thw[3 * s + 1], W = thw[3 * s + 2];
     const int len = cu[s + 1] - cu[s];
+    if (len == 0 && T * H * W == 0 && T >= 0 && H >= 0 && W >= 0) continue;
+    if (T <= 0 || H <= 0 || W <= 0 || T * H * W != len) return VFM_ERR_THW;
+    if (max_frames > 0 && T > max_frames) return VFM_ERR_THW;
+  }
+  return VFM_OK;
+}
+
+// Temporal attention, one run of (validated) clips: packed token offsets and pixel offsets
+// counted from the run's first clip.
+void build_temporal_table(const int32_t* thw, const int32_t* cu, int n_seqs, vfm::TemporalTable* t) {
+  t->n = n_seqs;
+  int pix = 0;
+  for (int s = 0; s < n_seqs; ++s) {
+    const int len = cu[s + 1] - cu[s];
     t->cu[s] = cu[s];
     t->pix_cu[s] = pix;
-    if (len == 0 && T * H * W == 0 && T >= 0 && H >= 0 && W >= 0) { t->hw[s] = 1; continue; }
-    if (T <= 0 || H <= 0 || W <= 0 || T * H * W != len || T > VFM_MAX_TEMPORAL) return VFM_ERR_THW;
-    t->hw[s] = (int)(H * W);
-    pix += (int)(H * W);
+    t->hw[s] = len == 0 ? 1 : thw[3 * s + 1] * thw[3 * s + 2];
+    if (len) pix += t->hw[s];
   }
   for (int s = n_seqs; s <= VFM_MAX_SEQS; ++s) {
-    t->cu[s] = total;
+    t->cu[s] = cu[n_seqs];
     t->pix_cu[s] = pix;
     if (s < VFM_MAX_SEQS) t->hw[s] = 1;
   }
-  return VFM_OK;
 }
 
 constexpr int kFp8Unit = 64;   // keys per packed unit of the FP8 path
@@ -129,11 +150,10 @@ int build_fp8_tables(const int32_t* cu, int n_seqs, int total, vfm::Fp8ClipTable
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Shared by the RoPE entry points: sizes, split, theta, cu_seqlens and the per-clip grids;
-// fills the clip table the kernels take by value.
+// Shared by the RoPE entry points: sizes, split, theta, cu_seqlens and the per-clip grids.
 int check_rope_args(const int32_t* thw, const int32_t* cu_seqlens, int n_seqs, int total_tokens,
                     int n_heads, int head_dim, int dim_t, int dim_h, int dim_w, float theta,
-                    vfm_dtype dt, RopeTable* tab) {
+                    vfm_dtype dt) {
   if (dt != VFM_BF16) return VFM_ERR_DTYPE;
   int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
   if (st) return st;
@@ -143,33 +163,27 @@ int check_rope_args(const int32_t* thw, const int32_t* cu_seqlens, int n_seqs, i
     return VFM_ERR_SPLIT;
   st = check_cu(cu_seqlens, n_seqs, total_tokens);
   if (st) return st;
+  return check_grids(thw, cu_seqlens, n_seqs, 0);
+}
+
+// The clip table the RoPE kernels take by value, for one run of (validated) clips.
+void build_rope_table(const int32_t* thw, const int32_t* cu, int n_seqs, RopeTable* tab) {
   tab->n = n_seqs;
   for (int s = 0; s < n_seqs; ++s) {
-    const long long T = thw[3 * s], H = thw[3 * s + 1], W = thw[3 * s + 2];
-    const int len = cu_seqlens[s + 1] - cu_seqlens[s];
-    tab->cu[s] = cu_seqlens[s];
-    if (len == 0 && T * H * W == 0 && T >= 0 && H >= 0 && W >= 0) {  // empty clip
-      tab->hw[s] = 1; tab->w[s] = 1;
-      continue;
-    }
-    if (T <= 0 || H <= 0 || W <= 0 || T * H * W != len) return VFM_ERR_THW;
-    tab->hw[s] = (int)(H * W);
-    tab->w[s] = (int)W;
+    const bool empty = cu[s + 1] == cu[s];
+    tab->cu[s] = cu[s];
+    tab->hw[s] = empty ? 1 : thw[3 * s + 1] * thw[3 * s + 2];
+    tab->w[s] = empty ? 1 : thw[3 * s + 2];
   }
-  tab->cu[n_seqs] = total_tokens;
-  for (int s = n_seqs; s < VFM_MAX_SEQS; ++s) { tab->cu[s + 1] = total_tokens; tab->hw[s] = 1; tab->w[s] = 1; }
-  return VFM_OK;
+  tab->cu[n_seqs] = cu[n_seqs];
+  for (int s = n_seqs; s < VFM_MAX_SEQS; ++s) { tab->cu[s + 1] = cu[n_seqs]; tab->hw[s] = 1; tab->w[s] = 1; }
 }
 
 // The HIP error behind this thread's most recent VFM_ERR_LAUNCH.
 thread_local hipError_t g_last_hip_error = hipSuccess;
 
-// hipGetLastError() reports the last error of ANY earlier runtime call of the thread, including
-// harmless ones of other libraries (a "not ready" from polling an event, a failed pointer
-// query on pageable host memory).  Such leftovers are dropped before the library launches, so
-// that what is read after the launches is the launches' own.
-inline void forget_foreign_errors() { (void)hipGetLastError(); }
-
+// Launches go through hipLaunchKernel, which returns each launch's own status: the thread's
+// pending error state (which may hold another library's leftover) is neither read nor cleared.
 inline int launch_status(hipError_t e) {
   if (e == hipSuccess) return VFM_OK;
   g_last_hip_error = e;
@@ -223,7 +237,7 @@ const char* vfm_strerror(int status) {
   switch (status) {
     case VFM_OK: return "ok";
     case VFM_ERR_NULL: return "a required pointer is NULL";
-    case VFM_ERR_SHAPE: return "total_tokens, n_heads, head_dim (64 or 128), n_seqs (<= 256), scale or theta (> 0, finite) or eps (>= 0) out of range, or dx aliases x";
+    case VFM_ERR_SHAPE: return "total_tokens, n_heads, head_dim (64 or 128), n_seqs (FP8 entry points: <= 256), a tensor beyond 4 GiB, scale or theta (> 0, finite) or eps (>= 0) out of range, or dx aliases x";
     case VFM_ERR_CU_SEQLENS: return "cu_seqlens must start at 0, be non-decreasing and end at total_tokens";
     case VFM_ERR_THW: return "each clip needs positive T, H, W with T*H*W equal to its length (temporal attention: T <= 32)";
     case VFM_ERR_SPLIT: return "dim_t + dim_h + dim_w must equal head_dim, each part even and >= 0";
@@ -240,16 +254,18 @@ int vfm_rope3d(void* x, const int32_t* thw, const int32_t* cu_seqlens, int n_seq
                int total_tokens, int n_heads, int head_dim, int dim_t, int dim_h, int dim_w,
                float theta, int inverse, vfm_dtype dt, void* hip_stream) {
   if (!x || !thw || !cu_seqlens) return VFM_ERR_NULL;
-  RopeTable tab;
   int st = check_rope_args(thw, cu_seqlens, n_seqs, total_tokens, n_heads, head_dim, dim_t, dim_h,
-                           dim_w, theta, dt, &tab);
+                           dim_w, theta, dt);
   if (st) return st;
   if (!aligned16(x)) return VFM_ERR_ALIGN;
-  if (total_tokens == 0) return VFM_OK;
-  forget_foreign_errors();
-  hipError_t e = vfm::launch_rope3d(x, tab, total_tokens, n_heads, head_dim, dim_t, dim_h, dim_w,
-                                    theta, inverse, static_cast<hipStream_t>(hip_stream));
-  return launch_status(e);
+  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_SEQS) {
+    RopeTable tab;
+    build_rope_table(thw + 3 * s0, cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), &tab);
+    hipError_t e = vfm::launch_rope3d(x, tab, n_heads, head_dim, dim_t, dim_h, dim_w, theta, inverse,
+                                      static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return launch_status(e);
+  }
+  return VFM_OK;
 }
 
 int vfm_qknorm_rope3d(const void* x, const float* gain, float eps, void* y, const int32_t* thw,
@@ -257,18 +273,19 @@ int vfm_qknorm_rope3d(const void* x, const float* gain, float eps, void* y, cons
                       int head_dim, int dim_t, int dim_h, int dim_w, float theta, vfm_dtype dt,
                       void* hip_stream) {
   if (!x || !gain || !y || !thw || !cu_seqlens) return VFM_ERR_NULL;
-  RopeTable tab;
   int st = check_rope_args(thw, cu_seqlens, n_seqs, total_tokens, n_heads, head_dim, dim_t, dim_h,
-                           dim_w, theta, dt, &tab);
+                           dim_w, theta, dt);
   if (st) return st;
   if (!(eps >= 0.f) || !isfinite(eps)) return VFM_ERR_SHAPE;
   if (!aligned16(x) || !aligned16(y) || (reinterpret_cast<uintptr_t>(gain) & 3u)) return VFM_ERR_ALIGN;
-  if (total_tokens == 0) return VFM_OK;
-  forget_foreign_errors();
-  hipError_t e = vfm::launch_qknorm_rope3d(x, y, gain, eps, tab, total_tokens, n_heads, head_dim,
-                                           dim_t, dim_h, dim_w, theta,
-                                           static_cast<hipStream_t>(hip_stream));
-  return launch_status(e);
+  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_SEQS) {
+    RopeTable tab;
+    build_rope_table(thw + 3 * s0, cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), &tab);
+    hipError_t e = vfm::launch_qknorm_rope3d(x, y, gain, eps, tab, n_heads, head_dim, dim_t, dim_h, dim_w,
+                                             theta, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return launch_status(e);
+  }
+  return VFM_OK;
 }
 
 int vfm_qknorm_rope3d_bwd(const void* x, const float* gain, float eps, const void* dy, void* dx,
@@ -276,20 +293,25 @@ int vfm_qknorm_rope3d_bwd(const void* x, const float* gain, float eps, const voi
                           int total_tokens, int n_heads, int head_dim, int dim_t, int dim_h,
                           int dim_w, float theta, vfm_dtype dt, void* hip_stream) {
   if (!x || !gain || !dy || !dx || !dgain || !thw || !cu_seqlens) return VFM_ERR_NULL;
-  RopeTable tab;
   int st = check_rope_args(thw, cu_seqlens, n_seqs, total_tokens, n_heads, head_dim, dim_t, dim_h,
-                           dim_w, theta, dt, &tab);
+                           dim_w, theta, dt);
   if (st) return st;
   if (!(eps >= 0.f) || !isfinite(eps)) return VFM_ERR_SHAPE;
   if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) ||
       ((reinterpret_cast<uintptr_t>(gain) | reinterpret_cast<uintptr_t>(dgain)) & 3u))
     return VFM_ERR_ALIGN;
   if (dx == x) return VFM_ERR_SHAPE;   // dx may overwrite dy, never x
-  forget_foreign_errors();
-  hipError_t e = vfm::launch_qknorm_rope3d_bwd(x, dy, dx, gain, eps, dgain, tab, total_tokens,
-                                               n_heads, head_dim, dim_t, dim_h, dim_w, theta,
-                                               static_cast<hipStream_t>(hip_stream));
-  return launch_status(e);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = vfm::launch_zero_f32(dgain, head_dim, stream);   // every run adds its share to dgain
+  if (e != hipSuccess) return launch_status(e);
+  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_SEQS) {
+    RopeTable tab;
+    build_rope_table(thw + 3 * s0, cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), &tab);
+    e = vfm::launch_qknorm_rope3d_bwd(x, dy, dx, gain, eps, dgain, tab, n_heads, head_dim, dim_t, dim_h,
+                                      dim_w, theta, stream);
+    if (e != hipSuccess) return launch_status(e);
+  }
+  return VFM_OK;
 }
 
 int vfm_attn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_seqlens,
@@ -304,44 +326,69 @@ int vfm_attn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_
   if (st) return st;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
     return VFM_ERR_ALIGN;
-  if (total_tokens == 0) return VFM_OK;
-  SegTable segs;
-  build_seg_table(cu_seqlens, n_seqs, &segs);
-  forget_foreign_errors();
-  hipError_t e = vfm::launch_attn_fwd(q, k, v, segs, total_tokens, n_heads, head_dim, scale, out,
-                                      lse, static_cast<hipStream_t>(hip_stream));
-  return launch_status(e);
+  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_SEQS) {
+    SegTable segs;
+    build_seg_table(cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), &segs);
+    hipError_t e = vfm::launch_attn_fwd(q, k, v, segs, total_tokens, n_heads, head_dim, scale, out, lse,
+                                        static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return launch_status(e);
+  }
+  return VFM_OK;
 }
 
 int vfm_schedule_units(const int32_t* cu_seqlens, int n_seqs, int total_tokens, int n_heads,
                        int rows_per_tile, int32_t* units, int capacity, int* n_blocks) {
   if (!cu_seqlens || !n_blocks || (!units && capacity > 0)) return VFM_ERR_NULL;
-  if (n_seqs < 0 || n_seqs > VFM_MAX_SEQS || total_tokens < 0 || n_heads < 1 || n_heads > 65535 ||
-      rows_per_tile < 1 || capacity < 0)
+  if (n_seqs < 0 || total_tokens < 0 || n_heads < 1 || n_heads > 65535 || rows_per_tile < 1 || capacity < 0)
+    return VFM_ERR_SHAPE;
+  if (int st = check_cu(cu_seqlens, n_seqs, total_tokens)) return st;
+  // exactly what the launchers and kernels do, run after run: count the tiles, build the unit
+  // map, and ask the kernels' own mapping which unit each workgroup of the grid takes
+  for (int pass = 0; pass < 2; ++pass) {
+    int at = 0;
+    for (int s0 = 0; s0 < n_seqs || s0 == 0; s0 += VFM_MAX_SEQS) {
+      SegTable segs;
+      build_seg_table(cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), &segs);
+      const vfm::UnitMap um = vfm::make_unit_map(vfm::count_tiles<false>(segs, rows_per_tile), n_heads);
+      const int grid = um.chunk * vfm::kNumXcd;
+      if (pass == 1)
+        for (int b = 0; b < grid; ++b) {
+          int32_t* u = units + 3 * (at + b);
+          int head, tile;
+          if (!vfm::map_unit(um, b, head, tile)) {
+            u[0] = -1;
+            u[1] = u[2] = 0;
+            continue;
+          }
+          int s, t;
+          vfm::locate_tile<false>(segs, rows_per_tile, tile, s, t);
+          const int first = segs.q_start(s) + t * rows_per_tile;
+          u[0] = head;
+          u[1] = first;
+          u[2] = std::min(rows_per_tile, segs.q_start(s) + segs.q_len(s) - first);
+        }
+      at += grid;
+      if (n_seqs == 0) break;
+    }
+    if (pass == 0) {
+      *n_blocks = at;
+      if (at > capacity) return VFM_ERR_SHAPE;
+    }
+  }
+  return VFM_OK;
+}
+
+int vfm_attn_fwd_tile_rows(const int32_t* cu_seqlens, int n_seqs, int total_tokens, int head_dim,
+                           int run, int* rows_per_tile) {
+  if (!cu_seqlens || !rows_per_tile) return VFM_ERR_NULL;
+  const int n_runs = n_seqs <= 0 ? 1 : (n_seqs + VFM_MAX_SEQS - 1) / VFM_MAX_SEQS;
+  if (n_seqs < 0 || total_tokens < 0 || (head_dim != 64 && head_dim != 128) || run < 0 || run >= n_runs)
     return VFM_ERR_SHAPE;
   if (int st = check_cu(cu_seqlens, n_seqs, total_tokens)) return st;
   SegTable segs;
-  build_seg_table(cu_seqlens, n_seqs, &segs);
-  // exactly what the launchers and kernels do: count the tiles, build the unit map, and ask
-  // the kernels' own mapping which unit each workgroup of the grid takes
-  const vfm::UnitMap um = vfm::make_unit_map(vfm::count_tiles<false>(segs, rows_per_tile), n_heads);
-  const int grid = um.chunk * vfm::kNumXcd;
-  *n_blocks = grid;
-  if (grid > capacity) return VFM_ERR_SHAPE;
-  for (int b = 0; b < grid; ++b) {
-    int head, tile;
-    if (!vfm::map_unit(um, b, head, tile)) {
-      units[3 * b] = -1;
-      units[3 * b + 1] = units[3 * b + 2] = 0;
-      continue;
-    }
-    int s, t;
-    vfm::locate_tile<false>(segs, rows_per_tile, tile, s, t);
-    const int first = segs.q_start(s) + t * rows_per_tile;
-    units[3 * b] = head;
-    units[3 * b + 1] = first;
-    units[3 * b + 2] = std::min(rows_per_tile, segs.q_start(s) + segs.q_len(s) - first);
-  }
+  const int s0 = run * VFM_MAX_SEQS;
+  build_seg_table(cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), &segs);
+  *rows_per_tile = vfm::fwd_tile_rows(segs, head_dim);
   return VFM_OK;
 }
 
@@ -358,10 +405,29 @@ size_t vfm_xattn_bwd_workspace_size(int total_q, int total_kv, int n_heads, int 
   return stats + align_up((size_t)2 * total_kv * n_heads * head_dim * sizeof(float), 256);
 }
 
-int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
-                 const void* dout, const int32_t* cu_seqlens, int n_seqs, int total_tokens,
-                 int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
-                 void* workspace, size_t workspace_bytes, vfm_dtype dt, void* hip_stream) {
+namespace {
+
+// Both self-attention backward entry points, once their statistics buffers are known.
+int attn_bwd_common(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                    const void* dout, const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                    int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv, float* delta,
+                    float* lse2, float* sentinel, hipStream_t stream) {
+  hipError_t e = vfm::launch_bwd_prepare(out, dout, lse, delta, lse2, sentinel, total_tokens, n_heads,
+                                         head_dim, stream);
+  if (e != hipSuccess) return launch_status(e);
+  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_SEQS) {
+    SegTable segs;
+    build_seg_table(cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), &segs);
+    e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_tokens, n_heads, head_dim, scale, dq, dk,
+                             dv, delta, lse2, sentinel, nullptr, 0, 0, 0, stream);
+    if (e != hipSuccess) return launch_status(e);
+  }
+  return VFM_OK;
+}
+
+int check_attn_bwd_args(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                        const void* dout, const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                        int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv, vfm_dtype dt) {
   if (!q || !k || !v || !out || !lse || !dout || !cu_seqlens || !dq || !dk || !dv)
     return VFM_ERR_NULL;
   if (dt != VFM_BF16) return VFM_ERR_DTYPE;
@@ -373,6 +439,18 @@ int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, c
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse) ||
       !aligned16(dout) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
     return VFM_ERR_ALIGN;
+  return VFM_OK;
+}
+
+}  // namespace
+
+int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
+                 const void* dout, const int32_t* cu_seqlens, int n_seqs, int total_tokens,
+                 int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
+                 void* workspace, size_t workspace_bytes, vfm_dtype dt, void* hip_stream) {
+  int st = check_attn_bwd_args(q, k, v, out, lse, dout, cu_seqlens, n_seqs, total_tokens, n_heads, head_dim,
+                               scale, dq, dk, dv, dt);
+  if (st) return st;
   if (total_tokens == 0) return VFM_OK;
   const size_t need = vfm_attn_bwd_workspace_size(total_tokens, n_heads, head_dim);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
@@ -381,30 +459,17 @@ int vfm_attn_bwd(const void* q, const void* k, const void* v, const void* out, c
   const size_t part = (need - 256) / 2;
   float* lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + part);
   float* sentinel = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * part);
-  SegTable segs;
-  build_seg_table(cu_seqlens, n_seqs, &segs);
-  forget_foreign_errors();
-  hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_tokens, n_heads,
-                                      head_dim, scale, dq, dk, dv, delta, lse2, sentinel, nullptr, 0,
-                                      static_cast<hipStream_t>(hip_stream));
-  return launch_status(e);
+  return attn_bwd_common(q, k, v, out, lse, dout, cu_seqlens, n_seqs, total_tokens, n_heads, head_dim, scale,
+                         dq, dk, dv, delta, lse2, sentinel, static_cast<hipStream_t>(hip_stream));
 }
 
 int vfm_attn_bwd_noalloc(const void* q, const void* k, const void* v, const void* out,
                          const float* lse, const void* dout, const int32_t* cu_seqlens, int n_seqs,
                          int total_tokens, int n_heads, int head_dim, float scale, void* dq, void* dk,
                          void* dv, vfm_dtype dt, void* hip_stream) {
-  if (!q || !k || !v || !out || !lse || !dout || !cu_seqlens || !dq || !dk || !dv)
-    return VFM_ERR_NULL;
-  if (dt != VFM_BF16) return VFM_ERR_DTYPE;
-  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  int st = check_attn_bwd_args(q, k, v, out, lse, dout, cu_seqlens, n_seqs, total_tokens, n_heads, head_dim,
+                               scale, dq, dk, dv, dt);
   if (st) return st;
-  if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
-  st = check_cu(cu_seqlens, n_seqs, total_tokens);
-  if (st) return st;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse) ||
-      !aligned16(dout) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
-    return VFM_ERR_ALIGN;
   if ((size_t)total_tokens * (size_t)n_heads > kNoallocRows) return VFM_ERR_SCRATCH;
   if (total_tokens == 0) return VFM_OK;
   void* base = nullptr;
@@ -414,13 +479,8 @@ int vfm_attn_bwd_noalloc(const void* q, const void* k, const void* v, const void
   float* delta = static_cast<float*>(base);
   float* lse2 = reinterpret_cast<float*>(static_cast<char*>(base) + kNoallocPart);
   float* sentinel = reinterpret_cast<float*>(static_cast<char*>(base) + 2 * kNoallocPart);
-  SegTable segs;
-  build_seg_table(cu_seqlens, n_seqs, &segs);
-  forget_foreign_errors();
-  e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_tokens, n_heads, head_dim, scale, dq,
-                           dk, dv, delta, lse2, sentinel, nullptr, 0,
-                           static_cast<hipStream_t>(hip_stream));
-  return launch_status(e);
+  return attn_bwd_common(q, k, v, out, lse, dout, cu_seqlens, n_seqs, total_tokens, n_heads, head_dim, scale,
+                         dq, dk, dv, delta, lse2, sentinel, static_cast<hipStream_t>(hip_stream));
 }
 
 int vfm_xattn_fwd(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_q,
@@ -428,24 +488,24 @@ int vfm_xattn_fwd(const void* q, const void* k, const void* v, const int32_t* cu
                   int head_dim, float scale, void* out, float* lse, vfm_dtype dt, void* hip_stream) {
   if (!q || !k || !v || !cu_seqlens_q || !cu_seqlens_kv || !out || !lse) return VFM_ERR_NULL;
   if (dt != VFM_BF16) return VFM_ERR_DTYPE;
-  if (n_seqs > VFM_MAX_XSEQS) return VFM_ERR_SHAPE;
   int st = check_shape(n_seqs, total_q, n_heads, head_dim);
   if (!st) st = check_shape(n_seqs, total_kv, n_heads, head_dim);
   if (st) return st;
   if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
   st = check_cu(cu_seqlens_q, n_seqs, total_q);
   if (!st) st = check_cu(cu_seqlens_kv, n_seqs, total_kv);
-  if (st) return st;
-  XSegTable segs;
-  st = build_xseg_table(cu_seqlens_q, cu_seqlens_kv, n_seqs, &segs);
+  if (!st) st = check_xseqs(cu_seqlens_q, cu_seqlens_kv, n_seqs);
   if (st) return st;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse))
     return VFM_ERR_ALIGN;
-  if (total_q == 0) return VFM_OK;
-  forget_foreign_errors();
-  hipError_t e = vfm::launch_attn_fwd(q, k, v, segs, total_q, n_heads, head_dim, scale, out, lse,
-                                      static_cast<hipStream_t>(hip_stream));
-  return launch_status(e);
+  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_XSEQS) {
+    XSegTable segs;
+    build_xseg_table(cu_seqlens_q + s0, cu_seqlens_kv + s0, std::min(VFM_MAX_XSEQS, n_seqs - s0), &segs);
+    hipError_t e = vfm::launch_attn_fwd(q, k, v, segs, total_q, n_heads, head_dim, scale, out, lse,
+                                        static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return launch_status(e);
+  }
+  return VFM_OK;
 }
 
 int vfm_xattn_bwd(const void* q, const void* k, const void* v, const void* out, const float* lse,
@@ -456,16 +516,13 @@ int vfm_xattn_bwd(const void* q, const void* k, const void* v, const void* out, 
   if (!q || !k || !v || !out || !lse || !dout || !cu_seqlens_q || !cu_seqlens_kv || !dq || !dk || !dv)
     return VFM_ERR_NULL;
   if (dt != VFM_BF16) return VFM_ERR_DTYPE;
-  if (n_seqs > VFM_MAX_XSEQS) return VFM_ERR_SHAPE;
   int st = check_shape(n_seqs, total_q, n_heads, head_dim);
   if (!st) st = check_shape(n_seqs, total_kv, n_heads, head_dim);
   if (st) return st;
   if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
   st = check_cu(cu_seqlens_q, n_seqs, total_q);
   if (!st) st = check_cu(cu_seqlens_kv, n_seqs, total_kv);
-  if (st) return st;
-  XSegTable segs;
-  st = build_xseg_table(cu_seqlens_q, cu_seqlens_kv, n_seqs, &segs);
+  if (!st) st = check_xseqs(cu_seqlens_q, cu_seqlens_kv, n_seqs);
   if (st) return st;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(lse) ||
       !aligned16(dout) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
@@ -480,11 +537,19 @@ int vfm_xattn_bwd(const void* q, const void* k, const void* v, const void* out, 
   float* lse2 = reinterpret_cast<float*>(static_cast<char*>(workspace) + part);
   float* sentinel = reinterpret_cast<float*>(static_cast<char*>(workspace) + 2 * part);
   float* dkv32 = reinterpret_cast<float*>(static_cast<char*>(workspace) + stats);
-  forget_foreign_errors();
-  hipError_t e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_q, n_heads, head_dim,
-                                      scale, dq, dk, dv, delta, lse2, sentinel, dkv32, total_kv,
-                                      static_cast<hipStream_t>(hip_stream));
-  return launch_status(e);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = vfm::launch_bwd_prepare(out, dout, lse, delta, lse2, sentinel, total_q, n_heads, head_dim, stream);
+  if (e != hipSuccess) return launch_status(e);
+  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_XSEQS) {
+    const int n = std::min(VFM_MAX_XSEQS, n_seqs - s0);
+    XSegTable segs;
+    build_xseg_table(cu_seqlens_q + s0, cu_seqlens_kv + s0, n, &segs);
+    e = vfm::launch_attn_bwd(q, k, v, out, lse, dout, segs, total_q, n_heads, head_dim, scale, dq, dk, dv,
+                             delta, lse2, sentinel, dkv32, total_kv, cu_seqlens_kv[s0], cu_seqlens_kv[s0 + n],
+                             stream);
+    if (e != hipSuccess) return launch_status(e);
+  }
+  return VFM_OK;
 }
 
 int vfm_tattn_fwd(const void* q, const void* k, const void* v, const int32_t* thw,
@@ -496,16 +561,17 @@ int vfm_tattn_fwd(const void* q, const void* k, const void* v, const int32_t* th
   if (st) return st;
   if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
   st = check_cu(cu_seqlens, n_seqs, total_tokens);
-  if (st) return st;
-  vfm::TemporalTable tab;
-  st = build_temporal_table(thw, cu_seqlens, n_seqs, total_tokens, &tab);
+  if (!st) st = check_grids(thw, cu_seqlens, n_seqs, VFM_MAX_TEMPORAL);
   if (st) return st;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return VFM_ERR_ALIGN;
-  if (total_tokens == 0) return VFM_OK;
-  forget_foreign_errors();
-  hipError_t e = vfm::launch_tattn_fwd(q, k, v, tab, n_heads, head_dim, scale, out,
-                                       static_cast<hipStream_t>(hip_stream));
-  return launch_status(e);
+  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_SEQS) {
+    vfm::TemporalTable tab;
+    build_temporal_table(thw + 3 * s0, cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), &tab);
+    hipError_t e = vfm::launch_tattn_fwd(q, k, v, tab, n_heads, head_dim, scale, out,
+                                         static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return launch_status(e);
+  }
+  return VFM_OK;
 }
 
 int vfm_tattn_bwd(const void* q, const void* k, const void* v, const void* dout, const int32_t* thw,
@@ -517,24 +583,25 @@ int vfm_tattn_bwd(const void* q, const void* k, const void* v, const void* dout,
   if (st) return st;
   if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
   st = check_cu(cu_seqlens, n_seqs, total_tokens);
-  if (st) return st;
-  vfm::TemporalTable tab;
-  st = build_temporal_table(thw, cu_seqlens, n_seqs, total_tokens, &tab);
+  if (!st) st = check_grids(thw, cu_seqlens, n_seqs, VFM_MAX_TEMPORAL);
   if (st) return st;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(dout) || !aligned16(dq) ||
       !aligned16(dk) || !aligned16(dv))
     return VFM_ERR_ALIGN;
-  if (total_tokens == 0) return VFM_OK;
-  forget_foreign_errors();
-  hipError_t e = vfm::launch_tattn_bwd(q, k, v, dout, tab, n_heads, head_dim, scale, dq, dk, dv,
-                                       static_cast<hipStream_t>(hip_stream));
-  return launch_status(e);
+  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_SEQS) {
+    vfm::TemporalTable tab;
+    build_temporal_table(thw + 3 * s0, cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), &tab);
+    hipError_t e = vfm::launch_tattn_bwd(q, k, v, dout, tab, n_heads, head_dim, scale, dq, dk, dv,
+                                         static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return launch_status(e);
+  }
+  return VFM_OK;
 }
 
 int vfm_fp8_pack_sizes(const int32_t* cu_seqlens, int n_seqs, int total_tokens, int n_heads,
                        int head_dim, size_t* q8_bytes, size_t* k8_bytes, size_t* vT8_bytes) {
   if (!cu_seqlens || !q8_bytes || !k8_bytes || !vT8_bytes) return VFM_ERR_NULL;
-  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim, VFM_MAX_SEQS);
   if (st) return st;
   st = check_cu(cu_seqlens, n_seqs, total_tokens);
   if (st) return st;
@@ -553,7 +620,7 @@ int vfm_fp8_pack(const void* q, const void* k, const void* v, const int32_t* cu_
   const float q_scale = scale * 1.4426950408889634f / k_scale;   // scores come out in log2 units
   if (!q || !k || !v || !cu_seqlens || !q8 || !k8 || !vT8) return VFM_ERR_NULL;
   if (dt != VFM_BF16) return VFM_ERR_DTYPE;
-  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim, VFM_MAX_SEQS);
   if (st) return st;
   for (float sc : {scale, k_scale, v_scale, q_scale})
     if (!(sc > 0.f) || !isfinite(sc)) return VFM_ERR_SHAPE;
@@ -564,7 +631,6 @@ int vfm_fp8_pack(const void* q, const void* k, const void* v, const int32_t* cu_
   vfm::Fp8ClipTable clips;
   const int units = build_fp8_tables(cu_seqlens, n_seqs, total_tokens, &clips, nullptr);
   if ((unsigned long long)units * n_heads * kFp8Unit * head_dim > 0xffffffffULL) return VFM_ERR_SHAPE;
-  forget_foreign_errors();
   hipError_t e = vfm::launch_fp8_pack(q, k, v, clips, units, total_tokens, n_heads, head_dim, q_scale,
                                       k_scale, v_scale, q8, k8, vT8, static_cast<hipStream_t>(hip_stream));
   return launch_status(e);
@@ -574,7 +640,7 @@ int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const int3
                      int n_seqs, int total_tokens, int n_heads, int head_dim, float v_scale,
                      void* out, float* lse, void* hip_stream) {
   if (!q8 || !k8 || !vT8 || !cu_seqlens || !out || !lse) return VFM_ERR_NULL;
-  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim, VFM_MAX_SEQS);
   if (st) return st;
   if (!(v_scale > 0.f) || !isfinite(v_scale)) return VFM_ERR_SHAPE;
   st = check_cu(cu_seqlens, n_seqs, total_tokens);
@@ -586,7 +652,6 @@ int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const int3
   vfm::Fp8SegTable segs;
   const int units = build_fp8_tables(cu_seqlens, n_seqs, total_tokens, &clips, &segs);
   if ((unsigned long long)units * n_heads * kFp8Unit * head_dim > 0xffffffffULL) return VFM_ERR_SHAPE;
-  forget_foreign_errors();
   hipError_t e = vfm::launch_attn_fwd_fp8(q8, k8, vT8, segs, units, total_tokens, n_heads, head_dim,
                                           1.0f / v_scale, out, lse,
                                           static_cast<hipStream_t>(hip_stream));

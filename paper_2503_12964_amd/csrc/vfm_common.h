@@ -4,6 +4,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <utility>
+
 #include "../../include/vfm.h"
 
 namespace vfm {
@@ -136,6 +139,21 @@ inline int count_tiles(const Segs& segs, int rows_per_tile) {
   return tiles;
 }
 
+// Query rows per workgroup of the forward kernel for the sequences of one launch.  Few keys
+// per sequence (cross-attention on a text prompt, packs of images): a workgroup's loop is
+// short against its prologue and epilogue, so 128-row workgroups are used, two of which share
+// a CU and overlap one's loads and stores with the other's loop (0.59 -> 0.55 ms for 56,320
+// queries x 512 keys x 32 heads; +3-5% on packs of 256- to 484-token clips).  Each
+// wavefront's arithmetic is the same.  With longer sequences the 256-row workgroup's halved
+// K/V staging traffic wins.  head_dim 64 always uses 128-row workgroups.
+template <class Segs>
+inline int fwd_tile_rows(const Segs& segs, int head_dim) {
+  if (head_dim != 128) return 128;
+  int longest_kv = 0;
+  for (int s = 0; s < segs.n; ++s) longest_kv = longest_kv > segs.kv_len(s) ? longest_kv : segs.kv_len(s);
+  return longest_kv <= 1024 ? 128 : 256;
+}
+
 // LDS tiles hold rows of D bf16 without padding; the 16-byte chunk index within
 // a row is XOR-ed with a function of the row so that both row-wise 16-byte reads
 // (16 consecutive rows, one chunk) and transposing 8-byte reads (4 consecutive
@@ -260,11 +278,11 @@ __device__ __forceinline__ uint32_t lds_addr_of(const void* p) {
 }
 __device__ __forceinline__ void lds_dma16(const void* base, uint32_t byte_off, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-               :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory");
+               :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory", "m0");
 }
 __device__ __forceinline__ void lds_dma4(const void* base, uint32_t byte_off, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-               :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory");
+               :: "s"(lds_addr), "v"(byte_off), "s"(base) : "memory", "m0");
 }
 // A pointer the compiler cannot prove wave-uniform (it depends on the wave index), moved
 // to scalar registers.
@@ -343,19 +361,41 @@ __device__ __forceinline__ void wait_mfma_a(f32x16& a, f32x16& b, f32x16& c, f32
   asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" : "+a"(a), "+a"(b), "+a"(c), "+a"(d));
 }
 
+// ---- kernel launch ----------------------------------------------------------
+// Every kernel of the library is launched through hipLaunchKernel, whose return value is that
+// launch's own status.  The thread's sticky "last error" is neither read nor cleared, so an
+// error other code left pending in the runtime stays where it is and is never mistaken for
+// the library's.
+template <class... P, size_t... I>
+inline hipError_t launch_impl(void (*kern)(P...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                              std::tuple<P...>& vals, std::index_sequence<I...>) {
+  void* ptrs[] = {static_cast<void*>(const_cast<std::remove_const_t<std::tuple_element_t<I, std::tuple<P...>>>*>(
+      &std::get<I>(vals)))...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kern), grid, block, ptrs, lds, stream);
+}
+template <class... P, class... A>
+inline hipError_t launch(void (*kern)(P...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                         const A&... args) {
+  static_assert(sizeof...(P) == sizeof...(A), "one argument per kernel parameter");
+  std::tuple<P...> vals{static_cast<P>(args)...};
+  return launch_impl(kern, grid, block, lds, stream, vals, std::index_sequence_for<P...>{});
+}
+
 // ---- launchers (defined next to their kernels) -----------------------------
-hipError_t launch_rope3d(void* x, const RopeTable& tab, int total, int n_heads, int head_dim,
+// The RoPE launchers work on the tokens [tab.cu[0], tab.cu[tab.n]) of the clips in tab.
+hipError_t launch_rope3d(void* x, const RopeTable& tab, int n_heads, int head_dim,
                          int dim_t, int dim_h, int dim_w, float theta, int inverse,
                          hipStream_t stream);
 
 hipError_t launch_qknorm_rope3d(const void* x, void* y, const float* gain, float eps,
-                                const RopeTable& tab, int total, int n_heads, int head_dim,
+                                const RopeTable& tab, int n_heads, int head_dim,
                                 int dim_t, int dim_h, int dim_w, float theta, hipStream_t stream);
 
 hipError_t launch_qknorm_rope3d_bwd(const void* x, const void* dy, void* dx, const float* gain,
-                                    float eps, float* dgain, const RopeTable& tab, int total,
+                                    float eps, float* dgain, const RopeTable& tab,
                                     int n_heads, int head_dim, int dim_t, int dim_h, int dim_w,
-                                    float theta, hipStream_t stream);
+                                    float theta, hipStream_t stream);   // accumulates into dgain
+hipError_t launch_zero_f32(float* p, int n, hipStream_t stream);
 
 hipError_t launch_tattn_fwd(const void* q, const void* k, const void* v, const TemporalTable& tab,
                             int n_heads, int head_dim, float scale, void* out, hipStream_t stream);
@@ -379,11 +419,16 @@ hipError_t launch_attn_fwd(const void* q, const void* k, const void* v, const Se
                            int total_q, int n_heads, int head_dim, float scale, void* out,
                            float* lse, hipStream_t stream);
 
+// Once per call: the statistics of all total_q query tokens.
+hipError_t launch_bwd_prepare(const void* out, const void* dout, const float* lse, float* delta, float* lse2,
+                              float* sentinel, int total_q, int n_heads, int head_dim, hipStream_t stream);
+// The sequences of segs (one run of a call's clips).  dkv32: optional fp32 dK, dV accumulators of
+// total_kv rows each (query-split pass); [kv_lo, kv_hi) is the run's range of key rows.
 template <class Segs>
 hipError_t launch_attn_bwd(const void* q, const void* k, const void* v, const void* out,
                            const float* lse, const void* dout, const Segs& segs, int total_q,
                            int n_heads, int head_dim, float scale, void* dq, void* dk, void* dv,
                            float* delta, float* lse2, float* sentinel, float* dkv32, int total_kv,
-                           hipStream_t stream);   // dkv32: optional fp32 dK,dV accumulators (query-split pass)
+                           int kv_lo, int kv_hi, hipStream_t stream);
 
 }  // namespace vfm

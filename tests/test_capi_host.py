@@ -77,7 +77,8 @@ def test_fwd_argument_errors(lib):
     assert _fwd(lib, [0, 8], 8, heads=0) == 2
     assert _fwd(lib, [0, 8], 8, scale=0.0) == 2
     assert _fwd(lib, [0, 8], 8, scale=float("nan")) == 2
-    assert _fwd(lib, [0] * 300, 0, n_seqs=299) == 2            # more clips than VFM_MAX_SEQS
+    assert _fwd(lib, [0] * 300, 0, n_seqs=299) == 0            # more clips than one table holds: legal
+    assert _fwd(lib, [0] * 299 + [9], 8, n_seqs=299) == 3      # ... and still validated to the end
     assert _fwd(lib, [1, 8], 8) == 3
     assert _fwd(lib, [0, 5, 4, 8], 8) == 3
     assert _fwd(lib, [0, 7], 8) == 3
@@ -140,7 +141,8 @@ def test_cross_attention_argument_errors(lib):
     assert xf([0, 8], [0, 4], 8, 4, q=None) == 1
     assert xf([0, 8], [0, 4], 8, 5) == 3                        # cu_seqlens_kv does not end at total_kv
     assert xf([0, 4, 8], [0, 4, 4], 8, 4) == 3                  # queries without keys
-    assert xf([0] * 130, [0] * 130, 0, 0) == 2                  # more sequences than VFM_MAX_XSEQS
+    assert xf([0] * 130, [0] * 130, 0, 0) == 0                  # more sequences than one table holds: legal
+    assert xf([0] * 129 + [8], [0] * 130, 8, 0) == 3            # queries without keys in the second run
     assert xf([0, 8], [0, 4], 8, 4, dt=1) == 6
     assert xf([0, 8], [0, 4], 8, 4, q=ODD) == 9
     assert xf([0, 8], [0, 4], 8, 4, scale=0.0) == 2
@@ -188,6 +190,8 @@ def test_fp8_argument_errors(lib):
     assert lib.vfm_fp8_pack_sizes(cu, 3, 166, 4, 128, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 3
     assert lib.vfm_fp8_pack_sizes(cu, 3, 165, 4, 96, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 2
     assert lib.vfm_fp8_pack_sizes(cu, 3, 165, 4, 128, None, ctypes.byref(b), ctypes.byref(c)) == 1
+    many, pm = _i32([0] * 300)
+    assert lib.vfm_fp8_pack_sizes(pm, 299, 0, 4, 128, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 2
 
     def pack(q=FAKE, qs=32.0, q8=FAKE, dt=0):
         return lib.vfm_fp8_pack(q, FAKE, FAKE, cu, 3, 165, 4, 128, qs, 1.0, 16.0, q8, FAKE, FAKE, dt, None)
@@ -203,6 +207,23 @@ def test_fp8_argument_errors(lib):
     assert fwd(vs=-1.0) == 2
     assert fwd(vs=0.0) == 2
     assert fwd(q8=ODD) == 9
+
+
+def test_forward_tile_rows_rule(lib):
+    def rows(cu, hd, run=0):
+        arr, p = _i32(cu)
+        r = ctypes.c_int(-1)
+        st = lib.vfm_attn_fwd_tile_rows(p, len(cu) - 1, cu[-1], hd, run, ctypes.byref(r))
+        return st, r.value
+    assert rows([0, 56320], 128) == (0, 256)
+    assert rows([0, 1024, 2048], 128) == (0, 128)               # longest clip <= 1,024 tokens
+    assert rows([0, 1025], 128) == (0, 256)
+    assert rows([0, 56320], 64) == (0, 128)
+    cu = [0] + [2000] * 256 + [2100]                            # run 0 holds the long clip, run 1 a short one
+    assert rows(cu, 128, 0) == (0, 256) and rows(cu, 128, 1) == (0, 128)
+    assert rows(cu, 128, 2)[0] == 2                             # no such run
+    assert rows([0, 8], 96)[0] == 2
+    assert rows([0, 8, 7], 128)[0] == 3
 
 
 def test_tensors_beyond_32bit_byte_offsets_are_rejected(lib):

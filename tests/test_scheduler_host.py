@@ -19,10 +19,17 @@ def _units_in_order(units):
     return [tuple(int(v) for v in u) for u in order]
 
 
-def _check(cu, heads, rows):
+def _check(cu, heads, rows, units=None):
+    """cu: boundaries of one launch's clips (absolute packed positions; cu[0] may be > 0 when the
+    launch is one run of a longer call); units: that launch's grid."""
     cu = np.asarray(cu, dtype=np.int64)
+    if units is None:
+        units = binding.vfm_schedule_units(cu, heads, rows)
+    base = int(cu[0])
+    cu = cu - base
+    units = np.array(units, dtype=np.int64)
+    units[units[:, 0] >= 0, 1] -= base
     total = int(cu[-1])
-    units = binding.vfm_schedule_units(cu, heads, rows)
     lens = np.diff(cu)
     n_tiles = int(sum((n + rows - 1) // rows for n in lens))
     assert len(units) % XCDS == 0
@@ -81,6 +88,41 @@ def test_equal_lengths_keep_packed_order_and_empty_input_has_no_workgroups():
     firsts = [int(u[1]) for u in _units_in_order(units) if u[0] >= 0]
     assert firsts == [0, 64, 100, 164, 200, 264]
     assert len(binding.vfm_schedule_units([0, 0, 0], 4, 256)) == 0
+
+
+def test_more_clips_than_a_table_holds_are_scheduled_run_by_run():
+    # 600 clips of 0..700 tokens: three launches (256 + 256 + 88 clips), whose grids follow one
+    # another; each is a complete schedule of its own run of clips
+    rng = np.random.default_rng(3)
+    lens = rng.integers(0, 700, size=600)
+    cu = np.concatenate([[0], np.cumsum(lens)])
+    heads, rows = 3, 128
+    units = binding.vfm_schedule_units(cu, heads, rows)
+    at = 0
+    for s0 in range(0, 600, 256):
+        run = cu[s0:min(600, s0 + 256) + 1]
+        n_tiles = int(sum((n + rows - 1) // rows for n in np.diff(run)))
+        grid = XCDS * ((n_tiles * heads + XCDS - 1) // XCDS)
+        _check(run, heads, rows, units[at:at + grid])
+        at += grid
+    assert at == len(units)
+
+
+def test_forward_schedule_with_its_own_tile_height():
+    # the forward cuts 128-row tiles when no clip of the launch has more than 1,024 tokens
+    # (and always at head_dim 64), 256-row tiles otherwise
+    for name, want in (("C2", 256), ("C4", 256)):
+        wl = W.WORKLOADS[name]
+        rows = binding.vfm_attn_fwd_tile_rows(wl.cu_seqlens, wl.head_dim)
+        assert rows == want
+        _check(wl.cu_seqlens, wl.n_heads, rows)
+    images = np.arange(0, 289) * 256                        # 288 images of 256 tokens: two runs
+    for run in (0, 1):
+        assert binding.vfm_attn_fwd_tile_rows(images, 128, run) == 128
+    spatial = W.WORKLOADS["C3"].spatial_cu_seqlens          # 36 frames of 256..1,024 tokens
+    assert binding.vfm_attn_fwd_tile_rows(spatial, 128) == 128
+    _check(spatial, 24, 128)
+    assert binding.vfm_attn_fwd_tile_rows(W.WORKLOADS["C4"].cu_seqlens, 64) == 128
 
 
 def test_argument_errors():
