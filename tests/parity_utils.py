@@ -45,3 +45,43 @@ def rel_rms(a, ref) -> float:
     d = np.asarray(a, dtype=np.float64) - ref
     den = float(np.sqrt(np.sum(ref * ref)))
     return float(np.sqrt(np.sum(d * d))) / den if den > 0 else float(np.sqrt(np.sum(d * d)))
+
+
+# A whole-tensor norm cannot see local damage: one unwritten row of an 8,192-token tensor moves the
+# relative RMS by 1.1e-2, under the gradient bound.  Every (token, head) row is therefore also held
+# to three times the tensor's bound: relative to the row's own magnitude, or, for rows that are
+# small by cancellation (below ROW_FLOOR of the tensor's RMS), relative to that floor.
+ROW_FACTOR = 3.0
+ROW_FLOOR = 1e-3
+
+
+def row_excess(got, ref, bound: float, tensor_rms=None) -> np.ndarray:
+    """Per row (all axes but the last): RMS error / (ROW_FACTOR * bound * max(row RMS, floor)); a
+    value above 1 breaks the per-row bound.  tensor_rms: RMS of the whole reference tensor when
+    `ref` holds only sampled rows of it."""
+    ref = np.asarray(ref, dtype=np.float64)
+    d = np.asarray(got, dtype=np.float64) - ref
+    row_ref = np.sqrt(np.mean(ref * ref, axis=-1))
+    row_err = np.sqrt(np.mean(d * d, axis=-1))
+    if tensor_rms is None:
+        tensor_rms = float(np.sqrt(np.mean(ref * ref))) if ref.size else 0.0
+    scale = np.maximum(row_ref, ROW_FLOOR * tensor_rms)
+    scale = np.where(scale > 0, scale, 1.0)
+    return row_err / (ROW_FACTOR * bound * scale)
+
+
+def assert_rows_close(name: str, got, ref, bound: float, tensor_rms=None, also=None) -> float:
+    """Every row of `got` within ROW_FACTOR * bound of the matching row of `ref` (or, row by row,
+    of the second reference `also` when one is given); returns the worst ratio (1.0 = at the
+    bound)."""
+    ex = row_excess(got, ref, bound, tensor_rms)
+    if also is not None:
+        ex = np.minimum(ex, row_excess(got, also, bound, tensor_rms))
+    if ex.size == 0:
+        return 0.0
+    worst = float(ex.max())
+    assert np.all(np.isfinite(ex)) and worst <= 1.0, (
+        f"{name}: row {np.unravel_index(int(np.nanargmax(ex)), ex.shape)} is off by "
+        f"{worst * ROW_FACTOR * bound:.3e} relative (per-row bound {ROW_FACTOR * bound:.1e}); "
+        f"{int(np.sum(ex > 1.0))} of {ex.size} rows beyond it")
+    return worst

@@ -90,11 +90,19 @@ def _assert_parity(wl, gpu, host, relative_maxabs=False):
     else:
         assert U.max_abs(o, o_ref) <= U.TOL_OUT_MAXABS
     assert U.rel_rms(o, o_ref) <= U.TOL_OUT_RELRMS
+    U.assert_rows_close("out", o, o_ref, U.TOL_OUT_RELRMS)
     assert U.max_abs(U.to_f64(lse), l_ref) <= U.TOL_LSE_MAXABS
-    for name, g, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), g_ref):
+    # The backward forms Delta = rowsum(dO o out) from the bf16 `out` it is handed (clips of at most
+    # 32 keys aside).  Where dS cancels almost completely (peaky softmax) that rounding shows in single
+    # rows of dq, dk although the tensor bound holds, so a row may sit within the per-row bound of
+    # the exact gradient or of the gradient that the same Delta from the same `out` gives; a
+    # damaged row is far from both.
+    g_met = orc.attn_bwd(q64, k64, v64, do64, wl.cu_seqlens, wl.scale, out=o)
+    for name, g, ref, met in zip(("dq", "dk", "dv"), (dq, dk, dv), g_ref, g_met):
         g64 = U.to_f64(g)
         assert np.all(np.isfinite(g64)), name
         assert U.rel_rms(g64, ref) <= U.TOL_GRAD_RELRMS, (name, U.rel_rms(g64, ref))
+        U.assert_rows_close(name, g64, ref, U.TOL_GRAD_RELRMS, also=met)     # every (token, head) row
 
 
 @pytest.mark.parametrize("name", list(SMALL))
@@ -179,27 +187,25 @@ def test_backward_is_bitwise_reproducible():
         assert np.array_equal(U.to_bits(a), U.to_bits(c))
 
 
-def test_two_token_clip_follows_delta_from_the_rounded_out():
-    # The backward takes Delta_i = sum_d dO_id O_id from the bf16 `out` it is given, as the method
-    # prescribes.  In a clip of two tokens dQ and dK are small by cancellation (dS_i1 = -dS_i2), so
-    # the rounding of `out` shows: against the exact oracle this case is off by 2% in dq and dk
-    # (found by a random sweep), against the same formulas with Delta from the rounded `out` by
-    # a quarter of a percent.  The second comparison is the one that checks the kernels.
-    wl = W.Workload("two_tokens", ((1, 1, 2), (0, 1, 1)), 1, 128, (32, 48, 48), seed=5469)
+@pytest.mark.parametrize("seed", [5469, 1, 2, 3])
+def test_two_token_clip_meets_the_gradient_bound(seed):
+    # In a clip of two tokens dQ and dK are small by cancellation (dS_i1 = -dS_i2).  With Delta
+    # taken from the bf16 `out` this very call (seed 5469, found by a random sweep) was off by 2%
+    # in dq and dk; for clips of at most 32 keys the backward now forms Delta as sum_j P_ij dP_ij,
+    # and the stated bound holds, for the tensor and for every row.
+    wl = W.Workload("two_tokens", ((1, 1, 2), (0, 1, 1)), 1, 128, (32, 48, 48), seed=seed)
     gpu, host = _run_fwd_bwd(wl, rope=True)
-    out, lse, dq, dk, dv = gpu
-    q, k, v, do = (x[:, 0] for x in host)
-    S = wl.scale * (q @ k.T)
-    P = np.exp(S - S.max(axis=1, keepdims=True))
-    P /= P.sum(axis=1, keepdims=True)
-    delta = (do * U.to_f64(out)[:, 0]).sum(axis=1, keepdims=True)
-    dS = P * (do @ v.T - delta)
-    assert U.rel_rms(U.to_f64(dq)[:, 0], wl.scale * dS @ k) <= 5e-3
-    assert U.rel_rms(U.to_f64(dk)[:, 0], wl.scale * dS.T @ q) <= 5e-3
-    assert U.rel_rms(U.to_f64(dv)[:, 0], P.T @ do) <= 5e-3
-    ref = orc.attn_bwd(*host, wl.cu_seqlens, wl.scale)
-    for g, r in zip((dq, dk, dv), ref):        # and the exact gradients are still met loosely
-        assert U.rel_rms(U.to_f64(g), r) <= 5e-2
+    _assert_parity(wl, gpu, host, relative_maxabs=True)
+
+
+def test_tiny_clips_of_every_length_up_to_forty():
+    # clip lengths 1..40 in one call, both sides of the 32-key limit of the exact-Delta path
+    wl = _custom("tiny_clips", [(1, 1, n) for n in range(1, 41)], 2, 128, (32, 48, 48), 31)
+    gpu, host = _run_fwd_bwd(wl, rope=True)
+    _assert_parity(wl, gpu, host, relative_maxabs=True)
+    wl = _custom("tiny_clips64", [(1, 1, n) for n in (1, 2, 3, 5, 8, 13, 21, 32, 33, 34)], 3, 64, (16, 24, 24), 32)
+    gpu, host = _run_fwd_bwd(wl, rope=True)
+    _assert_parity(wl, gpu, host, relative_maxabs=True)
 
 
 def test_closed_forms_on_gpu():

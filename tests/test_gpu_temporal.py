@@ -39,11 +39,13 @@ def _check(wl, gpu, dev, heads=None):
     # at most 32 keys: outputs are O(|v|), so the absolute bound is taken relative to max(1, |ref|)
     assert np.max(np.abs(o - o_ref) / np.maximum(1.0, np.abs(o_ref))) <= U.TOL_OUT_MAXABS
     assert U.rel_rms(o, o_ref) <= U.TOL_OUT_RELRMS
+    U.assert_rows_close("out", o, o_ref, U.TOL_OUT_RELRMS)
     for nm, g, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), g_ref):
         got = U.to_f64(g[:, hs, :])
         assert np.all(np.isfinite(got))
         r = U.rel_rms(got, ref)
         assert r <= U.TOL_GRAD_RELRMS, (nm, r)
+        U.assert_rows_close(nm, got, ref, U.TOL_GRAD_RELRMS)       # every (token, head) row
 
 
 def _run(b, wl):

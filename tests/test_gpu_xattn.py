@@ -42,11 +42,14 @@ def _assert(gpu, dev, cu_q, cu_kv, scale, heads=None):
     # few keys make outputs O(|v|): bound the error relative to max(1, |ref|) as for peaky softmax
     assert np.max(np.abs(o - o_ref) / np.maximum(1.0, np.abs(o_ref))) <= U.TOL_OUT_MAXABS
     assert U.rel_rms(o, o_ref) <= U.TOL_OUT_RELRMS
+    U.assert_rows_close("out", o, o_ref, U.TOL_OUT_RELRMS)
     # queries of empty sequences do not exist, so every lse entry is defined
     assert U.max_abs(U.to_f64(lse[hs, :]), l_ref) <= U.TOL_LSE_MAXABS
     for nm, g, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), g_ref):
-        r = U.rel_rms(U.to_f64(g[:, hs, :]), ref)
+        got = U.to_f64(g[:, hs, :])
+        r = U.rel_rms(got, ref)
         assert r <= U.TOL_GRAD_RELRMS, (nm, r)
+        U.assert_rows_close(nm, got, ref, U.TOL_GRAD_RELRMS)       # every (token, head) row
     return g_ref
 
 
