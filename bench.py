@@ -44,9 +44,65 @@ if ROOT not in sys.path:
 BF16_MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak (published)
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from `rocprofv3 --pmc` (FETCH_SIZE and
-# WRITE_SIZE runs, scaled by a copy kernel of known size); see profiles/.  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"C4": 24.96e9}
+# HBM bytes per launch of the dominant kernel from `rocprofv3 --pmc` (FETCH_SIZE and WRITE_SIZE
+# runs, scaled by a copy kernel of known size).  The figures live in a small text file that the
+# profile summariser (python -m paper_2503_12964_amd.profile_summary) rewrites from the counter
+# files of those runs; nothing is typed in here.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "attention_hbm_traffic.txt")
+
+
+def _measured_traffic(workload: str, key: str):
+    """Bytes per launch recorded for `workload` under `key` (e.g. "backward_call"), or None."""
+    try:
+        for line in open(TRAFFIC_FILE):
+            f = line.split()
+            if len(f) >= 3 and not line.startswith("#") and f[0] == workload and f[1] == key:
+                return float(f[2])
+    except OSError:
+        pass
+    return None
+
+
+class _ClockSampler:
+    """Polls `rocm-smi --showclocks --showpower --json` (a child process; this process' GPU work is
+    not touched) while the timed steps run, so the line carries the shader clock and power the
+    kernels actually ran at.  Absent tool or unparsable output: the sample is simply None."""
+
+    def __init__(self, period: float = 0.4):
+        import threading
+        self.period, self.samples, self._stop = period, [], threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        import re
+        while not self._stop.is_set():
+            try:
+                o = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--json"], capture_output=True,
+                                   text=True, timeout=5).stdout
+                card = next(iter(json.loads(o).values()))
+                sclk = next((re.sub(r"[^0-9.]", "", v) for k, v in card.items() if k.lower().startswith("sclk clock speed")), "")
+                power = next((v for k, v in card.items() if "power" in k.lower() and "(w)" in k.lower()), None)
+                self.samples.append((float(sclk) if sclk else None, float(power) if power is not None else None))
+            except Exception:
+                pass
+            self._stop.wait(self.period)
+
+    def __enter__(self):
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        self._thread.join(timeout=10)
+
+    def summary(self):
+        clk = [c for c, _ in self.samples if c]
+        pw = [p for _, p in self.samples if p]
+        if not clk:
+            return None
+        return {"sclk_mhz_median": float(np.median(clk)), "sclk_mhz_min": float(np.min(clk)),
+                "sclk_mhz_max": float(np.max(clk)), "power_w_median": float(np.median(pw)) if pw else None,
+                "samples": len(clk), "source": "rocm-smi --showclocks --showpower, polled during the timed steps"}
 
 
 def _mfma_ceiling(seconds: float = 1.5):
@@ -74,8 +130,12 @@ def _device_tensors(wl):
     return t
 
 
-def _cpu_baseline(wl, rows: int = 24576):
-    """The fp64 oracle, as it stands, on a bounded sample: `rows` query rows of head 0."""
+def _cpu_baseline(wl, seconds_per_pass: float = 4.0):
+    """The fp64 oracle, as it stands, on the host cores: one head of the workload (heads are
+    identical, independent work), forward + backward, on a block of query rows sized for a few
+    seconds per pass; 1 warm-up and 3 timed passes, median.  A workload whose head fits that
+    budget is timed in full.  The whole-head and whole-workload times are extrapolations
+    (rows are independent, identical work) and are labelled as such."""
     from oracle import vfm_oracle as orc
     from paper_2503_12964_amd import workloads as W
     try:
@@ -86,19 +146,34 @@ def _cpu_baseline(wl, rows: int = 24576):
     one = W.Workload(wl.name, wl.grids, 1, wl.head_dim, wl.rope_dims, wl.seed, wl.backward)
     inp = W.make_inputs(one)
     q, k, v, do = (W.bf16_bits_to_f32(inp[n]).astype(np.float64) for n in ("q", "k", "v", "dout"))
-    rows = min(rows, wl.seqlens[0])
-    sel = np.arange(rows)
-    t0 = time.perf_counter()
-    orc.attn_fwd_rows(q, k, v, wl.cu_seqlens, wl.scale, 0, sel)
-    if wl.backward:
-        orc.attn_bwd_rows(q, k, v, do, wl.cu_seqlens, wl.scale, 0, sel)
-    dt = time.perf_counter() - t0
     per_pair = (4 + (10 if wl.backward else 0)) * wl.head_dim
-    flops = float(per_pair) * rows * wl.seqlens[0]
+    clip = int(np.argmax(wl.seqlens))
+    a, n = int(wl.cu_seqlens[clip]), int(wl.seqlens[clip])
+
+    def one_pass(rows):
+        sel = a + np.arange(rows)
+        t0 = time.perf_counter()
+        orc.attn_fwd_rows(q, k, v, wl.cu_seqlens, wl.scale, 0, sel)
+        if wl.backward:
+            orc.attn_bwd_rows(q, k, v, do, wl.cu_seqlens, wl.scale, 0, sel)
+        return time.perf_counter() - t0
+    probe = min(n, 1024)
+    t_probe = one_pass(probe)                                    # warm-up (also sizes the block)
+    rows = int(min(n, max(probe, probe * seconds_per_pass / max(t_probe, 1e-3))))
+    rows -= rows % 256 if rows > 256 else 0
+    times = sorted(one_pass(rows) for _ in range(3))
+    dt = times[1]
+    rate = float(per_pair) * rows * n / dt
+    head_flops = float(per_pair) * sum(m * m for m in wl.seqlens)
     return {
-        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
-        "sample": f"{wl.name} head 0, first {rows} of {wl.seqlens[0]} query rows of clip 0, "
-                  f"{'fwd+bwd' if wl.backward else 'fwd'}, numpy fp64, {dt:.2f} s",
+        "value": rate / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"{wl.name} head 0, first {rows} of {n} query rows of clip {clip} against all its keys, "
+                  f"{'fwd+bwd' if wl.backward else 'fwd'}, numpy fp64; 1 warm-up + 3 timed passes, "
+                  f"median {dt:.2f} s (min {times[0]:.2f}, max {times[2]:.2f})",
+        "one_head_s_extrapolated": head_flops / rate,
+        "whole_workload_s_extrapolated": head_flops / rate * wl.n_heads,
+        "extrapolation": f"rows are independent, identical work: one head = the sample's rate over all "
+                         f"{sum(m * m for m in wl.seqlens)} (query, key) pairs; whole workload = x {wl.n_heads} heads",
     }
 
 
@@ -313,7 +388,8 @@ def main() -> int:
     spatial = args.workload.endswith("-spatial")
     wl = W.WORKLOADS[args.workload[:-len("-spatial")] if spatial else args.workload]
     t = _device_tensors(wl)
-    q, k, v, do = t["q"], t["k"], t["v"], t["dout"]
+    q0, k0, v, do = t["q"], t["k"], t["v"], t["dout"]      # q0, k0: the un-rotated draws, never written
+    q, k = torch.empty_like(q0), torch.empty_like(k0)
     out = torch.empty_like(q)
     lse = torch.empty((wl.n_heads, wl.total_tokens), dtype=torch.float32, device="cuda")
     dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
@@ -323,6 +399,11 @@ def main() -> int:
     cu_attn = wl.spatial_cu_seqlens if spatial else cu     # attention's sequence boundaries
 
     def step(ev=None):
+        # RoPE is in place: every step starts from fresh copies of the un-rotated q, k, so the
+        # rotation never compounds.  The two copies are outside the step's event bracket (they are
+        # the data loader's work, not the path's) but inside the wall-clock bracket.
+        q.copy_(q0)
+        k.copy_(k0)
         if ev: ev[0].record()
         B.vfm_rope3d(q, thw, cu, wl.rope_dims, wl.theta)
         B.vfm_rope3d(k, thw, cu, wl.rope_dims, wl.theta)
@@ -337,17 +418,22 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(events[i])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    sampler = _ClockSampler()
+    with sampler:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(events[i])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
 
-    ms_step = wall * 1e3 / args.steps
-    ms_rope = float(np.mean([e[0].elapsed_time(e[1]) for e in events]))
-    ms_fwd = float(np.mean([e[1].elapsed_time(e[2]) for e in events]))
-    ms_bwd = float(np.mean([e[2].elapsed_time(e[3]) for e in events])) if wl.backward else 0.0
+    # A step's time is its HIP-event time from before the first RoPE launch to after the backward;
+    # the reported ms_per_step is the median over the K timed steps (minimum beside it).  The wall
+    # clock over the same K steps, which also holds the two restoring copies, is reported too.
     ms_each = [e[0].elapsed_time(e[3]) for e in events]
+    ms_step = float(np.median(ms_each))
+    ms_rope = float(np.median([e[0].elapsed_time(e[1]) for e in events]))
+    ms_fwd = float(np.median([e[1].elapsed_time(e[2]) for e in events]))
+    ms_bwd = float(np.median([e[2].elapsed_time(e[3]) for e in events])) if wl.backward else 0.0
 
     f_fwd = wl.flops(backward=False, cu_seqlens=cu_attn)
     f_all = wl.flops(cu_seqlens=cu_attn)
@@ -381,11 +467,16 @@ def main() -> int:
                       "attn_only_model_tflops": (f_fwd + 0.8 * f_bwd) / ((ms_fwd + ms_bwd) * 1e-3) / 1e12
                                                 if wl.backward else None,
                       "step_ms_median": float(np.median(ms_each)), "step_ms_min": float(np.min(ms_each)),
+                      "step_ms_max": float(np.max(ms_each)),
+                      "wall_ms_per_step_incl_restoring_q_k": wall * 1e3 / args.steps,
+                      "timing": "ms_per_step = median of per-step HIP-event times (rope -> fwd -> bwd); q and k are "
+                                "restored from un-rotated copies before every step, outside the event bracket",
                       "rope_gbs": rope_bytes / (ms_rope * 1e-3) / 1e9,
                       "rope_frac_hbm_peak": rope_bytes / (ms_rope * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": achieved, "peak": BF16_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": achieved / BF16_MFMA_PEAK_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "ms": dom_ms, "note": dom_note},
+                     "traffic": _measured_traffic(args.workload, "backward_call" if wl.backward else "forward_call"),
+                     "ms": dom_ms, "note": dom_note, "clock_power_sample": sampler.summary()},
     }
     if ceiling:
         rnd = ceiling["random_operands_tflops"]
@@ -438,8 +529,10 @@ def main() -> int:
     # peak is the power limit and how much is the kernels' own schedule.  Skipped under a profiler
     # (it would mix into the per-kernel averages).
     if not args.no_constant_run and not any(name.startswith("ROCPROF") for name in os.environ):
-        for x in (q, k, v, do):
+        for x in (q0, k0, v, do):
             x.fill_(1.0)
+        q.copy_(q0)
+        k.copy_(k0)
 
         def attn_only():
             B.vfm_attn_fwd(q, k, v, cu_attn, wl.scale, out=out, lse=lse)
@@ -451,7 +544,7 @@ def main() -> int:
             "same_calls_on_the_synthetic_data_ms": ms_fwd + ms_bwd,
             "note": "vfm_attn_fwd (+ vfm_attn_bwd) with q = k = v = dout = 1.0: same kernels, same launch, "
                     "only the operand bits differ"}
-    del q, k, v, do, out, dq, dk, dv, ws, t
+    del q, k, q0, k0, v, do, out, dq, dk, dv, ws, t
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline and not spatial:
         result["cpu_baseline"] = _cpu_baseline(wl)
