@@ -34,7 +34,6 @@
  *     consecutive launches on hip_stream over runs of VFM_MAX_SEQS clips in
  *     packed order (VFM_MAX_XSEQS sequences for cross-attention).  Clips are
  *     independent, so the result does not depend on where the runs are cut.
- *     (Exception: the FP8 entry points take at most VFM_MAX_SEQS clips per call.)
  *   - Every function returns a vfm_status; 0 is success.  Argument errors are
  *     detected before anything is launched and leave all outputs untouched.
  *   - Re-entrant: no global mutable state (beyond the calling thread's last
@@ -288,16 +287,22 @@ VFM_API int vfm_tattn_bwd(const void* q, const void* k, const void* v, const voi
 /*
  * FP8 attention forward (Section 5.2 reports FP8 multi-head attention for
  * inference).  Operands are 8-bit floats in the E4M3 format of the OCP 8-bit
- * floating point specification, prepared once per (q, k, v) by vfm_fp8_pack:
- *   x8 = round_to_nearest_even(clamp(x * m_x, -448, 448))
- * with the multipliers  m_k = k_scale,  m_v = v_scale  (caller-chosen) and
- *   m_q = scale * log2(e) / k_scale
- * where scale is the softmax scale: the product q8 . k8 is then the softmax
- * exponent in log2 units, and the kernel needs no multiply before its exp2.
- * (Keep k_scale near 1 for unit-variance inputs so that m_q q stays in E4M3's
- * normal range, >= 2^-6.)  The three packed buffers hold, per head h (a "unit"
- * is 64 consecutive keys of one clip, zero padded at the clip's end; units are
- * numbered clip by clip in packed order, clip s owning ceil(len_s / 64)):
+ * floating point specification, with one power-of-two scale per tile, chosen by
+ * vfm_fp8_pack, which prepares the operands once per (q, k, v):
+ *   tile          = a (token, head) row of q  |  a (head, unit) of k  |  a (head, unit) of v
+ *                   (a "unit" is 64 consecutive keys of one clip, zero padded at
+ *                   the clip's end; units are numbered clip by clip in packed
+ *                   order, clip s owning ceil(len_s / 64))
+ *   e             = the largest integer with  max|x| * 2^e <= 448  over the tile,
+ *                   limited to [-120, 120], 0 for an all-zero tile
+ *   x8            = round_to_nearest_even(x * 2^e)          (x is read back as x8 * 2^-e)
+ * For q, x is q * scale * log2(e) rounded to fp32 (scale = the softmax scale):
+ * the product q8 . k8, descaled, is then the softmax exponent in log2 units.
+ * The kernel hands 2^-e of both tiles to the matrix instruction as its
+ * block-scale inputs, which applies them exactly and at no cost.  The fourth
+ * tensor of the row, P, is scaled per query row by the softmax reference point
+ * (every probability is stored relative to it) times a fixed 2^6.
+ * Packed buffers, per head h:
  *   q8  [n_heads][total_tokens][head_dim]
  *   k8  [n_heads][units][64][head_dim]: key row r of a unit holds its 16-byte
  *       chunk c at chunk position c ^ ((r >> 1) & 7) (head_dim 128) or
@@ -306,35 +311,39 @@ VFM_API int vfm_tattn_bwd(const void* q, const void* k, const void* v, const voi
  *       c ^ ((d >> 2) & 3), the logical chunk c of a 64-byte row whose byte
  *       32 g + j (g < 2, j < 32) is key  32 (j / 16) + 8 ((j % 16) / 4) + 4 g + j % 4
  *       of the unit.
+ *   scales: [n_heads][total_tokens] bytes 127 - e of the q rows, padded to a
+ *       multiple of 256 bytes, then [n_heads][units] 32-bit words whose byte 0
+ *       is 127 - e of the k unit and byte 1 is 127 - e of the v unit (bytes 2
+ *       and 3 are 127).
  * (The chunk permutations are the kernels' LDS bank swizzle, the byte order is
  * the order the matrix instruction consumes keys in; callers treat the buffers
- * as opaque.)  vfm_fp8_pack_sizes returns the three sizes in bytes.
+ * as opaque.)  vfm_fp8_pack_sizes returns the four sizes in bytes.
  * Errors: NULL, SHAPE (incl. a packed buffer beyond 4 GiB), CU_SEQLENS, DTYPE,
  * ALIGN, LAUNCH.
  */
 VFM_API int vfm_fp8_pack_sizes(const int32_t* cu_seqlens, int n_seqs, int total_tokens,
                        int n_heads, int head_dim,
-                       size_t* q8_bytes, size_t* k8_bytes, size_t* vT8_bytes);
+                       size_t* q8_bytes, size_t* k8_bytes, size_t* vT8_bytes, size_t* scales_bytes);
 VFM_API int vfm_fp8_pack(const void* q, const void* k, const void* v,
                  const int32_t* cu_seqlens, int n_seqs, int total_tokens,
-                 int n_heads, int head_dim, float scale, float k_scale, float v_scale,
-                 void* q8, void* k8, void* vT8, vfm_dtype dt, void* hip_stream);
+                 int n_heads, int head_dim, float scale,
+                 void* q8, void* k8, void* vT8, void* scales, vfm_dtype dt, void* hip_stream);
 
 /*
  * out, lse as vfm_attn_fwd, computed from the packed E4M3 operands with FP8
- * matrix instructions and fp32 accumulation:
- *     S_ij  = ln(2) * sum_d q8[i,d] k8[j,d]        (= scale q_i . k_j up to rounding)
- *     out_i = (1 / v_scale) * sum_j softmax_j(S_ij) v8[j,:]
- * v_scale is the one given to vfm_fp8_pack.  The probabilities are rounded to
- * E4M3 (3 mantissa bits) before the second product, so out carries a relative
- * error of a few percent against the exact result on the same quantised
- * operands; lse is accumulated in fp32.  out: bf16 [total_tokens, n_heads,
- * head_dim]; lse: fp32 [n_heads, total_tokens].
+ * matrix instructions and fp32 accumulation (q', k', v' = the values the tiles
+ * read back as):
+ *     S_ij  = ln(2) * sum_d q'[i,d] k'[j,d]        (= scale q_i . k_j up to rounding)
+ *     out_i = sum_j softmax_j(S_ij) v'[j,:]
+ * The probabilities are rounded to E4M3 (3 mantissa bits) before the second
+ * product, so out carries a relative error of a few percent against the exact
+ * result on the same quantised operands; lse is accumulated in fp32.  out: bf16
+ * [total_tokens, n_heads, head_dim]; lse: fp32 [n_heads, total_tokens].
  * Errors: NULL, SHAPE, CU_SEQLENS, ALIGN, LAUNCH.
  */
-VFM_API int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8,
+VFM_API int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const void* scales,
                      const int32_t* cu_seqlens, int n_seqs, int total_tokens,
-                     int n_heads, int head_dim, float v_scale,
+                     int n_heads, int head_dim,
                      void* out, float* lse, void* hip_stream);
 
 /*

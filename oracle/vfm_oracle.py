@@ -67,6 +67,7 @@ __all__ = [
     "temporal_attn_bwd",
     "fp8_e4m3_decode",
     "fp8_e4m3_encode",
+    "fp8_tile_exponent",
     "attn_fwd_rows",
     "attn_bwd_rows",
     "attn_bwd_cols",
@@ -423,6 +424,21 @@ def fp8_e4m3_encode(x) -> np.ndarray:
     code = np.where(pick_lo, lo, hi).astype(np.uint8)
     code = np.where(np.signbit(x), code | 0x80, code).astype(np.uint8)
     return np.where(np.isnan(x), np.uint8(0x7F), code).astype(np.uint8)
+
+
+def fp8_tile_exponent(amax) -> np.ndarray:
+    """Scale exponent of a tile of values that is to be stored in E4M3 (FP8 attention, Section
+    5.2; the paper names no scaling rule, the reading taken is one power-of-two scale per tile,
+    which the matrix hardware applies exactly): the largest integer e with
+        amax * 2**e <= 448        (448 = largest finite E4M3 value)
+    where amax is the largest magnitude in the tile.  e is limited to [-120, 120] (scales travel
+    as 8-bit exponents), and an all-zero tile takes e = 0.  The tile is stored as the E4M3
+    codes of x * 2**e and read back as decode(code) * 2**-e.  Returns int64."""
+    a = np.abs(np.asarray(amax, dtype=np.float64))
+    m, x = np.frexp(a)                       # a = m * 2**x with m in [0.5, 1);  448 = 0.875 * 2**9
+    e = np.where(m <= 0.875, 9 - x, 8 - x)
+    e = np.clip(e, -120, 120)
+    return np.where(a == 0.0, 0, e).astype(np.int64)
 
 
 def _segment_of(cu: np.ndarray, n: int):

@@ -92,12 +92,12 @@ def load_library(path: str = LIB_PATH) -> ctypes.CDLL:
                                   c_float, c_void_p, c_void_p, c_void_p, c_int, c_void_p]
     p_size = ctypes.POINTER(c_size_t)
     lib.vfm_fp8_pack_sizes.restype = c_int
-    lib.vfm_fp8_pack_sizes.argtypes = [p_i32, c_int, c_int, c_int, c_int, p_size, p_size, p_size]
+    lib.vfm_fp8_pack_sizes.argtypes = [p_i32, c_int, c_int, c_int, c_int, p_size, p_size, p_size, p_size]
     lib.vfm_fp8_pack.restype = c_int
-    lib.vfm_fp8_pack.argtypes = [c_void_p, c_void_p, c_void_p, p_i32, c_int, c_int, c_int, c_int, c_float, c_float,
-                                 c_float, c_void_p, c_void_p, c_void_p, c_int, c_void_p]
+    lib.vfm_fp8_pack.argtypes = [c_void_p, c_void_p, c_void_p, p_i32, c_int, c_int, c_int, c_int, c_float,
+                                 c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_void_p]
     lib.vfm_attn_fwd_fp8.restype = c_int
-    lib.vfm_attn_fwd_fp8.argtypes = [c_void_p, c_void_p, c_void_p, p_i32, c_int, c_int, c_int, c_int, c_float,
+    lib.vfm_attn_fwd_fp8.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, p_i32, c_int, c_int, c_int, c_int,
                                      c_void_p, c_void_p, c_void_p]
     lib.vfm_strerror.restype = ctypes.c_char_p
     lib.vfm_strerror.argtypes = [c_int]
@@ -362,35 +362,36 @@ def vfm_tattn_bwd(q, k, v, dout, thw, cu_seqlens, scale: float, dq=None, dk=None
     return dq, dk, dv
 
 
-def vfm_fp8_pack_sizes(cu_seqlens, n_heads: int, head_dim: int) -> Tuple[int, int, int]:
-    """Bytes of the packed q8, k8 and vT8 buffers for these clips."""
+def vfm_fp8_pack_sizes(cu_seqlens, n_heads: int, head_dim: int) -> Tuple[int, int, int, int]:
+    """Bytes of the packed q8, k8, vT8 and scales buffers for these clips."""
     lib = load_library()
     cu = _host_i32(cu_seqlens)
-    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    a, b, c, d = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
     _check(lib.vfm_fp8_pack_sizes(_i32_ptr(cu), int(cu.size - 1), int(cu[-1]), int(n_heads), int(head_dim),
-                                  ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
-    return int(a.value), int(b.value), int(c.value)
+                                  ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(d)))
+    return int(a.value), int(b.value), int(c.value), int(d.value)
 
 
-def vfm_fp8_pack(q, k, v, cu_seqlens, scale: float, k_scale: float, v_scale: float, q8=None, k8=None,
-                 vT8=None, stream=None) -> Tuple:
-    """Quantise bf16 q, k, v to E4M3 in the packed layout vfm_attn_fwd_fp8 reads (uint8 device buffers).
-    k and v are multiplied by k_scale, v_scale; q by scale * log2(e) / k_scale (scale = softmax scale)."""
+def vfm_fp8_pack(q, k, v, cu_seqlens, scale: float, q8=None, k8=None, vT8=None, scales=None, stream=None) -> Tuple:
+    """Quantise bf16 q, k, v to E4M3 tiles with power-of-two scales, in the packed layout
+    vfm_attn_fwd_fp8 reads (uint8 device buffers q8, k8, vT8 and the scales buffer).  q also
+    carries scale * log2(e) (scale = softmax scale)."""
     import torch
     lib = load_library()
     cu = _host_i32(cu_seqlens)
     total, heads, hd = q.shape
-    nq, nk, nv = vfm_fp8_pack_sizes(cu, heads, hd)
+    nq, nk, nv, ns = vfm_fp8_pack_sizes(cu, heads, hd)
     q8 = torch.empty(max(nq, 16), dtype=torch.uint8, device=q.device) if q8 is None else q8
     k8 = torch.empty(max(nk, 16), dtype=torch.uint8, device=q.device) if k8 is None else k8
     vT8 = torch.empty(max(nv, 16), dtype=torch.uint8, device=q.device) if vT8 is None else vT8
+    scales = torch.empty(max(ns, 16), dtype=torch.uint8, device=q.device) if scales is None else scales
     _check(lib.vfm_fp8_pack(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _i32_ptr(cu), int(cu.size - 1), int(total),
-                            int(heads), int(hd), float(scale), float(k_scale), float(v_scale), _dev(q8, "q8"),
-                            _dev(k8, "k8"), _dev(vT8, "vT8"), _dtype_code(q), _stream_ptr(stream)))
-    return q8, k8, vT8
+                            int(heads), int(hd), float(scale), _dev(q8, "q8"), _dev(k8, "k8"), _dev(vT8, "vT8"),
+                            _dev(scales, "scales"), _dtype_code(q), _stream_ptr(stream)))
+    return q8, k8, vT8, scales
 
 
-def vfm_attn_fwd_fp8(q8, k8, vT8, cu_seqlens, n_heads: int, head_dim: int, v_scale: float, out=None, lse=None,
+def vfm_attn_fwd_fp8(q8, k8, vT8, scales, cu_seqlens, n_heads: int, head_dim: int, out=None, lse=None,
                      stream=None) -> Tuple:
     """FP8 attention forward on packed operands: out (bf16 [total, heads, head_dim]) and lse (fp32)."""
     import torch
@@ -401,7 +402,7 @@ def vfm_attn_fwd_fp8(q8, k8, vT8, cu_seqlens, n_heads: int, head_dim: int, v_sca
         out = torch.empty((total, n_heads, head_dim), dtype=torch.bfloat16, device=q8.device)
     if lse is None:
         lse = torch.empty((n_heads, total), dtype=torch.float32, device=q8.device)
-    _check(lib.vfm_attn_fwd_fp8(_dev(q8, "q8"), _dev(k8, "k8"), _dev(vT8, "vT8"), _i32_ptr(cu), int(cu.size - 1),
-                                total, int(n_heads), int(head_dim), float(v_scale), _dev(out, "out"),
+    _check(lib.vfm_attn_fwd_fp8(_dev(q8, "q8"), _dev(k8, "k8"), _dev(vT8, "vT8"), _dev(scales, "scales"), _i32_ptr(cu),
+                                int(cu.size - 1), total, int(n_heads), int(head_dim), _dev(out, "out"),
                                 _dev(lse, "lse"), _stream_ptr(stream)))
     return out, lse

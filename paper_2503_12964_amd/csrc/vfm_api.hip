@@ -121,28 +121,38 @@ void build_temporal_table(const int32_t* thw, const int32_t* cu, int n_seqs, vfm
 
 constexpr int kFp8Unit = 64;   // keys per packed unit of the FP8 path
 
-// Units of 64 keys per clip (never straddling clips); returns their total.
-int build_fp8_tables(const int32_t* cu, int n_seqs, int total, vfm::Fp8ClipTable* clips,
+// Units of 64 keys per clip (never straddling clips), over the whole call.
+size_t count_fp8_units(const int32_t* cu, int n_seqs) {
+  size_t units = 0;
+  for (int s = 0; s < n_seqs; ++s) units += (size_t)(cu[s + 1] - cu[s] + kFp8Unit - 1) / kFp8Unit;
+  return units;
+}
+
+// Tables of one run of clips; unit_base = units of the clips before the run.  Returns the units
+// of the clips before the next run.
+int build_fp8_tables(const int32_t* cu, int n_seqs, int unit_base, vfm::Fp8ClipTable* clips,
                      vfm::Fp8SegTable* segs) {
-  int units = 0;
+  int units = unit_base;
+  int unit0[VFM_MAX_SEQS];
   clips->n = n_seqs;
   for (int s = 0; s < n_seqs; ++s) {
     clips->cu[s] = cu[s];
-    clips->unit0[s] = units;
+    clips->unit0[s] = unit0[s] = units;
     units += (cu[s + 1] - cu[s] + kFp8Unit - 1) / kFp8Unit;
   }
-  for (int s = n_seqs; s <= VFM_MAX_SEQS; ++s) { clips->cu[s] = total; clips->unit0[s] = units; }
-  if (segs) {
-    SegTable plain;
-    build_seg_table(cu, n_seqs, &plain);
-    segs->n = plain.n;
+  for (int s = n_seqs; s <= VFM_MAX_SEQS; ++s) { clips->cu[s] = cu[n_seqs]; clips->unit0[s] = units; }
+  if (segs) {   // the forward kernel's schedule: non-empty clips, longest first
+    int order[VFM_MAX_SEQS];
+    int n = 0;
+    for (int s = 0; s < n_seqs; ++s)
+      if (cu[s + 1] > cu[s]) order[n++] = s;
+    std::stable_sort(order, order + n, [&](int a, int b) { return (cu[a + 1] - cu[a]) > (cu[b + 1] - cu[b]); });
+    segs->n = n;
     for (int i = 0; i < VFM_MAX_SEQS; ++i) {
-      segs->start[i] = plain.start[i];
-      segs->len[i] = plain.len[i];
-      segs->unit0[i] = 0;
-      if (i < plain.n)
-        for (int s = 0; s < n_seqs; ++s)
-          if (cu[s] == plain.start[i] && cu[s + 1] - cu[s] == plain.len[i]) { segs->unit0[i] = clips->unit0[s]; break; }
+      const bool live = i < n;
+      segs->start[i] = live ? cu[order[i]] : 0;
+      segs->len[i] = live ? cu[order[i] + 1] - cu[order[i]] : 0;
+      segs->unit0[i] = live ? unit0[order[i]] : 0;
     }
   }
   return units;
@@ -237,7 +247,7 @@ const char* vfm_strerror(int status) {
   switch (status) {
     case VFM_OK: return "ok";
     case VFM_ERR_NULL: return "a required pointer is NULL";
-    case VFM_ERR_SHAPE: return "total_tokens, n_heads, head_dim (64 or 128), n_seqs (FP8 entry points: <= 256), a tensor beyond 4 GiB, scale or theta (> 0, finite) or eps (>= 0) out of range, or dx aliases x";
+    case VFM_ERR_SHAPE: return "total_tokens, n_heads, head_dim (64 or 128), a tensor beyond 4 GiB, scale or theta (> 0, finite) or eps (>= 0) out of range, or dx aliases x";
     case VFM_ERR_CU_SEQLENS: return "cu_seqlens must start at 0, be non-decreasing and end at total_tokens";
     case VFM_ERR_THW: return "each clip needs positive T, H, W with T*H*W equal to its length (temporal attention: T <= 32)";
     case VFM_ERR_SPLIT: return "dim_t + dim_h + dim_w must equal head_dim, each part even and >= 0";
@@ -599,63 +609,74 @@ int vfm_tattn_bwd(const void* q, const void* k, const void* v, const void* dout,
 }
 
 int vfm_fp8_pack_sizes(const int32_t* cu_seqlens, int n_seqs, int total_tokens, int n_heads,
-                       int head_dim, size_t* q8_bytes, size_t* k8_bytes, size_t* vT8_bytes) {
-  if (!cu_seqlens || !q8_bytes || !k8_bytes || !vT8_bytes) return VFM_ERR_NULL;
-  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim, VFM_MAX_SEQS);
+                       int head_dim, size_t* q8_bytes, size_t* k8_bytes, size_t* vT8_bytes,
+                       size_t* scales_bytes) {
+  if (!cu_seqlens || !q8_bytes || !k8_bytes || !vT8_bytes || !scales_bytes) return VFM_ERR_NULL;
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
   if (st) return st;
   st = check_cu(cu_seqlens, n_seqs, total_tokens);
   if (st) return st;
-  vfm::Fp8ClipTable clips;
-  const size_t units = (size_t)build_fp8_tables(cu_seqlens, n_seqs, total_tokens, &clips, nullptr);
+  const size_t units = count_fp8_units(cu_seqlens, n_seqs);
   *q8_bytes = (size_t)total_tokens * n_heads * head_dim;
   *k8_bytes = units * n_heads * kFp8Unit * head_dim;
   *vT8_bytes = *k8_bytes;
+  *scales_bytes = 0;
   if (*k8_bytes > 0xffffffffULL) return VFM_ERR_SHAPE;   // the kernels address a unit with a 32-bit byte offset
+  *scales_bytes = vfm::fp8_scales_bytes(total_tokens, n_heads, (int)units);
   return VFM_OK;
 }
 
 int vfm_fp8_pack(const void* q, const void* k, const void* v, const int32_t* cu_seqlens, int n_seqs,
-                 int total_tokens, int n_heads, int head_dim, float scale, float k_scale,
-                 float v_scale, void* q8, void* k8, void* vT8, vfm_dtype dt, void* hip_stream) {
-  const float q_scale = scale * 1.4426950408889634f / k_scale;   // scores come out in log2 units
-  if (!q || !k || !v || !cu_seqlens || !q8 || !k8 || !vT8) return VFM_ERR_NULL;
+                 int total_tokens, int n_heads, int head_dim, float scale, void* q8, void* k8, void* vT8,
+                 void* scales, vfm_dtype dt, void* hip_stream) {
+  const float pre = scale * 1.4426950408889634f;   // scores come out in log2 units
+  if (!q || !k || !v || !cu_seqlens || !q8 || !k8 || !vT8 || !scales) return VFM_ERR_NULL;
   if (dt != VFM_BF16) return VFM_ERR_DTYPE;
-  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim, VFM_MAX_SEQS);
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
   if (st) return st;
-  for (float sc : {scale, k_scale, v_scale, q_scale})
-    if (!(sc > 0.f) || !isfinite(sc)) return VFM_ERR_SHAPE;
+  if (!(scale > 0.f) || !isfinite(scale) || !isfinite(pre)) return VFM_ERR_SHAPE;
   st = check_cu(cu_seqlens, n_seqs, total_tokens);
   if (st) return st;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(q8) || !aligned16(k8) || !aligned16(vT8))
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(q8) || !aligned16(k8) || !aligned16(vT8) ||
+      !aligned16(scales))
     return VFM_ERR_ALIGN;
-  vfm::Fp8ClipTable clips;
-  const int units = build_fp8_tables(cu_seqlens, n_seqs, total_tokens, &clips, nullptr);
-  if ((unsigned long long)units * n_heads * kFp8Unit * head_dim > 0xffffffffULL) return VFM_ERR_SHAPE;
-  hipError_t e = vfm::launch_fp8_pack(q, k, v, clips, units, total_tokens, n_heads, head_dim, q_scale,
-                                      k_scale, v_scale, q8, k8, vT8, static_cast<hipStream_t>(hip_stream));
-  return launch_status(e);
+  const size_t units = count_fp8_units(cu_seqlens, n_seqs);
+  if (units * n_heads * kFp8Unit * head_dim > 0xffffffffULL) return VFM_ERR_SHAPE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e = vfm::launch_fp8_pack_q(q, total_tokens, n_heads, head_dim, pre, q8, scales, stream);
+  if (e != hipSuccess) return launch_status(e);
+  int unit_base = 0;
+  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_SEQS) {
+    vfm::Fp8ClipTable clips;
+    unit_base = build_fp8_tables(cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), unit_base, &clips, nullptr);
+    e = vfm::launch_fp8_pack_kv(k, v, clips, (int)units, total_tokens, n_heads, head_dim, k8, vT8, scales, stream);
+    if (e != hipSuccess) return launch_status(e);
+  }
+  return VFM_OK;
 }
 
-int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const int32_t* cu_seqlens,
-                     int n_seqs, int total_tokens, int n_heads, int head_dim, float v_scale,
+int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const void* scales,
+                     const int32_t* cu_seqlens, int n_seqs, int total_tokens, int n_heads, int head_dim,
                      void* out, float* lse, void* hip_stream) {
-  if (!q8 || !k8 || !vT8 || !cu_seqlens || !out || !lse) return VFM_ERR_NULL;
-  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim, VFM_MAX_SEQS);
+  if (!q8 || !k8 || !vT8 || !scales || !cu_seqlens || !out || !lse) return VFM_ERR_NULL;
+  int st = check_shape(n_seqs, total_tokens, n_heads, head_dim);
   if (st) return st;
-  if (!(v_scale > 0.f) || !isfinite(v_scale)) return VFM_ERR_SHAPE;
   st = check_cu(cu_seqlens, n_seqs, total_tokens);
   if (st) return st;
-  if (!aligned16(q8) || !aligned16(k8) || !aligned16(vT8) || !aligned16(out) || !aligned16(lse))
+  if (!aligned16(q8) || !aligned16(k8) || !aligned16(vT8) || !aligned16(scales) || !aligned16(out) || !aligned16(lse))
     return VFM_ERR_ALIGN;
-  if (total_tokens == 0) return VFM_OK;
-  vfm::Fp8ClipTable clips;
-  vfm::Fp8SegTable segs;
-  const int units = build_fp8_tables(cu_seqlens, n_seqs, total_tokens, &clips, &segs);
-  if ((unsigned long long)units * n_heads * kFp8Unit * head_dim > 0xffffffffULL) return VFM_ERR_SHAPE;
-  hipError_t e = vfm::launch_attn_fwd_fp8(q8, k8, vT8, segs, units, total_tokens, n_heads, head_dim,
-                                          1.0f / v_scale, out, lse,
-                                          static_cast<hipStream_t>(hip_stream));
-  return launch_status(e);
+  const size_t units = count_fp8_units(cu_seqlens, n_seqs);
+  if (units * n_heads * kFp8Unit * head_dim > 0xffffffffULL) return VFM_ERR_SHAPE;
+  int unit_base = 0;
+  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_SEQS) {
+    vfm::Fp8ClipTable clips;
+    vfm::Fp8SegTable segs;
+    unit_base = build_fp8_tables(cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), unit_base, &clips, &segs);
+    hipError_t e = vfm::launch_attn_fwd_fp8(q8, k8, vT8, scales, segs, (int)units, total_tokens, n_heads, head_dim,
+                                            out, lse, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return launch_status(e);
+  }
+  return VFM_OK;
 }
 
 }  // extern "C"

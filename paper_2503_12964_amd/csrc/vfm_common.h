@@ -404,13 +404,15 @@ hipError_t launch_tattn_bwd(const void* q, const void* k, const void* v, const v
                             const TemporalTable& tab, int n_heads, int head_dim, float scale, void* dq,
                             void* dk, void* dv, hipStream_t stream);
 
-hipError_t launch_fp8_pack(const void* q, const void* k, const void* v, const Fp8ClipTable& clips,
-                           int n_units, int total, int n_heads, int head_dim, float qs, float ks,
-                           float vs, void* q8, void* k8, void* vT8, hipStream_t stream);
-
-hipError_t launch_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const Fp8SegTable& segs,
-                               int n_units, int total, int n_heads, int head_dim, float v_descale,
+// FP8 path.  scales: the q row exponents and the units' scale words (fp8_scales_bytes() bytes).
+hipError_t launch_fp8_pack_q(const void* q, int total, int n_heads, int head_dim, float pre, void* q8,
+                             void* scales, hipStream_t stream);
+hipError_t launch_fp8_pack_kv(const void* k, const void* v, const Fp8ClipTable& clips, int n_units, int total,
+                              int n_heads, int head_dim, void* k8, void* vT8, void* scales, hipStream_t stream);
+hipError_t launch_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const void* scales,
+                               const Fp8SegTable& segs, int n_units, int total, int n_heads, int head_dim,
                                void* out, float* lse, hipStream_t stream);
+size_t fp8_scales_bytes(int total, int n_heads, int n_units);
 
 // Segs is SegTable (self-attention) or XSegTable (cross-attention); total_q is the number
 // of query tokens (rows of lse, Delta).

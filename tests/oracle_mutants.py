@@ -79,6 +79,9 @@ MUTANTS = {
     "fp8_ties_to_odd": ("(lo % 2 == 0)", "(lo % 2 == 1)", 0),
     "fp8_truncates": ("pick_lo = (d_lo < d_hi) |", "pick_lo = (d_lo >= 0) |", 0),
     "fp8_sign_lost": ("code = np.where(np.signbit(x), code | 0x80, code)", "code = np.where(np.signbit(x), code, code)", 0),
+    "fp8_tile_exponent_off_by_one": ("e = np.where(m <= 0.875, 9 - x, 8 - x)", "e = np.where(m <= 0.875, 8 - x, 7 - x)", 0),
+    "fp8_tile_exponent_boundary": ("e = np.where(m <= 0.875, 9 - x, 8 - x)", "e = np.where(m < 0.875, 9 - x, 8 - x)", 0),
+    "fp8_tile_exponent_to_256": ("e = np.where(m <= 0.875, 9 - x, 8 - x)", "e = np.where(m <= 0.5, 9 - x, 8 - x)", 0),
     # ---- helpers for sampled rows and columns of large cases
     "rows_dq_scale_dropped": ("dq[sel] = scale * (dS @ K)", "dq[sel] = (dS @ K)", 0),
     "rows_delta_dropped": ("dS = P * (dP - delta)\n        dq[sel]", "dS = P * dP\n        dq[sel]", 0),

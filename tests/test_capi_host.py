@@ -183,29 +183,31 @@ def test_temporal_attention_argument_errors(lib):
 
 def test_fp8_argument_errors(lib):
     arr, cu = _i32([0, 100, 100, 165])
-    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
-    assert lib.vfm_fp8_pack_sizes(cu, 3, 165, 4, 128, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 0
+    a, b, c, d = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    refs = (ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(d))
+    assert lib.vfm_fp8_pack_sizes(cu, 3, 165, 4, 128, *refs) == 0
     # units: ceil(100/64) + 0 + ceil(65/64) = 4
     assert a.value == 165 * 4 * 128 and b.value == 4 * 4 * 64 * 128 and c.value == b.value
-    assert lib.vfm_fp8_pack_sizes(cu, 3, 166, 4, 128, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 3
-    assert lib.vfm_fp8_pack_sizes(cu, 3, 165, 4, 96, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 2
-    assert lib.vfm_fp8_pack_sizes(cu, 3, 165, 4, 128, None, ctypes.byref(b), ctypes.byref(c)) == 1
+    assert d.value == 768 + 4 * 4 * 4          # 660 q-row bytes padded to 768, then one word per (head, unit)
+    assert lib.vfm_fp8_pack_sizes(cu, 3, 166, 4, 128, *refs) == 3
+    assert lib.vfm_fp8_pack_sizes(cu, 3, 165, 4, 96, *refs) == 2
+    assert lib.vfm_fp8_pack_sizes(cu, 3, 165, 4, 128, None, *refs[1:]) == 1
     many, pm = _i32([0] * 300)
-    assert lib.vfm_fp8_pack_sizes(pm, 299, 0, 4, 128, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)) == 2
+    assert lib.vfm_fp8_pack_sizes(pm, 299, 0, 4, 128, *refs) == 0            # more clips than one table holds: legal
 
-    def pack(q=FAKE, qs=32.0, q8=FAKE, dt=0):
-        return lib.vfm_fp8_pack(q, FAKE, FAKE, cu, 3, 165, 4, 128, qs, 1.0, 16.0, q8, FAKE, FAKE, dt, None)
+    def pack(q=FAKE, scale=0.09, q8=FAKE, scales=FAKE, dt=0):
+        return lib.vfm_fp8_pack(q, FAKE, FAKE, cu, 3, 165, 4, 128, scale, q8, FAKE, FAKE, scales, dt, None)
     assert pack(q=None) == 1
-    assert pack(qs=0.0) == 2
-    assert pack(qs=float("inf")) == 2
+    assert pack(scales=None) == 1
+    assert pack(scale=0.0) == 2
+    assert pack(scale=float("inf")) == 2
     assert pack(dt=1) == 6
     assert pack(q8=ODD) == 9
 
-    def fwd(q8=FAKE, vs=16.0, lse=FAKE):
-        return lib.vfm_attn_fwd_fp8(q8, FAKE, FAKE, cu, 3, 165, 4, 128, vs, FAKE, lse, None)
+    def fwd(q8=FAKE, scales=FAKE, lse=FAKE):
+        return lib.vfm_attn_fwd_fp8(q8, FAKE, FAKE, scales, cu, 3, 165, 4, 128, FAKE, lse, None)
     assert fwd(lse=None) == 1
-    assert fwd(vs=-1.0) == 2
-    assert fwd(vs=0.0) == 2
+    assert fwd(scales=None) == 1
     assert fwd(q8=ODD) == 9
 
 

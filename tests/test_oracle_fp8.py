@@ -44,3 +44,34 @@ def test_encode_is_nearest():
     grid = np.concatenate([-grid[::-1], grid])
     best = np.min(np.abs(np.clip(x, -448, 448)[:, None] - grid[None, :]), axis=1)
     np.testing.assert_allclose(np.abs(np.clip(x, -448, 448) - q), best, rtol=0, atol=0)
+
+
+# ---------------------------------------------------------- per-tile power-of-two scales
+def test_tile_exponent_is_the_largest_that_fits_by_brute_force():
+    rng = np.random.default_rng(5)
+    amax = np.concatenate([np.abs(rng.standard_normal(200)) * 10.0 ** rng.integers(-6, 7, 200),
+                           [448.0, 448.0 * 2 ** -5, 448.0 * 2 ** 7, np.nextafter(448.0, 1e9), np.nextafter(448.0, 0.0),
+                            224.0, 1.0, 1.75, np.nextafter(1.75, 2.0), 3.5e-5]])
+    got = orc.fp8_tile_exponent(amax)
+    for a, e in zip(amax, got):
+        fits = [k for k in range(-130, 131) if a * 2.0 ** k <= 448.0]      # plain search
+        assert int(e) == max(fits), (a, e)
+        assert a * 2.0 ** int(e) > 224.0                                  # the top binade of E4M3 is used
+
+
+def test_tile_exponent_special_cases():
+    assert orc.fp8_tile_exponent(0.0) == 0
+    assert orc.fp8_tile_exponent(448.0) == 0 and orc.fp8_tile_exponent(449.0) == -1
+    assert orc.fp8_tile_exponent(1e-60) == 120 and orc.fp8_tile_exponent(1e60) == -120
+    assert orc.fp8_tile_exponent(-3.0) == orc.fp8_tile_exponent(3.0) == 7    # 3 * 128 = 384 <= 448 < 768
+
+
+def test_scaled_tile_round_trip_error_is_relative_to_the_tile():
+    # storing x * 2**e and reading decode * 2**-e: error at most half an E4M3 step of the top binade,
+    # 2**-4 of the tile's largest magnitude, however small or large the tile's values are
+    rng = np.random.default_rng(6)
+    for mag in (1e-4, 1.0, 3e4):
+        x = rng.standard_normal(4096) * mag
+        e = int(orc.fp8_tile_exponent(np.abs(x).max()))
+        back = orc.fp8_e4m3_decode(orc.fp8_e4m3_encode(x * 2.0 ** e)) * 2.0 ** -e
+        assert np.max(np.abs(back - x)) <= 2.0 ** -4 * np.abs(x).max()
