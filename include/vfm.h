@@ -57,7 +57,6 @@ extern "C" {
 
 #define VFM_MAX_SEQS 256    /* clips per launch (run), self-attention, RoPE, temporal attention */
 #define VFM_MAX_XSEQS 128   /* sequences per launch (run), cross-attention */
-#define VFM_MAX_TEMPORAL 32 /* latent frames per clip, temporal attention */
 #define VFM_NOALLOC_MAX_ROWS (1 << 21) /* n_heads * total_tokens, vfm_attn_bwd_noalloc */
 
 #define VFM_API __attribute__((visibility("default")))
@@ -264,8 +263,11 @@ VFM_API int vfm_xattn_bwd(const void* q, const void* k, const void* v, const voi
  * read as [(b*h*w), t, d].  For clip s with grid (T,H,W) = thw[3s..3s+2] and
  * pixel p < H*W the sequence is the T rows cu_seqlens[s] + t*H*W + p; per head
  *     out_i = sum_j softmax_j(scale * q_i . k_j) v_j       i, j over the T frames.
- * T <= VFM_MAX_TEMPORAL (THW otherwise).  q, k, v, out: bf16 [total_tokens,
- * n_heads, head_dim]; thw, cu_seqlens: host.  No statistics are saved.
+ * Any T >= 1 (the section speaks of hundreds of frames): up to 32 frames a
+ * sequence is one register tile and the call is bound by HBM; a call (run of
+ * clips) in which some clip has more is walked in 32-frame blocks with an
+ * online softmax.  q, k, v, out: bf16 [total_tokens, n_heads, head_dim]; thw,
+ * cu_seqlens: host.  No statistics are saved.
  * Errors: NULL, SHAPE, CU_SEQLENS, THW, DTYPE, ALIGN, LAUNCH.
  */
 VFM_API int vfm_tattn_fwd(const void* q, const void* k, const void* v,
@@ -276,7 +278,9 @@ VFM_API int vfm_tattn_fwd(const void* q, const void* k, const void* v,
 /*
  * Temporal attention backward: dq, dk, dv (bf16, fully overwritten) from dout.
  * The softmax is recomputed from q and k; Delta_i = sum_j P_ij (dout_i . v_j).
- * Every output is written once, no atomics, no workspace.
+ * No atomics, no workspace; every output is written once, except that with clips
+ * of more than 32 frames the first 8 bytes of every dq row hold that query's
+ * softmax statistics while the call runs, before dq is written over them.
  * Errors: NULL, SHAPE, CU_SEQLENS, THW, DTYPE, ALIGN, LAUNCH.
  */
 VFM_API int vfm_tattn_bwd(const void* q, const void* k, const void* v, const void* dout,

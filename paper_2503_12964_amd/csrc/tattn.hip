@@ -1,7 +1,8 @@
 // Temporal attention for gfx950: one sequence per (clip, pixel) made of that pixel's token
-// in every latent frame (T <= 32 rows, H*W tokens apart in the packed buffer), per head.
-// HBM-bound: the whole problem of one (pixel, head) is a 16 x 16 score tile (a 32 x 32 one,
-// further down, when a clip has more than 16 frames).
+// in every latent frame (T rows, H*W tokens apart in the packed buffer), per head.
+// HBM-bound up to 32 frames: the whole problem of one (pixel, head) is a 16 x 16 score tile (a
+// 32 x 32 one, further down, when a clip has more than 16 frames).  Clips with more than 32
+// frames are walked in 32-row blocks by the kernels at the end of the file.
 //
 // One wavefront owns one (pixel, head).  It gathers the T rows of q, k, v (and dout) into a
 // wave-private LDS tile with direct global->LDS loads (16-byte chunks, 256-byte rows, the same
@@ -515,6 +516,395 @@ __global__ __launch_bounds__(kTWaves * 64) void tattn32_bwd_kernel(const __bf16*
   }
 }
 
+// ---------------------------------------------------------------- more than 32 frames
+// Section 4.6 speaks of videos of hundreds of frames.  For clips with T > 32 a wavefront owns one
+// 32-row block of one (pixel, head) sequence and walks the sequence's other side in blocks of 32
+// with the online softmax of the packed kernels (running reference m, running sum l, rescaled
+// accumulators), on the 32 x 32 tiles, lane layouts and LDS helpers of the 17..32-frame kernels.
+// Blocks of one sequence are consecutive work units, so the wavefronts that re-read a
+// sequence's K/V (or Q/dO) rows run together and find them in cache.
+// The backward still takes no workspace: a first kernel writes each query's statistics (lse in
+// log2 units and Delta_i = sum_j P_ij dP_ij, two floats) into the first 8 bytes of that query's
+// dq row, the dK/dV kernel reads them from there, and the dQ kernel reads its own rows'
+// statistics before it overwrites those rows with dq.
+namespace {
+
+struct LUnit {
+  TUnit u;
+  int blk;      // 32-row block of the sequence this wavefront owns
+  int n_blk;    // blocks of the sequence
+};
+
+__device__ __forceinline__ bool long_unit(const TemporalLTable& tab, int n_heads, LUnit& w) {
+  const long long unit = (long long)blockIdx.x * kTWaves + (threadIdx.x >> 6);
+  if (unit >= (long long)tab.blk_cu[tab.n] * n_heads) return false;
+  int lo = 0, hi = tab.n;            // last clip s with blk_cu[s] * n_heads <= unit (skips empty clips)
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if ((long long)tab.blk_cu[mid] * n_heads <= unit) lo = mid; else hi = mid;
+  }
+  const int hw = tab.hw[lo];
+  const int T = (tab.cu[lo + 1] - tab.cu[lo]) / hw;
+  const int nb = (T + kT2Rows - 1) / kT2Rows;
+  const long long local = unit - (long long)tab.blk_cu[lo] * n_heads;   // ((pixel * heads + head) * nb + block)
+  w.blk = (int)(local % nb);
+  w.n_blk = nb;
+  const long long ph = local / nb;
+  w.u.head = (int)(ph % n_heads);
+  w.u.hw = hw;
+  w.u.T = T;
+  w.u.first_row = tab.cu[lo] + (int)(ph / n_heads);
+  return true;
+}
+
+// Rows 32*blk .. 32*blk + 31 of the sequence (clamped to its last row) into a swizzled [32][D] tile.
+template <int D>
+__device__ __forceinline__ void gather_block(const __bf16* base, const TUnit& u, int blk, uint32_t row_bytes,
+                                             uint32_t lds_tile, int lane) {
+  using Cfg = T2Cfg<D>;
+#pragma unroll
+  for (int x = 0; x < Cfg::kLoadsPerTile; ++x) {
+    const int p = x * 64 + lane;
+    const int r = p / Cfg::kChunksPerRow;
+    const int chunk = (p % Cfg::kChunksPerRow) ^ swz<D>(r);
+    const uint32_t off = (uint32_t)(u.first_row + min(blk * kT2Rows + r, u.T - 1) * u.hw) * row_bytes +
+                         (uint32_t)(u.head * D * 2 + chunk * 16);
+    lds_dma16(base, off, lds_tile + x * 1024);
+  }
+}
+
+// Row operands of block blk straight from global memory: lane l holds row 32*blk + l%32 (clamped),
+// columns ks*16 + 8*(l/32)..+7.
+template <int D>
+__device__ __forceinline__ void load_rows_global(const __bf16* base, const TUnit& u, int blk, size_t row_stride,
+                                                 int lane, bf16x8 (&f)[D / 16]) {
+  const size_t row = (size_t)(u.first_row + min(blk * kT2Rows + (lane & 31), u.T - 1) * u.hw);
+  const __bf16* p = base + row * row_stride + (size_t)u.head * D + 8 * (lane >> 5);
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) f[ks] = *reinterpret_cast<const bf16x8*>(p + ks * 16);
+}
+
+// Store an accumulator tile as rows 32*blk + l%32 of the sequence.
+template <int D>
+__device__ __forceinline__ void store_block(__bf16* base, const TUnit& u, int blk, size_t row_stride, int lane,
+                                            int db, const f32x16& c, float mul) {
+  const int t = blk * kT2Rows + (lane & 31);
+  if (t < u.T) {
+    __bf16* p = base + (size_t)(u.first_row + t * u.hw) * row_stride + (size_t)u.head * D + db * 32 + 4 * (lane >> 5);
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      f32x4 o = {c[4 * q4] * mul, c[4 * q4 + 1] * mul, c[4 * q4 + 2] * mul, c[4 * q4 + 3] * mul};
+      *reinterpret_cast<bf16x4*>(p + 8 * q4) = to_bf16x4(o);
+    }
+  }
+}
+
+// The two statistics of query t of the sequence live in the first 8 bytes of its dq row.
+template <int D>
+__device__ __forceinline__ float* stat_slot(__bf16* dq, const TUnit& u, int t, size_t row_stride) {
+  return reinterpret_cast<float*>(dq + (size_t)(u.first_row + t * u.hw) * row_stride + (size_t)u.head * D);
+}
+
+constexpr f32x16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+}  // namespace
+
+// STATS = false: out.  STATS = true (first backward kernel): the queries' statistics into dq rows;
+// `v` then also feeds dP^T = V dO^T and `dout` must be given.
+template <int D, bool STATS>
+__global__ __launch_bounds__(kTWaves * 64) void tattnL_fwd_kernel(const __bf16* __restrict__ q,
+                                                                  const __bf16* __restrict__ k,
+                                                                  const __bf16* __restrict__ v,
+                                                                  const __bf16* __restrict__ dout,
+                                                                  __bf16* __restrict__ out,   // out, or dq (statistics)
+                                                                  const TemporalLTable tab, int n_heads,
+                                                                  float scale_log2) {
+  using Cfg = T2Cfg<D>;
+  constexpr int TB = Cfg::kTileBytes;
+  constexpr int KS = D / 16, DB = D / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  LUnit w;
+  if (!long_unit(tab, n_heads, w)) return;   // whole wavefronts leave; there are no barriers
+  const TUnit& u = w.u;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
+  const size_t row_stride = (size_t)n_heads * D;
+  const uint32_t row_bytes = (uint32_t)row_stride * 2u;
+  char* kt = smem + wave * 2 * TB;
+  char* vt = kt + TB;
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(kt));
+
+  bf16x8 qf[KS], df[KS];
+  load_rows_global<D>(q, u, w.blk, row_stride, lane, qf);
+  if constexpr (STATS) load_rows_global<D>(dout, u, w.blk, row_stride, lane, df);
+  float m = -INFINITY, l = 0.f, dnum = 0.f;   // running reference (log2 units), sum, and sum of e^{s-m} dP
+  f32x16 oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) oacc[db] = kZero16;
+
+  for (int kb = 0; kb < w.n_blk; ++kb) {
+    gather_block<D>(k, u, kb, row_bytes, lds0, lane);
+    gather_block<D>(v, u, kb, row_bytes, lds0 + TB, lane);
+    wait_vmcnt<0>();
+    bf16x8 kf[KS];
+    read_rows32<D>(kt, lane, kf);
+    f32x16 st = kZero16;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) st = mfma32(kf[ks], qf[ks], st);
+    // lane: query l%32 of the block; register r: key 32*kb + 8*(r/4) + 4g + r%4
+    float mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      if (kb * kT2Rows + 8 * (r >> 2) + 4 * g + (r & 3) >= u.T) st[r] = -INFINITY;
+      mx = fmaxf(mx, st[r]);
+    }
+    const float m_new = fmaxf(m, pair_max(mx) * scale_log2);   // every block has a valid key, so m_new is finite
+    const float alpha = fast_exp2(m - m_new);                  // 0 for the first block (m = -inf)
+    f32x16 p;
+    float sum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      p[r] = fast_exp2(st[r] * scale_log2 - m_new);
+      sum += p[r];
+    }
+    l = l * alpha + sum;       // (per lane: this lane's half of the keys; halves are added at the end)
+    m = m_new;
+    if constexpr (STATS) {
+      bf16x8 vf[KS];
+      read_rows32<D>(vt, lane, vf);
+      f32x16 dp = kZero16;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) dp = mfma32(vf[ks], df[ks], dp);
+      float dsum = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) dsum += p[r] * dp[r];      // p is 0 for masked keys
+      dnum = dnum * alpha + dsum;
+    } else {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+      const bf16x8 pb0 = half_to_bf16(p, 0), pb1 = half_to_bf16(p, 1);
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        oacc[db] = mfma32(read_tr32<D>(vt, lane, db, 0), pb0, oacc[db]);
+        oacc[db] = mfma32(read_tr32<D>(vt, lane, db, 1), pb1, oacc[db]);
+      }
+    }
+    // the tiles are overwritten by the next block's loads: every read above must have completed
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  }
+  const float l_tot = pair_sum(l);
+  if constexpr (STATS) {
+    const float d_tot = pair_sum(dnum);       // (both halves of the wavefront take part in the exchange)
+    const int t = w.blk * kT2Rows + (lane & 31);
+    if (t < u.T && g == 0) {
+      float* slot = stat_slot<D>(out, u, t, row_stride);
+      slot[0] = m + __log2f(l_tot);           // P = exp2(s * scale_log2 - slot[0])
+      slot[1] = d_tot / l_tot;                // Delta
+    }
+  } else {
+    const float inv = 1.0f / l_tot;
+#pragma unroll
+    for (int db = 0; db < DB; ++db) store_block<D>(out, u, w.blk, row_stride, lane, db, oacc[db], inv);
+  }
+}
+
+// dK, dV of one 32-key block: walks the sequence's query blocks.
+template <int D>
+__global__ __launch_bounds__(kTWaves * 64) void tattnL_dkdv_kernel(const __bf16* __restrict__ q,
+                                                                   const __bf16* __restrict__ k,
+                                                                   const __bf16* __restrict__ v,
+                                                                   const __bf16* __restrict__ dout,
+                                                                   __bf16* __restrict__ dq,   // statistics (read only here)
+                                                                   __bf16* __restrict__ dk, __bf16* __restrict__ dv,
+                                                                   const TemporalLTable tab, int n_heads,
+                                                                   float scale, float scale_log2) {
+  using Cfg = T2Cfg<D>;
+  constexpr int TB = Cfg::kTileBytes;
+  constexpr int KS = D / 16, DB = D / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  LUnit w;
+  if (!long_unit(tab, n_heads, w)) return;
+  const TUnit& u = w.u;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
+  const size_t row_stride = (size_t)n_heads * D;
+  const uint32_t row_bytes = (uint32_t)row_stride * 2u;
+  char* qt = smem + wave * 2 * TB;
+  char* dot = qt + TB;
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(qt));
+
+  bf16x8 kf[KS], vf[KS];     // this block's key and value rows: lane = key
+  load_rows_global<D>(k, u, w.blk, row_stride, lane, kf);
+  load_rows_global<D>(v, u, w.blk, row_stride, lane, vf);
+  f32x16 dkacc[DB], dvacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) { dkacc[db] = kZero16; dvacc[db] = kZero16; }
+
+  for (int qb = 0; qb < w.n_blk; ++qb) {
+    gather_block<D>(q, u, qb, row_bytes, lds0, lane);
+    gather_block<D>(dout, u, qb, row_bytes, lds0 + TB, lane);
+    // statistics of query 32*qb + l%32 (rows past the end: any finite value, their P is zeroed below)
+    const int tq = min(qb * kT2Rows + (lane & 31), u.T - 1);
+    const float* slot = stat_slot<D>(dq, u, tq, row_stride);
+    const float lse2 = slot[0], delta = slot[1];
+    wait_vmcnt<0>();
+    bf16x8 qf[KS], df[KS];
+    read_rows32<D>(qt, lane, qf);
+    read_rows32<D>(dot, lane, df);
+    // lane = key of this block, register r = query 32*qb + 8*(r/4) + 4g + r%4
+    f32x16 sB = kZero16, dpB = kZero16;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      sB = mfma32(qf[ks], kf[ks], sB);
+      dpB = mfma32(df[ks], vf[ks], dpB);
+    }
+    f32x16 pB, dsB;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int i = 8 * (r >> 2) + 4 * g + (r & 3);
+      const float l2 = __shfl(lse2, i);
+      const float dd = __shfl(delta, i);
+      const float pv = (qb * kT2Rows + i < u.T) ? fast_exp2(sB[r] * scale_log2 - l2) : 0.f;   // padded queries add nothing
+      pB[r] = pv;
+      dsB[r] = pv * (dpB[r] - dd);
+    }
+    const bf16x8 p0 = half_to_bf16(pB, 0), p1 = half_to_bf16(pB, 1);
+    const bf16x8 s0 = half_to_bf16(dsB, 0), s1 = half_to_bf16(dsB, 1);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      // dV^T[d, j] += sum_i dO[i, d] P[i, j];  dK^T[d, j] += sum_i Q[i, d] dS[i, j]
+      dvacc[db] = mfma32(read_tr32<D>(dot, lane, db, 0), p0, dvacc[db]);
+      dvacc[db] = mfma32(read_tr32<D>(dot, lane, db, 1), p1, dvacc[db]);
+      dkacc[db] = mfma32(read_tr32<D>(qt, lane, db, 0), s0, dkacc[db]);
+      dkacc[db] = mfma32(read_tr32<D>(qt, lane, db, 1), s1, dkacc[db]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  }
+  // keys past the end of the sequence (last block) are never stored
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    store_block<D>(dk, u, w.blk, row_stride, lane, db, dkacc[db], scale);
+    store_block<D>(dv, u, w.blk, row_stride, lane, db, dvacc[db], 1.0f);
+  }
+}
+
+// dQ of one 32-query block: reads the block's statistics from its dq rows, walks the key blocks,
+// then overwrites the rows.
+template <int D>
+__global__ __launch_bounds__(kTWaves * 64) void tattnL_dq_kernel(const __bf16* __restrict__ q,
+                                                                 const __bf16* __restrict__ k,
+                                                                 const __bf16* __restrict__ v,
+                                                                 const __bf16* __restrict__ dout,
+                                                                 __bf16* __restrict__ dq,
+                                                                 const TemporalLTable tab, int n_heads,
+                                                                 float scale, float scale_log2) {
+  using Cfg = T2Cfg<D>;
+  constexpr int TB = Cfg::kTileBytes;
+  constexpr int KS = D / 16, DB = D / 32;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  LUnit w;
+  if (!long_unit(tab, n_heads, w)) return;
+  const TUnit& u = w.u;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, g = lane >> 5;
+  const size_t row_stride = (size_t)n_heads * D;
+  const uint32_t row_bytes = (uint32_t)row_stride * 2u;
+  char* kt = smem + wave * 2 * TB;
+  char* vt = kt + TB;
+  const uint32_t lds0 = __builtin_amdgcn_readfirstlane(lds_addr_of(kt));
+
+  bf16x8 qf[KS], df[KS];     // lane = query
+  load_rows_global<D>(q, u, w.blk, row_stride, lane, qf);
+  load_rows_global<D>(dout, u, w.blk, row_stride, lane, df);
+  const float* slot = stat_slot<D>(dq, u, min(w.blk * kT2Rows + (lane & 31), u.T - 1), row_stride);
+  const float lse2 = slot[0], delta = slot[1];
+  f32x16 dqacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) dqacc[db] = kZero16;
+
+  for (int kb = 0; kb < w.n_blk; ++kb) {
+    gather_block<D>(k, u, kb, row_bytes, lds0, lane);
+    gather_block<D>(v, u, kb, row_bytes, lds0 + TB, lane);
+    wait_vmcnt<0>();
+    bf16x8 kf[KS], vf[KS];
+    read_rows32<D>(kt, lane, kf);
+    read_rows32<D>(vt, lane, vf);
+    f32x16 sA = kZero16, dpA = kZero16;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      sA = mfma32(kf[ks], qf[ks], sA);
+      dpA = mfma32(vf[ks], df[ks], dpA);
+    }
+    f32x16 dsA;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const bool live = kb * kT2Rows + 8 * (r >> 2) + 4 * g + (r & 3) < u.T;
+      const float pv = live ? fast_exp2(sA[r] * scale_log2 - lse2) : 0.f;
+      dsA[r] = pv * (dpA[r] - delta);
+    }
+    const bf16x8 d0 = half_to_bf16(dsA, 0), d1 = half_to_bf16(dsA, 1);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {   // dQ^T[d, i] += sum_j K[j, d] dS^T[j, i]
+      dqacc[db] = mfma32(read_tr32<D>(kt, lane, db, 0), d0, dqacc[db]);
+      dqacc[db] = mfma32(read_tr32<D>(kt, lane, db, 1), d1, dqacc[db]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  }
+#pragma unroll
+  for (int db = 0; db < DB; ++db) store_block<D>(dq, u, w.blk, row_stride, lane, db, dqacc[db], scale);
+}
+
+// Some clip of the run has more than 32 frames: the block-walking kernels serve the whole run.
+template <int D>
+static hipError_t launch_long(const void* q, const void* k, const void* v, const void* dout,
+                              const TemporalTable& tab, int n_heads, float scale, void* o0, void* o1,
+                              void* o2, hipStream_t stream) {
+  TemporalLTable lt;
+  lt.n = tab.n;
+  int blocks = 0;
+  for (int s = 0; s <= VFM_MAX_SEQS; ++s) {
+    lt.cu[s] = tab.cu[s];
+    lt.blk_cu[s] = blocks;
+    if (s < VFM_MAX_SEQS) {
+      lt.hw[s] = tab.hw[s];
+      if (s < tab.n && tab.cu[s + 1] > tab.cu[s]) {
+        const int T = (tab.cu[s + 1] - tab.cu[s]) / tab.hw[s];
+        blocks += tab.hw[s] * ((T + kT2Rows - 1) / kT2Rows);
+      }
+    }
+  }
+  const long long n_units = (long long)blocks * n_heads;
+  if (n_units == 0) return hipSuccess;
+  const dim3 grid((unsigned)((n_units + kTWaves - 1) / kTWaves)), block(kTWaves * 64);
+  constexpr int lds = kTWaves * 2 * T2Cfg<D>::kTileBytes;
+  const __bf16 *qb = (const __bf16*)q, *kb = (const __bf16*)k, *vb = (const __bf16*)v, *dob = (const __bf16*)dout;
+  const float scale_log2 = scale * kLog2eT;
+  hipError_t e;
+  if (!dout) {
+    auto kern = tattnL_fwd_kernel<D, false>;
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    return launch(kern, grid, block, lds, stream, qb, kb, vb, dob, (__bf16*)o0, lt, n_heads, scale_log2);
+  }
+  auto stats = tattnL_fwd_kernel<D, true>;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(stats), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e != hipSuccess) return e;
+  e = launch(stats, grid, block, lds, stream, qb, kb, vb, dob, (__bf16*)o0, lt, n_heads, scale_log2);   // o0 = dq
+  if (e != hipSuccess) return e;
+  auto dkdv = tattnL_dkdv_kernel<D>;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(dkdv), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e != hipSuccess) return e;
+  e = launch(dkdv, grid, block, lds, stream, qb, kb, vb, dob, (__bf16*)o0, (__bf16*)o1, (__bf16*)o2, lt, n_heads, scale,
+             scale_log2);
+  if (e != hipSuccess) return e;
+  auto dqk = tattnL_dq_kernel<D>;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(dqk), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e != hipSuccess) return e;
+  return launch(dqk, grid, block, lds, stream, qb, kb, vb, dob, (__bf16*)o0, lt, n_heads, scale, scale_log2);
+}
+
 template <int D>
 static hipError_t launch_t(const void* q, const void* k, const void* v, const void* dout,
                            const TemporalTable& tab, int n_heads, float scale, void* o0, void* o1,
@@ -524,6 +914,7 @@ static hipError_t launch_t(const void* q, const void* k, const void* v, const vo
   int max_t = 0;
   for (int s = 0; s < tab.n; ++s)
     if (tab.hw[s] > 0) max_t = std::max(max_t, (tab.cu[s + 1] - tab.cu[s]) / tab.hw[s]);
+  if (max_t > kT2Rows) return launch_long<D>(q, k, v, dout, tab, n_heads, scale, o0, o1, o2, stream);
   const bool big = max_t > kTRows;     // some clip has more than 16 frames: 32-row tiles for the call
   const int grid = (int)((n_units + kTWaves - 1) / kTWaves);
   const int tiles = dout ? 4 : 3;

@@ -249,7 +249,7 @@ const char* vfm_strerror(int status) {
     case VFM_ERR_NULL: return "a required pointer is NULL";
     case VFM_ERR_SHAPE: return "total_tokens, n_heads, head_dim (64 or 128), a tensor beyond 4 GiB, scale or theta (> 0, finite) or eps (>= 0) out of range, or dx aliases x";
     case VFM_ERR_CU_SEQLENS: return "cu_seqlens must start at 0, be non-decreasing and end at total_tokens";
-    case VFM_ERR_THW: return "each clip needs positive T, H, W with T*H*W equal to its length (temporal attention: T <= 32)";
+    case VFM_ERR_THW: return "each clip needs positive T, H, W with T*H*W equal to its length";
     case VFM_ERR_SPLIT: return "dim_t + dim_h + dim_w must equal head_dim, each part even and >= 0";
     case VFM_ERR_DTYPE: return "unsupported element type (only bf16)";
     case VFM_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or smaller than vfm_attn_bwd_workspace_size()";
@@ -571,7 +571,7 @@ int vfm_tattn_fwd(const void* q, const void* k, const void* v, const int32_t* th
   if (st) return st;
   if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
   st = check_cu(cu_seqlens, n_seqs, total_tokens);
-  if (!st) st = check_grids(thw, cu_seqlens, n_seqs, VFM_MAX_TEMPORAL);
+  if (!st) st = check_grids(thw, cu_seqlens, n_seqs, 0);
   if (st) return st;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return VFM_ERR_ALIGN;
   for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_SEQS) {
@@ -593,7 +593,7 @@ int vfm_tattn_bwd(const void* q, const void* k, const void* v, const void* dout,
   if (st) return st;
   if (!(scale > 0.f) || !isfinite(scale)) return VFM_ERR_SHAPE;
   st = check_cu(cu_seqlens, n_seqs, total_tokens);
-  if (!st) st = check_grids(thw, cu_seqlens, n_seqs, VFM_MAX_TEMPORAL);
+  if (!st) st = check_grids(thw, cu_seqlens, n_seqs, 0);
   if (st) return st;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(dout) || !aligned16(dq) ||
       !aligned16(dk) || !aligned16(dv))

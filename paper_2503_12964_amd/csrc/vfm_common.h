@@ -84,6 +84,15 @@ struct TemporalTable {
   int hw[VFM_MAX_SEQS];          // H*W of clip s (1 for an empty clip)
 };
 
+// The same clips for the temporal kernels that walk sequences of more than 32 frames in
+// 32-row blocks: a work unit is one block of one (pixel, head) sequence.
+struct TemporalLTable {
+  int n;
+  int cu[VFM_MAX_SEQS + 1];      // first packed token of clip s
+  int blk_cu[VFM_MAX_SEQS + 1];  // (pixel, block) pairs of the clips before s: sum of H*W * ceil(T / 32)
+  int hw[VFM_MAX_SEQS];          // H*W of clip s (1 for an empty clip)
+};
+
 // Work unit u = head * tiles_per_head + tile, units split into kNumXcd
 // contiguous chunks so that one XCD (one L2) walks the tiles of one head
 // together.  Returns false if this workgroup has nothing to do.

@@ -85,6 +85,9 @@ WORKLOADS = {
                    24, 128, (32, 48, 48), seed=2),
     # 720p-class 121-frame latent (headline)
     "C4": Workload("C4", ((16, 44, 80),), 32, 128, (32, 48, 48), seed=3),
+    # a long video for temporal attention only (Section 4.6: hundreds of frames): 64 latent frames of the
+    # 720p-class grid, 8 heads (bench.py --workload L64-temporal)
+    "L64": Workload("L64", ((64, 44, 80),), 8, 128, (32, 48, 48), seed=5),
     # 1080p-class latent, inference denoising step (forward only)
     "C5": Workload("C5", ((16, 68, 120),), 40, 128, (32, 48, 48), seed=4, backward=False),
 }

@@ -168,7 +168,7 @@ def test_temporal_attention_argument_errors(lib):
         b, pb = _i32(cu)
         return lib.vfm_tattn_fwd(q, FAKE, FAKE, pa, pb, len(cu) - 1, total, 2, 128, scale, out, dt, None)
     assert tf([2, 2, 2], [0, 8], 8, out=None) == 1
-    assert tf([33, 1, 1], [0, 33], 33) == 4                     # more than VFM_MAX_TEMPORAL frames
+    assert tf([33, 1, 1], [0, 32], 32) == 4                     # grid and length disagree
     assert tf([2, 2, 3], [0, 8], 8) == 4
     assert tf([2, 2, 2], [0, 9], 8) == 3
     assert tf([2, 2, 2], [0, 8], 8, dt=1) == 6

@@ -72,12 +72,40 @@ def test_single_frame_clip_copies_values_and_has_zero_qk_gradients():
     assert np.array_equal(U.to_bits(dv[a:b]), U.to_bits(dev["dout"][a:b]))
 
 
-def test_more_than_thirty_two_frames_is_an_error():
+LONG = {
+    # more than 32 frames (Section 4.6: videos of hundreds of frames): 33, 48, 121 frames, block
+    # multiples (64, 96) and short clips, an empty and a single-frame one in the same call
+    "t128_33_48": W.Workload("t128_33_48", ((33, 2, 3), (48, 1, 5), (4, 3, 3), (0, 1, 1), (1, 2, 2), (64, 1, 2)), 3, 128,
+                             (32, 48, 48), seed=35),
+    "t128_121": W.Workload("t128_121", ((121, 3, 2), (96, 1, 1), (17, 2, 2)), 2, 128, (32, 48, 48), seed=36),
+    "t64_long": W.Workload("t64_100", ((100, 2, 2), (33, 1, 3), (65, 1, 1), (2, 2, 2)), 2, 64, (16, 24, 24), seed=37),
+    "t128_300": W.Workload("t128_300", ((300, 1, 2),), 1, 128, (32, 48, 48), seed=38),
+}
+
+
+@pytest.mark.parametrize("name", list(LONG))
+def test_more_than_thirty_two_frames(name):
+    wl = LONG[name]
+    dev, gpu = _run(_binding(), wl)
+    _check(wl, gpu, dev)
+
+
+def test_long_clip_statistics_do_not_leak_into_dq():
+    # with more than 32 frames the dq rows carry the queries' statistics while the call runs; afterwards
+    # every dq element is a gradient, also after a second call into the same buffers
     import torch
+    wl = LONG["t128_33_48"]
     b = _binding()
-    x = torch.zeros((33 * 4, 1, 64), dtype=torch.bfloat16, device="cuda")
-    with pytest.raises(b.VfmError):
-        b.vfm_tattn_fwd(x, x, x, [(33, 2, 2)], [0, 132], 0.125)
+    inp = W.make_inputs(wl)
+    dev = {n: U.to_device(inp[n]) for n in ("q", "k", "v", "dout")}
+    dq, dk, dv = (torch.full_like(dev["q"], float("nan")) for _ in range(3))
+    for _ in range(2):
+        b.vfm_tattn_bwd(dev["q"], dev["k"], dev["v"], dev["dout"], wl.thw, wl.cu_seqlens, wl.scale, dq=dq, dk=dk, dv=dv)
+    host = {n: U.to_f64(t) for n, t in dev.items()}
+    g_ref = orc.temporal_attn_bwd(host["q"], host["k"], host["v"], host["dout"], wl.thw, wl.cu_seqlens, wl.scale)
+    for nm, g, ref in zip(("dq", "dk", "dv"), (dq, dk, dv), g_ref):
+        assert U.rel_rms(U.to_f64(g), ref) <= U.TOL_GRAD_RELRMS, nm
+        U.assert_rows_close(nm, U.to_f64(g), ref, U.TOL_GRAD_RELRMS)
 
 
 def test_single_frame_clip_in_a_long_call():
