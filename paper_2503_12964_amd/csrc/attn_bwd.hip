@@ -20,6 +20,7 @@
 //                     dQ^T += K^T dS^T                     (A = transposing reads of the K tile)
 //                 S and dP are recomputed here (7 GEMMs in total instead of 5).
 #include <algorithm>
+#include <atomic>
 
 #include "vfm_common.h"
 
@@ -1077,6 +1078,19 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
   }
 }
 
+// Compute units of the current device (asked once; 256 on MI355X, also the fallback).
+static int compute_unit_count() {
+  static std::atomic<int> cached{0};
+  int n = cached.load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+    n = 256;
+  cached.store(n, std::memory_order_relaxed);
+  return n;
+}
+
 template <int D, class Segs>
 static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, const void* out,
                                const float* lse, const void* dout, const Segs& segs, int total,
@@ -1102,10 +1116,11 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
     UnitMap um = make_unit_map(tiles, n_heads);
     // Few key tiles and long query ranges (cross-attention): split the queries over workgroups.
     int q_split = 1;
-    if (dkv32 && tiles * n_heads < 256) {
+    const int cus = compute_unit_count();
+    if (dkv32 && tiles * n_heads < cus) {
       int max_q = 0;
       for (int s2 = 0; s2 < segs.n; ++s2) max_q = std::max(max_q, segs.q_len(s2));
-      q_split = std::min(std::min(16, (256 + tiles * n_heads - 1) / (tiles * n_heads)), std::max(1, max_q / 512));
+      q_split = std::min(std::min(16, (cus + tiles * n_heads - 1) / (tiles * n_heads)), std::max(1, max_q / 512));
     }
     if (q_split > 1) {
       // the accumulators and the conversion cover this run's key rows [kv_lo, kv_hi) only:

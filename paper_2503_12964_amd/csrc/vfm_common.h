@@ -23,7 +23,10 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kNumXcd = 8;  // MI355X: 8 XCDs, workgroups are dealt to them round-robin
+// MI355X: 8 XCDs, workgroups are dealt to them round-robin.  A compile-time constant on purpose: it
+// is part of the device-side block -> unit mapping (the HIP runtime exposes no XCD count to ask for),
+// and the library is built for this one chip.
+constexpr int kNumXcd = 8;
 
 // Non-empty clips, longest first.  Passed to kernels by value (kernel argument
 // memory), so no device allocation or copy is needed for the schedule.  Self-attention:
