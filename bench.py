@@ -81,8 +81,8 @@ class _ClockSampler:
                                    text=True, timeout=5).stdout
                 card = next(iter(json.loads(o).values()))
                 sclk = next((re.sub(r"[^0-9.]", "", v) for k, v in card.items() if k.lower().startswith("sclk clock speed")), "")
-                power = next((v for k, v in card.items() if "power" in k.lower() and "(w)" in k.lower()), None)
-                self.samples.append((float(sclk) if sclk else None, float(power) if power is not None else None))
+                power = next((re.sub(r"[^0-9.]", "", str(v)) for k, v in card.items() if "power" in k.lower()), "")
+                self.samples.append((float(sclk) if sclk else None, float(power) if power else None))
             except Exception:
                 pass
             self._stop.wait(self.period)

@@ -43,6 +43,7 @@ KERNELS = (("attn_bwd_dkdv", "attn_bwd_dkdv_kernel"), ("attn_bwd_dq2", "attn_bwd
            ("attn_fwd", "attn_fwd_kernel"), ("qknorm_rope3d_bwd", "qknorm_rope3d_bwd_kernel (outside the step)"),
            ("qknorm_rope3d", "qknorm_rope3d_kernel (outside the step)"), ("rope3d", "rope3d_kernel"),
            ("bwd_prepare", "bwd_prepare_kernel"), ("bwd_short_delta", "bwd_short_delta_kernel"),
+           ("tattn_fwd", "tattn_fwd_kernel"), ("tattn_bwd", "tattn_bwd_kernel"),
            ("copyBuffer", "copy kernel (1 GiB)"))
 ATTENTION = ("attn_bwd_dkdv_kernel", "attn_bwd_dq2_kernel", "attn_fwd_kernel")
 N_SIMD, N_CU, N_SE = 1024, 256, 32      # MI355X: 256 CUs x 4 SIMDs, 8 XCDs x 4 shader engines
@@ -216,12 +217,79 @@ def summarise(run_dir: str, workload: str, out_path: str) -> str:
     return text
 
 
+WIDENED = (("C2", "2 x 4,096 tokens, 16 heads (classifier-free-guidance batch), rope+fwd+bwd"),
+           ("C3", "8 mixed clips packed, 28,704 tokens, 24 heads, rope+fwd+bwd"),
+           ("C5", "130,560 tokens, 40 heads, rope+fwd (inference step)"),
+           ("C4-spatial", "spatial view of the headline latent: 16 sequences of 3,520 tokens, rope+fwd+bwd"),
+           ("P288", "288 images of 256 tokens packed (73,728 tokens), 32 heads, rope+fwd+bwd"),
+           ("C4-cross", "cross-attention: 56,320 queries x 512 text keys/values, fwd+bwd"),
+           ("C4-temporal", "temporal attention: 3,520 pixels x 16 frames, 32 heads, fwd+bwd"),
+           ("L64-temporal", "temporal attention: 3,520 pixels x 64 frames, 8 heads, fwd+bwd (block-walking kernels)"),
+           ("C4-fp8", "FP8 (E4M3, per-tile scales) forward at the headline shape: pack + attention"),
+           ("C5-fp8", "FP8 forward at the 130,560-token inference shape: pack + attention"))
+
+
+def _short_kernel(name: str):
+    import re
+    m = re.match(r"(?:void )?(?:vfm::)?(\w+)<", name) or re.match(r"_ZN3vfm\d+(\w+?_kernel)I", name)
+    return m.group(1) if m else None
+
+
+def summarise_widened(run_dir: str, out_path: str) -> str:
+    """Per-kernel times of the workloads beyond the headline: RUN_DIR/<W>.log and <W>_kernel_stats.csv from
+    rocprofv3 --kernel-trace --stats -d RUN_DIR -o <W> --output-format csv -- python3 bench.py --workload <W> ..."""
+    rel = os.path.relpath(run_dir, ROOT)
+    L = ["rocprofv3 summary: the workloads beyond the headline run (bf16 unless noted), one MI355X (gfx950)",
+         "commands run from the repository root after  cd /tmp && export TMPDIR=/tmp && cd <repo>;  summarised by:",
+         f"  python -m paper_2503_12964_amd.profile_summary {rel} --widened",
+         "kernel names are shortened (template arguments dropped); a call with more than 256 clips launches a kernel once per run of clips"]
+    P = L.append
+    for w, what in WIDENED:
+        b = _bench_line(os.path.join(run_dir, f"{w}.log"))
+        stats = os.path.join(run_dir, f"{w}_kernel_stats.csv")
+        if not b or not os.path.exists(stats):
+            continue
+        br, rf = b["breakdown"], b["roofline"]
+        P("")
+        P(f"[{w}] {what}")
+        P(f"    rocprofv3 --kernel-trace --stats -d {rel} -o {w} --output-format csv -- python3 bench.py --workload {w} "
+          f"--steps {b['steps']} --warmup {b['warmup']} --no-cpu-baseline --no-mfma-ceiling --no-constant-run")
+        parts = [f"value={b['value']:.1f} {b['unit']}", f"ms_per_step={b['ms_per_step']:.3f}"]
+        parts += [f"{k}={br[k]:.3f}" for k in ("rope_ms", "pack_ms", "fwd_ms", "bwd_ms") if isinstance(br.get(k), float) and br[k] > 0]
+        P("    bench line: " + " ".join(parts) + f"; roofline {rf['bound']} achieved={rf['achieved']:.1f} {rf['unit']} frac={rf['frac']:.3f}")
+        P(f"    {'kernel':28s} {'calls':>5s} {'avg_ms':>9s} {'min_ms':>9s} {'max_ms':>9s}")
+        for r in csv.DictReader(open(stats)):
+            k = _short_kernel(r["Name"])
+            if k and float(r["Percentage"]) >= 0.3 and "qknorm" not in k:
+                P(f"    {k:28s} {r['Calls']:>5s} {float(r['AverageNs']) / 1e6:9.3f} {float(r['MinNs']) / 1e6:9.3f} {float(r['MaxNs']) / 1e6:9.3f}")
+    tf, tw = _pmc(run_dir, "temporal_fetch"), _pmc(run_dir, "temporal_write")
+    if tf and tw:
+        P("")
+        P(f"[C4-temporal HBM traffic]  rocprofv3 --pmc FETCH_SIZE (then WRITE_SIZE) -d {rel} -o temporal_fetch (temporal_write) --output-format csv")
+        P("        -- python3 bench.py --workload C4-temporal --steps 2 --warmup 1 --no-cpu-baseline --no-mfma-ceiling")
+        P("    counter scale factors from the plain-copy calibration in attention_C4_56k_rocprofv3.txt: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0 (KiB)")
+        tensor_gb = 56320 * 32 * 128 * 2 / 1e9
+        for kname, nt_r, nt_w in (("tattn_fwd_kernel", 3, 1), ("tattn_bwd_kernel", 4, 3)):
+            rg = sum(v for (k, c), v in tf.items() if c == "FETCH_SIZE" and kname.split("_kernel")[0] in k) * 2.0 * 1024 / 1e9
+            wg = sum(v for (k, c), v in tw.items() if c == "WRITE_SIZE" and kname.split("_kernel")[0] in k) * 1024 / 1e9
+            P(f"    {kname:20s} read {rg:.3f} GB (algorithmic {nt_r * tensor_gb:.3f}), written {wg:.3f} GB (algorithmic {nt_w * tensor_gb:.3f})")
+    text = "\n".join(L) + "\n"
+    os.makedirs(os.path.dirname(os.path.abspath(out_path)), exist_ok=True)
+    open(out_path, "w").write(text)
+    return text
+
+
 def main(argv=None) -> int:
     ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
     ap.add_argument("run_dir")
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--out", default=None)
+    ap.add_argument("--widened", action="store_true", help="summarise the workloads beyond the headline run")
     args = ap.parse_args(argv)
+    if args.widened:
+        out = args.out or os.path.join(ROOT, "profiles", "widened_rows_rocprofv3.txt")
+        sys.stdout.write(summarise_widened(os.path.abspath(args.run_dir), out))
+        return 0
     out = args.out or os.path.join(ROOT, "profiles", f"attention_{args.workload}_rocprofv3.txt")
     sys.stdout.write(summarise(os.path.abspath(args.run_dir), args.workload, out))
     return 0
