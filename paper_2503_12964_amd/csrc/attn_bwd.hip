@@ -85,9 +85,9 @@ template <int D, class Segs>
 __global__ __launch_bounds__(64) void bwd_short_delta_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ v,
     const __bf16* __restrict__ dout, const float* __restrict__ lse, float* __restrict__ delta,
-    const Segs segs, int total, int n_heads, float scale) {
+    const Segs segs, const TileIndex ti, int total, int n_heads, float scale) {
   int seq, t;
-  locate_tile<false>(segs, 64, blockIdx.x, seq, t);
+  locate_tile(ti, segs.n, blockIdx.x, seq, t);
   const int nk = segs.kv_len(seq);
   if (nk > kShortKeys) return;
   const int head = blockIdx.y;
@@ -161,7 +161,7 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
                           const float* __restrict__ lse2, const float* __restrict__ delta,
                           const float* __restrict__ sentinel,   // [+inf, 0]
                           __bf16* __restrict__ dk, __bf16* __restrict__ dv,
-                          const Segs segs, const UnitMap um,
+                          const Segs segs, const UnitMap um, const TileIndex ti,
                           int total, int n_heads, float scale, float scale_log2,
                           float* __restrict__ dkv32, size_t kv_elems, int q_split) {
   using Cfg = BwdCfg<D>;
@@ -181,7 +181,7 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   int q_chunk = 0;
   if constexpr (SPLIT) { q_chunk = tile % q_split; tile /= q_split; }
   int seq, tk;
-  locate_tile<true>(segs, kBwdBC, tile, seq, tk);
+  locate_tile(ti, segs.n, tile, seq, tk);
   const int kv_b = segs.kv_start(seq) + segs.kv_len(seq);
   const int j0 = segs.kv_start(seq) + tk * kBwdBC;
   int qa = segs.q_start(seq), qb = qa + segs.q_len(seq);
@@ -529,7 +529,7 @@ __global__ __launch_bounds__(W * 64, (NI == 1 ? 2 : 1))
 void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                         const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
                         const float* __restrict__ lse2g, const float* __restrict__ delta,
-                        __bf16* __restrict__ dq, const Segs segs, const UnitMap um,
+                        __bf16* __restrict__ dq, const Segs segs, const UnitMap um, const TileIndex ti,
                         int total, int n_heads, float scale, float scale_log2) {
   using Cfg = DqCfg<D, NI, W>;
   constexpr int KS = D / 16;
@@ -544,7 +544,7 @@ void attn_bwd_dq_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__
   if (!map_unit(um, blockIdx.x, head, tile)) return;
   // query rows of the range [.., q_b); keys and values are rows [seg_a, seg_b) of k, v
   int seq, tq;
-  locate_tile<false>(segs, Cfg::kBR, tile, seq, tq);
+  locate_tile(ti, segs.n, tile, seq, tq);
   const int q_b = segs.q_start(seq) + segs.q_len(seq);
   const int q0 = segs.q_start(seq) + tq * Cfg::kBR;
   const int seg_a = segs.kv_start(seq);
@@ -771,7 +771,7 @@ __global__ __launch_bounds__(kDq2Waves * 64, 1)
 void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                          const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
                          const float* __restrict__ lse2g, const float* __restrict__ delta,
-                         __bf16* __restrict__ dq, const Segs segs, const UnitMap um,
+                         __bf16* __restrict__ dq, const Segs segs, const UnitMap um, const TileIndex ti,
                          int total, int n_heads, float scale, float scale_log2) {
   using Cfg = Dq2Cfg<D>;
   constexpr int KS = D / 16;
@@ -788,7 +788,7 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
   int head, tile;
   if (!map_unit(um, blockIdx.x, head, tile)) return;
   int seq, tq;
-  locate_tile<false>(segs, Cfg::kBR, tile, seq, tq);
+  locate_tile(ti, segs.n, tile, seq, tq);
   const int q_b = segs.q_start(seq) + segs.q_len(seq);
   const int q0 = segs.q_start(seq) + tq * Cfg::kBR;
   const int seg_a = segs.kv_start(seq);
@@ -1104,14 +1104,16 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
     for (int s2 = 0; s2 < segs.n; ++s2)
       any_short |= segs.q_len(s2) > 0 && segs.kv_len(s2) > 0 && segs.kv_len(s2) <= kShortKeys;
     if (any_short) {   // sequences with a handful of keys: Delta in its cancellation-free form
-      e = launch(bwd_short_delta_kernel<D, Segs>, dim3(count_tiles<false>(segs, 64), n_heads), dim3(64), 0,
-                 stream, qb, kb, vb, dob, lse, delta, segs, total, n_heads, scale);
+      const TileIndex ti = make_tile_index<false>(segs, 64);
+      e = launch(bwd_short_delta_kernel<D, Segs>, dim3(count_tiles(ti), n_heads), dim3(64), 0,
+                 stream, qb, kb, vb, dob, lse, delta, segs, ti, total, n_heads, scale);
       if (e != hipSuccess) return e;
     }
   }
   {
     using Cfg = BwdCfg<D>;
-    const int tiles = count_tiles<true>(segs, kBwdBC);
+    const TileIndex ti = make_tile_index<true>(segs, kBwdBC);
+    const int tiles = count_tiles(ti);
     if (tiles == 0) return hipSuccess;
     UnitMap um = make_unit_map(tiles, n_heads);
     // Few key tiles and long query ranges (cross-attention): split the queries over workgroups.
@@ -1140,7 +1142,7 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
       if (e != hipSuccess) return e;
       e = launch(kern, dim3(um.chunk * kNumXcd), dim3(kBwdWaves * 64), Cfg::kLdsBytes, stream, qb, kb, vb, dob,
-                 lse2, delta, sentinel, (__bf16*)dk, (__bf16*)dv, segs, um, total, n_heads, scale,
+                 lse2, delta, sentinel, (__bf16*)dk, (__bf16*)dv, segs, um, ti, total, n_heads, scale,
                  scale * kLog2eB, dkv32, kv_elems, q_split);
       if (e != hipSuccess) return e;
       e = launch(f32_to_bf16_kernel, cgrid, dim3(256), 0, stream, (const f32x4*)acc_k, (bf16x4*)dk + lo4, h4);
@@ -1153,14 +1155,15 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
                               hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
       if (e != hipSuccess) return e;
       e = launch(kern, dim3(um.chunk * kNumXcd), dim3(kBwdWaves * 64), Cfg::kLdsBytes, stream, qb, kb, vb, dob,
-                 lse2, delta, sentinel, (__bf16*)dk, (__bf16*)dv, segs, um, total, n_heads, scale,
+                 lse2, delta, sentinel, (__bf16*)dk, (__bf16*)dv, segs, um, ti, total, n_heads, scale,
                  scale * kLog2eB, (float*)nullptr, (size_t)0, 1);
       if (e != hipSuccess) return e;
     }
   }
   if constexpr (D == 128) {
     using Cfg = Dq2Cfg<D>;
-    const int tiles = count_tiles<false>(segs, Cfg::kBR);
+    const TileIndex ti = make_tile_index<false>(segs, Cfg::kBR);
+    const int tiles = count_tiles(ti);
     if (tiles == 0) return hipSuccess;
     UnitMap um = make_unit_map(tiles, n_heads);
     auto kern = attn_bwd_dq2_kernel<D, Segs>;
@@ -1168,12 +1171,13 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
                             hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
     return launch(kern, dim3(um.chunk * kNumXcd), dim3(kDq2Waves * 64), Cfg::kLdsBytes, stream, qb, kb, vb, dob,
-                  lse2, delta, (__bf16*)dq, segs, um, total, n_heads, scale, scale * kLog2eB);
+                  lse2, delta, (__bf16*)dq, segs, um, ti, total, n_heads, scale, scale * kLog2eB);
   } else {
     constexpr int NI = 1;
     constexpr int W = 8;   // 256 query rows share each staged K/V tile
     using Cfg = DqCfg<D, NI, W>;
-    const int tiles = count_tiles<false>(segs, Cfg::kBR);
+    const TileIndex ti = make_tile_index<false>(segs, Cfg::kBR);
+    const int tiles = count_tiles(ti);
     if (tiles == 0) return hipSuccess;
     UnitMap um = make_unit_map(tiles, n_heads);
     auto kern = attn_bwd_dq_kernel<D, NI, W, Segs>;
@@ -1181,7 +1185,7 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
                             hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
     if (e != hipSuccess) return e;
     return launch(kern, dim3(um.chunk * kNumXcd), dim3(W * 64), Cfg::kLdsBytes, stream, qb, kb, vb, dob, lse2,
-                  delta, (__bf16*)dq, segs, um, total, n_heads, scale, scale * kLog2eB);
+                  delta, (__bf16*)dq, segs, um, ti, total, n_heads, scale, scale * kLog2eB);
   }
 }
 

@@ -234,8 +234,8 @@ __global__ __launch_bounds__(kF8Waves * 64, 2)
 void attn_fwd_fp8_kernel(const unsigned char* __restrict__ q8, const unsigned char* __restrict__ k8,
                          const unsigned char* __restrict__ vT8, __bf16* __restrict__ out,
                          const unsigned char* __restrict__ q_exp, const uint32_t* __restrict__ unit_scale,
-                         float* __restrict__ lse, const Fp8SegTable segs, const UnitMap um, int total,
-                         int n_heads, int n_units) {
+                         float* __restrict__ lse, const Fp8SegTable segs, const UnitMap um, const TileIndex ti,
+                         int total, int n_heads, int n_units) {
   constexpr int KS = D / 64;            // instructions per 32-key score tile
   constexpr int DB = D / 32;            // 32-row blocks of O^T
   constexpr int UB = kF8Unit * D;       // bytes of a K unit and of a V^T unit
@@ -247,7 +247,7 @@ void attn_fwd_fp8_kernel(const unsigned char* __restrict__ q8, const unsigned ch
   int head, tile;
   if (!map_unit(um, blockIdx.x, head, tile)) return;
   int seq, tq;
-  locate_tile<false>(segs, kF8Rows, tile, seq, tq);
+  locate_tile(ti, segs.n, tile, seq, tq);
   const int seg_a = segs.start[seq], seg_b = seg_a + segs.len[seq];
   const int q0 = seg_a + tq * kF8Rows;
   const int unit0 = segs.unit0[seq];
@@ -500,8 +500,8 @@ template <int D>
 static hipError_t fwd_fp8_d(const void* q8, const void* k8, const void* vT8, const void* scales,
                             const Fp8SegTable& segs, int n_units, int total, int n_heads,
                             void* out, float* lse, hipStream_t stream) {
-  int tiles = 0;
-  for (int s = 0; s < segs.n; ++s) tiles += (segs.len[s] + kF8Rows - 1) / kF8Rows;
+  const TileIndex ti = make_tile_index<false>(segs, kF8Rows);
+  const int tiles = count_tiles(ti);
   if (tiles == 0) return hipSuccess;
   UnitMap um = make_unit_map(tiles, n_heads);
   constexpr int lds = kF8Ring * 2 * kF8Unit * D + kF8Ring * 16;
@@ -512,7 +512,7 @@ static hipError_t fwd_fp8_d(const void* q8, const void* k8, const void* vT8, con
   const unsigned char* q_exp = static_cast<const unsigned char*>(scales);
   const uint32_t* us = reinterpret_cast<const uint32_t*>(q_exp + unit_scale_offset(total, n_heads));
   return launch(kern, dim3(um.chunk * kNumXcd), dim3(kF8Waves * 64), lds, stream, (const unsigned char*)q8,
-                (const unsigned char*)k8, (const unsigned char*)vT8, (__bf16*)out, q_exp, us, lse, segs, um, total,
+                (const unsigned char*)k8, (const unsigned char*)vT8, (__bf16*)out, q_exp, us, lse, segs, um, ti, total,
                 n_heads, n_units);
 }
 

@@ -50,7 +50,7 @@ template <int D, int W, class Segs>
 __global__ __launch_bounds__(W * 64, 2)
 void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
                      const __bf16* __restrict__ v, __bf16* __restrict__ out,
-                     float* __restrict__ lse, const Segs segs, const UnitMap um,
+                     float* __restrict__ lse, const Segs segs, const UnitMap um, const TileIndex ti,
                      int total, int n_heads, float scale_log2) {
   using Cfg = FwdCfg<D, W>;
   constexpr int KS = D / 16;   // k-steps of the QK^T contraction
@@ -67,7 +67,7 @@ void attn_fwd_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
   // query rows [q0, q0 + rows) of the sequence's query range [.., q_b); its keys and values
   // are rows [seg_a, seg_b) of k and v (the same range for self-attention)
   int seq, tq;
-  locate_tile<false>(segs, Cfg::kRows, tile, seq, tq);
+  locate_tile(ti, segs.n, tile, seq, tq);
   const int q_b = segs.q_start(seq) + segs.q_len(seq);
   const int q0 = segs.q_start(seq) + tq * Cfg::kRows;
   const int seg_a = segs.kv_start(seq);
@@ -374,7 +374,8 @@ static hipError_t launch_fwd_cfg(const void* q, const void* k, const void* v, co
                                  int total, int n_heads, float scale, void* out, float* lse,
                                  hipStream_t stream) {
   using Cfg = FwdCfg<D, W>;
-  const int tiles = count_tiles<false>(segs, Cfg::kRows);
+  const TileIndex ti = make_tile_index<false>(segs, Cfg::kRows);
+  const int tiles = count_tiles(ti);
   if (tiles == 0) return hipSuccess;
   UnitMap um = make_unit_map(tiles, n_heads);
   const int grid = um.chunk * kNumXcd;
@@ -383,7 +384,7 @@ static hipError_t launch_fwd_cfg(const void* q, const void* k, const void* v, co
                                      hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kLdsBytes);
   if (e != hipSuccess) return e;
   return launch(kern, dim3(grid), dim3(W * 64), Cfg::kLdsBytes, stream, (const __bf16*)q, (const __bf16*)k,
-                (const __bf16*)v, (__bf16*)out, lse, segs, um, total, n_heads, scale * kLog2e);
+                (const __bf16*)v, (__bf16*)out, lse, segs, um, ti, total, n_heads, scale * kLog2e);
 }
 
 template <class Segs>

@@ -148,7 +148,7 @@ int build_fp8_tables(const int32_t* cu, int n_seqs, int unit_base, vfm::Fp8ClipT
       if (cu[s + 1] > cu[s]) order[n++] = s;
     std::stable_sort(order, order + n, [&](int a, int b) { return (cu[a + 1] - cu[a]) > (cu[b + 1] - cu[b]); });
     segs->n = n;
-    for (int i = 0; i < VFM_MAX_SEQS; ++i) {
+    for (int i = 0; i < vfm::kFp8MaxSeqs; ++i) {
       const bool live = i < n;
       segs->start[i] = live ? cu[order[i]] : 0;
       segs->len[i] = live ? cu[order[i] + 1] - cu[order[i]] : 0;
@@ -359,7 +359,8 @@ int vfm_schedule_units(const int32_t* cu_seqlens, int n_seqs, int total_tokens, 
     for (int s0 = 0; s0 < n_seqs || s0 == 0; s0 += VFM_MAX_SEQS) {
       SegTable segs;
       build_seg_table(cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), &segs);
-      const vfm::UnitMap um = vfm::make_unit_map(vfm::count_tiles<false>(segs, rows_per_tile), n_heads);
+      const vfm::TileIndex ti = vfm::make_tile_index<false>(segs, rows_per_tile);
+      const vfm::UnitMap um = vfm::make_unit_map(vfm::count_tiles(ti), n_heads);
       const int grid = um.chunk * vfm::kNumXcd;
       if (pass == 1)
         for (int b = 0; b < grid; ++b) {
@@ -371,7 +372,7 @@ int vfm_schedule_units(const int32_t* cu_seqlens, int n_seqs, int total_tokens, 
             continue;
           }
           int s, t;
-          vfm::locate_tile<false>(segs, rows_per_tile, tile, s, t);
+          vfm::locate_tile(ti, segs.n, tile, s, t);
           const int first = segs.q_start(s) + t * rows_per_tile;
           u[0] = head;
           u[1] = first;
@@ -646,9 +647,9 @@ int vfm_fp8_pack(const void* q, const void* k, const void* v, const int32_t* cu_
   hipError_t e = vfm::launch_fp8_pack_q(q, total_tokens, n_heads, head_dim, pre, q8, scales, stream);
   if (e != hipSuccess) return launch_status(e);
   int unit_base = 0;
-  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_SEQS) {
+  for (int s0 = 0; s0 < n_seqs; s0 += vfm::kFp8MaxSeqs) {
     vfm::Fp8ClipTable clips;
-    unit_base = build_fp8_tables(cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), unit_base, &clips, nullptr);
+    unit_base = build_fp8_tables(cu_seqlens + s0, std::min(vfm::kFp8MaxSeqs, n_seqs - s0), unit_base, &clips, nullptr);
     e = vfm::launch_fp8_pack_kv(k, v, clips, (int)units, total_tokens, n_heads, head_dim, k8, vT8, scales, stream);
     if (e != hipSuccess) return launch_status(e);
   }
@@ -668,10 +669,10 @@ int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, const void
   const size_t units = count_fp8_units(cu_seqlens, n_seqs);
   if (units * n_heads * kFp8Unit * head_dim > 0xffffffffULL) return VFM_ERR_SHAPE;
   int unit_base = 0;
-  for (int s0 = 0; s0 < n_seqs; s0 += VFM_MAX_SEQS) {
+  for (int s0 = 0; s0 < n_seqs; s0 += vfm::kFp8MaxSeqs) {
     vfm::Fp8ClipTable clips;
     vfm::Fp8SegTable segs;
-    unit_base = build_fp8_tables(cu_seqlens + s0, std::min(VFM_MAX_SEQS, n_seqs - s0), unit_base, &clips, &segs);
+    unit_base = build_fp8_tables(cu_seqlens + s0, std::min(vfm::kFp8MaxSeqs, n_seqs - s0), unit_base, &clips, &segs);
     hipError_t e = vfm::launch_attn_fwd_fp8(q8, k8, vT8, scales, segs, (int)units, total_tokens, n_heads, head_dim,
                                             out, lse, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return launch_status(e);

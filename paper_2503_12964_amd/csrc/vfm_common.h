@@ -67,12 +67,15 @@ struct Fp8ClipTable {
   int cu[VFM_MAX_SEQS + 1];     // first packed token of clip s
   int unit0[VFM_MAX_SEQS + 1];  // units of the clips before s
 };
-// ... and the forward kernel's schedule (non-empty clips, longest first).
+// ... and the forward kernel's schedule (non-empty clips, longest first).  The FP8 entry points
+// cut a call into runs of kFp8MaxSeqs clips: with three arrays per clip and the tile index beside
+// it, a 256-clip table would not fit the 4 KB of kernel arguments.
+constexpr int kFp8MaxSeqs = 128;
 struct Fp8SegTable {
   int n;
-  int start[VFM_MAX_SEQS];
-  int len[VFM_MAX_SEQS];
-  int unit0[VFM_MAX_SEQS];      // first unit of the clip in the packed buffers
+  int start[kFp8MaxSeqs];
+  int len[kFp8MaxSeqs];
+  int unit0[kFp8MaxSeqs];       // first unit of the clip in the packed buffers
   __device__ __host__ int q_start(int s) const { return start[s]; }
   __device__ __host__ int q_len(int s) const { return len[s]; }
   __device__ __host__ int kv_start(int s) const { return start[s]; }
@@ -127,28 +130,37 @@ __host__ __device__ __forceinline__ bool map_unit(const UnitMap& um, int block, 
   return true;
 }
 
-// Tile index (over all sequences in table order) -> sequence s and tile t within it.
-// Tiles are cut from the query ranges (KV = false) or from the key/value ranges (KV = true);
-// rows_per_tile is the tile height.
-template <bool KV, class Segs>
-__host__ __device__ __forceinline__ void locate_tile(const Segs& segs, int rows_per_tile, int tile, int& s,
-                                            int& t) {
-  s = 0;
-  for (; s < segs.n - 1; ++s) {
-    const int len = KV ? segs.kv_len(s) : segs.q_len(s);
-    const int nt = (len + rows_per_tile - 1) / rows_per_tile;
-    if (tile < nt) break;
-    tile -= nt;
-  }
-  t = tile;
-}
+// Tiles of the sequences before s (table order) for one launch's tile height, built on the host
+// and passed by value beside the sequence table.  A workgroup finds its sequence by binary
+// search in it: walking the table instead costs a dependent scalar load per sequence, which with
+// 256 clips in a call took as long as a short clip's whole key loop.  Tiles are cut from the
+// query ranges (KV = false) or from the key/value ranges (KV = true).
+struct TileIndex {
+  int cu[VFM_MAX_SEQS + 1];   // cu[s] = tiles of sequences 0..s-1; entries past the table repeat the total
+};
 
 template <bool KV, class Segs>
-inline int count_tiles(const Segs& segs, int rows_per_tile) {
+inline TileIndex make_tile_index(const Segs& segs, int rows_per_tile) {
+  TileIndex ti;
   int tiles = 0;
-  for (int s = 0; s < segs.n; ++s)
-    tiles += ((KV ? segs.kv_len(s) : segs.q_len(s)) + rows_per_tile - 1) / rows_per_tile;
-  return tiles;
+  for (int s = 0; s <= VFM_MAX_SEQS; ++s) {
+    ti.cu[s] = tiles;
+    if (s < segs.n) tiles += ((KV ? segs.kv_len(s) : segs.q_len(s)) + rows_per_tile - 1) / rows_per_tile;
+  }
+  return ti;
+}
+inline int count_tiles(const TileIndex& ti) { return ti.cu[VFM_MAX_SEQS]; }
+
+// Tile index (over the n sequences of the table, in table order) -> sequence s and tile t within
+// it: the last s with cu[s] <= tile, which skips sequences that have no tile.
+__host__ __device__ __forceinline__ void locate_tile(const TileIndex& ti, int n, int tile, int& s, int& t) {
+  int lo = 0, hi = n;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (ti.cu[mid] <= tile) lo = mid; else hi = mid;
+  }
+  s = lo;
+  t = tile - ti.cu[lo];
 }
 
 // Query rows per workgroup of the forward kernel for the sequences of one launch.  Few keys
