@@ -38,12 +38,12 @@ LDS_COUNTERS = ("SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_WAIT_INST_LDS SQ_INSTS_
                 "SQ_ACTIVE_INST_VALU SQ_WAVE_CYCLES SQ_BUSY_CYCLES")
 
 # kernel-name fragment -> short label, most specific first
-KERNELS = (("attn_bwd_dkdv", "attn_bwd_dkdv_kernel"), ("attn_bwd_dq2", "attn_bwd_dq2_kernel"),
+KERNELS = (("tattn_fwd", "tattn_fwd_kernel"), ("tattn_bwd", "tattn_bwd_kernel"),
+           ("attn_bwd_dkdv", "attn_bwd_dkdv_kernel"), ("attn_bwd_dq2", "attn_bwd_dq2_kernel"),
            ("attn_bwd_dq", "attn_bwd_dq_kernel"), ("attn_fwd_fp8", "attn_fwd_fp8_kernel"),
            ("attn_fwd", "attn_fwd_kernel"), ("qknorm_rope3d_bwd", "qknorm_rope3d_bwd_kernel (outside the step)"),
            ("qknorm_rope3d", "qknorm_rope3d_kernel (outside the step)"), ("rope3d", "rope3d_kernel"),
            ("bwd_prepare", "bwd_prepare_kernel"), ("bwd_short_delta", "bwd_short_delta_kernel"),
-           ("tattn_fwd", "tattn_fwd_kernel"), ("tattn_bwd", "tattn_bwd_kernel"),
            ("copyBuffer", "copy kernel (1 GiB)"))
 ATTENTION = ("attn_bwd_dkdv_kernel", "attn_bwd_dq2_kernel", "attn_fwd_kernel")
 N_SIMD, N_CU, N_SE = 1024, 256, 32      # MI355X: 256 CUs x 4 SIMDs, 8 XCDs x 4 shader engines
@@ -232,7 +232,12 @@ WIDENED = (("C2", "2 x 4,096 tokens, 16 heads (classifier-free-guidance batch), 
 def _short_kernel(name: str):
     import re
     m = re.match(r"(?:void )?(?:vfm::)?(\w+)<", name) or re.match(r"_ZN3vfm\d+(\w+?_kernel)I", name)
-    return m.group(1) if m else None
+    if not m:
+        return None
+    k = m.group(1)
+    if k == "tattnL_fwd_kernel":        # two instances: the forward pass, and the backward's statistics pass
+        k += " (bwd stats)" if ("Lb1E" in name or ", true>" in name) else " (forward)"
+    return k
 
 
 def summarise_widened(run_dir: str, out_path: str) -> str:
@@ -257,11 +262,11 @@ def summarise_widened(run_dir: str, out_path: str) -> str:
         parts = [f"value={b['value']:.1f} {b['unit']}", f"ms_per_step={b['ms_per_step']:.3f}"]
         parts += [f"{k}={br[k]:.3f}" for k in ("rope_ms", "pack_ms", "fwd_ms", "bwd_ms") if isinstance(br.get(k), float) and br[k] > 0]
         P("    bench line: " + " ".join(parts) + f"; roofline {rf['bound']} achieved={rf['achieved']:.1f} {rf['unit']} frac={rf['frac']:.3f}")
-        P(f"    {'kernel':28s} {'calls':>5s} {'avg_ms':>9s} {'min_ms':>9s} {'max_ms':>9s}")
+        P(f"    {'kernel':32s} {'calls':>5s} {'avg_ms':>9s} {'min_ms':>9s} {'max_ms':>9s}")
         for r in csv.DictReader(open(stats)):
             k = _short_kernel(r["Name"])
-            if k and float(r["Percentage"]) >= 0.3 and "qknorm" not in k:
-                P(f"    {k:28s} {r['Calls']:>5s} {float(r['AverageNs']) / 1e6:9.3f} {float(r['MinNs']) / 1e6:9.3f} {float(r['MaxNs']) / 1e6:9.3f}")
+            if k and float(r["Percentage"]) >= 0.05 and "qknorm" not in k:
+                P(f"    {k:32s} {r['Calls']:>5s} {float(r['AverageNs']) / 1e6:9.3f} {float(r['MinNs']) / 1e6:9.3f} {float(r['MaxNs']) / 1e6:9.3f}")
     tf, tw = _pmc(run_dir, "temporal_fetch"), _pmc(run_dir, "temporal_write")
     if tf and tw:
         P("")
