@@ -338,7 +338,7 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
 // assembly with a VGPR destination and the loop-invariant B operand in an AGPR tuple (which
 // an MFMA may read directly).  The compiler does not know that the statement is an MFMA, so
 // it inserts no wait states for readers of d: every reader must be at least two MFMAs
-// downstream in program order.
+// downstream in program order (tests/test_isa_hazards.py checks the emitted assembly for it).
 __device__ __forceinline__ void mfma32_v(f32x16& d, const bf16x8& a, const bf16x8& b, bool first) {
   if (first) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
   else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
