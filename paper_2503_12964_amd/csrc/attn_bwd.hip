@@ -32,6 +32,8 @@ constexpr int kBwdBQ = 64;   // query rows per inner step
 constexpr float kLog2eB = 1.4426950408889634f;
 
 // ---------------------------------------------------------------- prepare
+constexpr int kPrepHeads = 4;   // heads per workgroup (grid.y = ceil(n_heads / kPrepHeads))
+
 template <int D>
 __global__ __launch_bounds__(256) void bwd_prepare_kernel(const u32x4* __restrict__ out,
                                                           const u32x4* __restrict__ dout,
@@ -46,23 +48,32 @@ __global__ __launch_bounds__(256) void bwd_prepare_kernel(const u32x4* __restric
   const int chunk = threadIdx.x % kLanesPerRow;
   const bool valid = tok < total;
   const int tk = valid ? tok : total - 1;
-  if (blockIdx.x == 0 && threadIdx.x == 0) {   // statistics fetched for rows past a clip's end
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {   // statistics fetched for rows past a clip's end
     sentinel[0] = INFINITY;                    // lse2: P = exp2(s - inf) = 0
     sentinel[1] = 0.f;                         // Delta
   }
-  for (int h = 0; h < n_heads; ++h) {
-    const size_t row = (size_t)tk * n_heads + h;
-    const u32x4 a = out[row * kLanesPerRow + chunk];
-    const u32x4 b = dout[row * kLanesPerRow + chunk];
+  // blockIdx.y picks a group of kPrepHeads heads: their rows of one token are contiguous, the
+  // loads of a group are in flight together, and a small call still spreads over the chip
+  const int h0 = blockIdx.y * kPrepHeads;
+  u32x4 a[kPrepHeads], b[kPrepHeads];
+#pragma unroll
+  for (int i = 0; i < kPrepHeads; ++i) {
+    const size_t row = (size_t)tk * n_heads + min(h0 + i, n_heads - 1);
+    a[i] = out[row * kLanesPerRow + chunk];
+    b[i] = dout[row * kLanesPerRow + chunk];
+  }
+#pragma unroll
+  for (int i = 0; i < kPrepHeads; ++i) {
+    const int h = h0 + i;
     float s = 0.f;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      s += __builtin_bit_cast(float, a[e] << 16) * __builtin_bit_cast(float, b[e] << 16);
-      s += __builtin_bit_cast(float, a[e] & 0xffff0000u) * __builtin_bit_cast(float, b[e] & 0xffff0000u);
+      s += __builtin_bit_cast(float, a[i][e] << 16) * __builtin_bit_cast(float, b[i][e] << 16);
+      s += __builtin_bit_cast(float, a[i][e] & 0xffff0000u) * __builtin_bit_cast(float, b[i][e] & 0xffff0000u);
     }
 #pragma unroll
     for (int o = kLanesPerRow / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, kLanesPerRow);
-    if (valid && chunk == 0) {
+    if (valid && chunk == 0 && h < n_heads) {
       delta[(size_t)h * total + tok] = s;
       lse2[(size_t)h * total + tok] = lse[(size_t)h * total + tok] * kLog2eB;   // log2 units
     }
@@ -1195,7 +1206,7 @@ hipError_t launch_bwd_prepare(const void* out, const void* dout, const float* ls
                               float* sentinel, int total, int n_heads, int head_dim, hipStream_t stream) {
   if (total == 0) return hipSuccess;
   const int tok_per_block = 256 / (head_dim / 8);
-  const dim3 grid((total + tok_per_block - 1) / tok_per_block);
+  const dim3 grid((total + tok_per_block - 1) / tok_per_block, (n_heads + kPrepHeads - 1) / kPrepHeads);
   if (head_dim == 128)
     return launch(bwd_prepare_kernel<128>, grid, dim3(256), 0, stream, (const u32x4*)out, (const u32x4*)dout, lse,
                   delta, lse2, sentinel, total, n_heads);
