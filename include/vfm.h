@@ -359,6 +359,9 @@ VFM_API int vfm_attn_fwd_fp8(const void* q8, const void* k8, const void* vT8, co
  * 8) take consecutive tiles of the same head.  The attention kernels use this
  * very mapping over query rows with rows_per_tile = 256 in the dQ kernel and
  * vfm_attn_fwd_tile_rows() in the forward, and over key rows with 128 (dK/dV).
+ * (A backward launch at head_dim 128 whose sequences all have at most 1,024
+ * rows deals both kinds of tile from one grid, per (head, sequence) the key
+ * tiles and then the query tiles, with the same tile heights and XCD rule.)
  * For workgroup b < *n_blocks: units[3b] = head (-1: the workgroup is grid
  * padding and exits), units[3b+1] = first packed row, units[3b+2] = rows
  * (1..rows_per_tile).  With more than VFM_MAX_SEQS clips the call is one launch

@@ -165,16 +165,18 @@ struct BwdCfg {
 // SPLIT: the sequence's query range is cut into q_split chunks, one workgroup each; partial
 // dK/dV are added to zeroed fp32 accumulators (dkv32: dK, then dV) with fp32 atomics and
 // converted afterwards.  Used when a few long key tiles would otherwise leave CUs idle.
+// The work of one workgroup: key tile tk of sequence seq, one head (and, if SPLIT, one chunk of
+// the sequence's queries).
 template <int D, class Segs, bool SPLIT>
-__global__ __launch_bounds__(kBwdWaves * 64, 1)
-void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                          const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
-                          const float* __restrict__ lse2, const float* __restrict__ delta,
-                          const float* __restrict__ sentinel,   // [+inf, 0]
-                          __bf16* __restrict__ dk, __bf16* __restrict__ dv,
-                          const Segs segs, const UnitMap um, const TileIndex ti,
-                          int total, int n_heads, float scale, float scale_log2,
-                          float* __restrict__ dkv32, size_t kv_elems, int q_split) {
+__device__ __forceinline__
+void bwd_dkdv_unit(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                   const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
+                   const float* __restrict__ lse2, const float* __restrict__ delta,
+                   const float* __restrict__ sentinel,   // [+inf, 0]
+                   __bf16* __restrict__ dk, __bf16* __restrict__ dv, const Segs& segs,
+                   int total, int n_heads, float scale, float scale_log2,
+                   float* __restrict__ dkv32, size_t kv_elems, int q_split,
+                   int head, int seq, int tk, int q_chunk) {
   using Cfg = BwdCfg<D>;
   constexpr int KS = D / 16;
   constexpr int DB = D / 32;
@@ -185,14 +187,8 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
-  int head, tile;
-  if (!map_unit(um, blockIdx.x, head, tile)) return;
   // key rows [j0, j0 + kBwdBC) of the sequence's key/value range [.., kv_b); the queries it
   // walks are rows [seg_a, seg_b) of q, dout (the same range for self-attention)
-  int q_chunk = 0;
-  if constexpr (SPLIT) { q_chunk = tile % q_split; tile /= q_split; }
-  int seq, tk;
-  locate_tile(ti, segs.n, tile, seq, tk);
   const int kv_b = segs.kv_start(seq) + segs.kv_len(seq);
   const int j0 = segs.kv_start(seq) + tk * kBwdBC;
   int qa = segs.q_start(seq), qb = qa + segs.q_len(seq);
@@ -512,6 +508,26 @@ void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict
   }
 }
 
+template <int D, class Segs, bool SPLIT>
+__global__ __launch_bounds__(kBwdWaves * 64, 1)
+void attn_bwd_dkdv_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                          const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
+                          const float* __restrict__ lse2, const float* __restrict__ delta,
+                          const float* __restrict__ sentinel,
+                          __bf16* __restrict__ dk, __bf16* __restrict__ dv,
+                          const Segs segs, const UnitMap um, const TileIndex ti,
+                          int total, int n_heads, float scale, float scale_log2,
+                          float* __restrict__ dkv32, size_t kv_elems, int q_split) {
+  int head, tile;
+  if (!map_unit(um, blockIdx.x, head, tile)) return;
+  int q_chunk = 0;
+  if constexpr (SPLIT) { q_chunk = tile % q_split; tile /= q_split; }
+  int seq, tk;
+  locate_tile(ti, segs.n, tile, seq, tk);
+  bwd_dkdv_unit<D, Segs, SPLIT>(q, k, v, dout, lse2, delta, sentinel, dk, dv, segs, total, n_heads, scale,
+                                scale_log2, dkv32, kv_elems, q_split, head, seq, tk, q_chunk);
+}
+
 // fp32 accumulators -> bf16 gradients (after a split dK/dV pass); also zeroes them beforehand
 __global__ void fill_zero_f32x4_kernel(f32x4* p, size_t n4) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -777,13 +793,14 @@ struct Dq2Cfg {
   static constexpr int kChunksPerThread = kDqBC * kChunksPerRow / (kDq2Waves * 64);
 };
 
+// The work of one workgroup: query tile tq of sequence seq, one head.
 template <int D, class Segs>
-__global__ __launch_bounds__(kDq2Waves * 64, 1)
-void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                         const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
-                         const float* __restrict__ lse2g, const float* __restrict__ delta,
-                         __bf16* __restrict__ dq, const Segs segs, const UnitMap um, const TileIndex ti,
-                         int total, int n_heads, float scale, float scale_log2) {
+__device__ __forceinline__
+void bwd_dq2_unit(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                  const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
+                  const float* __restrict__ lse2g, const float* __restrict__ delta,
+                  __bf16* __restrict__ dq, const Segs& segs, int total, int n_heads, float scale,
+                  float scale_log2, int head, int seq, int tq) {
   using Cfg = Dq2Cfg<D>;
   constexpr int KS = D / 16;
   constexpr int DB = D / 32;
@@ -796,10 +813,6 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
 
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
-  int head, tile;
-  if (!map_unit(um, blockIdx.x, head, tile)) return;
-  int seq, tq;
-  locate_tile(ti, segs.n, tile, seq, tq);
   const int q_b = segs.q_start(seq) + segs.q_len(seq);
   const int q0 = segs.q_start(seq) + tq * Cfg::kBR;
   const int seg_a = segs.kv_start(seq);
@@ -1089,6 +1102,53 @@ void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict_
   }
 }
 
+template <int D, class Segs>
+__global__ __launch_bounds__(kDq2Waves * 64, 1)
+void attn_bwd_dq2_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                         const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
+                         const float* __restrict__ lse2g, const float* __restrict__ delta,
+                         __bf16* __restrict__ dq, const Segs segs, const UnitMap um, const TileIndex ti,
+                         int total, int n_heads, float scale, float scale_log2) {
+  int head, tile;
+  if (!map_unit(um, blockIdx.x, head, tile)) return;
+  int seq, tq;
+  locate_tile(ti, segs.n, tile, seq, tq);
+  bwd_dq2_unit<D, Segs>(q, k, v, dout, lse2g, delta, dq, segs, total, n_heads, scale, scale_log2, head, seq, tq);
+}
+
+// ---------------------------------------------------------------- short sequences: one launch
+// For sequences of a few hundred tokens the two passes above are bound by the memory path, not
+// by the matrix pipe: each reads q, k, v, dout of a (sequence, head) once, a millisecond apart,
+// so the second pass finds nothing of it in L2.  This kernel runs the same two units from one
+// grid: per (head, sequence) the key tiles' dK/dV units, then the query tiles' dQ units, as
+// consecutive workgroups of one XCD, so that they run side by side and share the lines they
+// fetch.  ti counts both kinds of tile per sequence (key tiles first).
+template <int D, class Segs>
+__global__ __launch_bounds__(kBwdWaves * 64, 1)
+void attn_bwd_both_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
+                          const __bf16* __restrict__ v, const __bf16* __restrict__ dout,
+                          const float* __restrict__ lse2, const float* __restrict__ delta,
+                          const float* __restrict__ sentinel, __bf16* __restrict__ dq,
+                          __bf16* __restrict__ dk, __bf16* __restrict__ dv,
+                          const Segs segs, const UnitMap um, const TileIndex ti,
+                          int total, int n_heads, float scale, float scale_log2) {
+  static_assert(kBwdWaves == kDq2Waves, "one workgroup shape for both units");
+  int head, tile;
+  if (!map_unit(um, blockIdx.x, head, tile)) return;
+  int seq, t;
+  locate_tile(ti, segs.n, tile, seq, t);
+  const int key_tiles = (segs.kv_len(seq) + kBwdBC - 1) / kBwdBC;
+  if (t < key_tiles)
+    bwd_dkdv_unit<D, Segs, false>(q, k, v, dout, lse2, delta, sentinel, dk, dv, segs, total, n_heads, scale,
+                                  scale_log2, nullptr, 0, 1, head, seq, t, 0);
+  else
+    bwd_dq2_unit<D, Segs>(q, k, v, dout, lse2, delta, dq, segs, total, n_heads, scale, scale_log2, head, seq,
+                          t - key_tiles);
+}
+
+// Sequences up to this many rows (queries and keys) take the single launch above.
+constexpr int kBothMaxRows = 1024;
+
 // Compute units of the current device (asked once; 256 on MI355X, also the fallback).
 static int compute_unit_count() {
   static std::atomic<int> cached{0};
@@ -1134,6 +1194,27 @@ static hipError_t launch_bwd_d(const void* q, const void* k, const void* v, cons
       int max_q = 0;
       for (int s2 = 0; s2 < segs.n; ++s2) max_q = std::max(max_q, segs.q_len(s2));
       q_split = std::min(std::min(16, (cus + tiles * n_heads - 1) / (tiles * n_heads)), std::max(1, max_q / 512));
+    }
+    if constexpr (D == 128) {
+      int longest = 0;
+      for (int s2 = 0; s2 < segs.n; ++s2) longest = std::max(longest, std::max(segs.q_len(s2), segs.kv_len(s2)));
+      if (q_split == 1 && longest <= kBothMaxRows) {   // short sequences: both passes from one grid
+        TileIndex both;
+        int n_both = 0;
+        for (int s2 = 0; s2 <= VFM_MAX_SEQS; ++s2) {
+          both.cu[s2] = n_both;
+          if (s2 < segs.n)
+            n_both += (segs.kv_len(s2) + kBwdBC - 1) / kBwdBC + (segs.q_len(s2) + Dq2Cfg<D>::kBR - 1) / Dq2Cfg<D>::kBR;
+        }
+        um = make_unit_map(n_both, n_heads);
+        constexpr int lds = Cfg::kLdsBytes > Dq2Cfg<D>::kLdsBytes ? Cfg::kLdsBytes : Dq2Cfg<D>::kLdsBytes;
+        auto kern = attn_bwd_both_kernel<D, Segs>;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess) return e;
+        return launch(kern, dim3(um.chunk * kNumXcd), dim3(kBwdWaves * 64), lds, stream, qb, kb, vb, dob, lse2,
+                      delta, sentinel, (__bf16*)dq, (__bf16*)dk, (__bf16*)dv, segs, um, both, total, n_heads, scale,
+                      scale * kLog2eB);
+      }
     }
     if (q_split > 1) {
       // the accumulators and the conversion cover this run's key rows [kv_lo, kv_hi) only:

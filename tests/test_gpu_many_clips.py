@@ -21,6 +21,32 @@ def test_288_images_of_256_tokens():
     _assert_parity(wl, gpu, host)
 
 
+def test_short_sequences_one_launch_equals_two_passes():
+    # Packs whose sequences all have at most 1,024 rows run dK/dV and dQ units from one grid; one
+    # longer clip in the pack sends it through the two separate kernels.  Both run the same unit
+    # code on the same rows, so the short clips' gradients must agree bit for bit.
+    import torch
+    short = tuple((1, 16, 16) for _ in range(5)) + ((1, 3, 7), (2, 9, 17), (1, 32, 32), (1, 1, 1), (1, 20, 45))
+    wl_a = W.Workload("short", short, 3, 128, (32, 48, 48), seed=85)
+    wl_b = W.Workload("short+long", short + ((1, 33, 32),), 3, 128, (32, 48, 48), seed=85)
+    assert max(wl_a.seqlens) <= 1024 < max(wl_b.seqlens)
+    b = _binding()
+    inp = W.make_inputs(wl_b)
+    n = wl_a.total_tokens
+    dev_b = {k: U.to_device(x) for k, x in inp.items()}
+    dev_a = {k: t[:n].contiguous() for k, t in dev_b.items()}
+    res = []
+    for wl, dev in ((wl_a, dev_a), (wl_b, dev_b)):
+        out, lse = b.vfm_attn_fwd(dev["q"], dev["k"], dev["v"], wl.cu_seqlens, wl.scale)
+        res.append(b.vfm_attn_bwd(dev["q"], dev["k"], dev["v"], out, lse, dev["dout"], wl.cu_seqlens, wl.scale))
+    for nm, ga, gb in zip(("dq", "dk", "dv"), *res):
+        assert torch.equal(ga.view(torch.int16), gb[:n].view(torch.int16)), nm
+    host = tuple(U.to_f64(dev_a[k]) for k in ("q", "k", "v", "dout"))
+    g_ref = orc.attn_bwd(*host, wl_a.cu_seqlens, wl_a.scale)
+    for nm, g, ref in zip(("dq", "dk", "dv"), res[0], g_ref):
+        assert U.rel_rms(U.to_f64(g), ref) <= U.TOL_GRAD_RELRMS, nm
+
+
 def test_600_mixed_clips():
     # three runs; empty, one-token and tile-boundary clips fall on both sides of the cuts
     rng = np.random.default_rng(17)
