@@ -440,7 +440,12 @@ def main() -> int:
     f_bwd = f_all - f_fwd
     value = f_all / (ms_step * 1e-3) / 1e12
     rope_bytes = 2 * 2 * wl.total_tokens * wl.n_heads * wl.head_dim * 2   # q and k, read + write
-    if wl.backward:
+    if wl.backward and int(np.max(np.diff(cu_attn))) <= 1024 and wl.head_dim == 128:
+        # sequences of at most 1,024 rows: the library deals both backward units from one grid
+        dom, dom_flops, dom_ms = "attn_bwd_both_kernel", f_bwd, ms_bwd
+        dom_note = ("vfm_attn_bwd call: bwd_prepare + attn_bwd_both_kernel (dK/dV and dQ units in one grid); "
+                    "10*D algorithmic flops/pair/head (the units execute 14*D)")
+    elif wl.backward:
         dom, dom_flops, dom_ms = "attn_bwd_dkdv_kernel + attn_bwd_dq2_kernel", f_bwd, ms_bwd
         dom_note = ("vfm_attn_bwd call: bwd_prepare + attn_bwd_dkdv_kernel + attn_bwd_dq2_kernel; "
                     "10*D algorithmic flops/pair/head (the two kernels execute 14*D)")
