@@ -39,13 +39,13 @@ LDS_COUNTERS = ("SQ_LDS_IDX_ACTIVE SQ_ACTIVE_INST_LDS SQ_WAIT_INST_LDS SQ_INSTS_
 
 # kernel-name fragment -> short label, most specific first
 KERNELS = (("tattn_fwd", "tattn_fwd_kernel"), ("tattn_bwd", "tattn_bwd_kernel"),
-           ("attn_bwd_dkdv", "attn_bwd_dkdv_kernel"), ("attn_bwd_dq2", "attn_bwd_dq2_kernel"),
+           ("attn_bwd_both", "attn_bwd_both_kernel"), ("attn_bwd_dkdv", "attn_bwd_dkdv_kernel"), ("attn_bwd_dq2", "attn_bwd_dq2_kernel"),
            ("attn_bwd_dq", "attn_bwd_dq_kernel"), ("attn_fwd_fp8", "attn_fwd_fp8_kernel"),
            ("attn_fwd", "attn_fwd_kernel"), ("qknorm_rope3d_bwd", "qknorm_rope3d_bwd_kernel (outside the step)"),
            ("qknorm_rope3d", "qknorm_rope3d_kernel (outside the step)"), ("rope3d", "rope3d_kernel"),
            ("bwd_prepare", "bwd_prepare_kernel"), ("bwd_short_delta", "bwd_short_delta_kernel"),
            ("copyBuffer", "copy kernel (1 GiB)"))
-ATTENTION = ("attn_bwd_dkdv_kernel", "attn_bwd_dq2_kernel", "attn_fwd_kernel")
+ATTENTION = ("attn_bwd_dkdv_kernel", "attn_bwd_dq2_kernel", "attn_bwd_both_kernel", "attn_fwd_kernel")
 N_SIMD, N_CU, N_SE = 1024, 256, 32      # MI355X: 256 CUs x 4 SIMDs, 8 XCDs x 4 shader engines
 
 
@@ -96,6 +96,8 @@ def summarise(run_dir: str, workload: str, out_path: str) -> str:
     d = _bench_line(os.path.join(run_dir, "bench_default.log"))
     b = _bench_line(os.path.join(run_dir, "stats.log"))
     cfg = (d or b or {}).get("config", {}).get("workload", workload)
+    if len(cfg) > 240:                      # packs of hundreds of clips: the list of grids is cut
+        cfg = cfg[:cfg.index("(") + 48] + " ... " + cfg[cfg.index("] ->"):]
     P(f"rocprofv3 summary: packed 3D-RoPE attention, workload {cfg}")
     P("device: AMD Instinct MI355X (gfx950), 256 CUs, 2.4 GHz; all commands run from the repository root after")
     P("  cd /tmp && export TMPDIR=/tmp && cd <repo>;   summarised by: python -m paper_2503_12964_amd.profile_summary " + rel)
@@ -140,7 +142,8 @@ def summarise(run_dir: str, workload: str, out_path: str) -> str:
                 avg[lab] = float(r["AverageNs"]) / 1e6
                 P(f"    {lab:46s} {r['Calls']:>5s} {float(r['AverageNs']) / 1e6:10.3f} {float(r['MinNs']) / 1e6:10.3f} "
                   f"{float(r['MaxNs']) / 1e6:10.3f} {float(r['Percentage']):7.3f}")
-        bwd_sum = sum(avg.get(x, 0.0) for x in ("attn_bwd_dkdv_kernel", "attn_bwd_dq2_kernel", "bwd_prepare_kernel"))
+        bwd_sum = sum(avg.get(x, 0.0) for x in ("attn_bwd_dkdv_kernel", "attn_bwd_dq2_kernel", "attn_bwd_both_kernel",
+                                                "bwd_prepare_kernel"))
         if b and bwd_sum:
             P(f"    backward kernels summed: {bwd_sum:.3f} ms (bench.py's HIP-event time for the vfm_attn_bwd call: "
               f"{b['breakdown']['bwd_ms']:.3f} ms)")
@@ -157,7 +160,8 @@ def summarise(run_dir: str, workload: str, out_path: str) -> str:
         P(f"                 WRITE_SIZE reads {cwv:.0f} KiB for 1,048,576 KiB written -> scale {kw:.4f}")
         P(f"    {'kernel':46s} {'FETCH_SIZE':>12s} {'WRITE_SIZE':>12s} {'scaled read GB':>15s} {'scaled write GB':>16s}")
         bwd_total, fwd_total = 0.0, 0.0
-        for lab in ("attn_bwd_dkdv_kernel", "attn_bwd_dq2_kernel", "attn_bwd_dq_kernel", "attn_fwd_kernel", "rope3d_kernel",
+        for lab in ("attn_bwd_dkdv_kernel", "attn_bwd_dq2_kernel", "attn_bwd_both_kernel", "attn_bwd_dq_kernel",
+                    "attn_fwd_kernel", "rope3d_kernel",
                     "bwd_prepare_kernel", "bwd_short_delta_kernel"):
             fv, wv = f.get((lab, "FETCH_SIZE")), w.get((lab, "WRITE_SIZE"))
             if fv is None and wv is None:
@@ -169,7 +173,7 @@ def summarise(run_dir: str, workload: str, out_path: str) -> str:
             if lab == "attn_fwd_kernel":
                 fwd_total = (rg + wg) * 1e9
             P(f"    {lab:46s} {fv:12.0f} {wv:12.0f} {rg:15.3f} {wg:16.3f}")
-        P(f"    backward call (prepare + dK/dV + dQ) scaled traffic: {bwd_total / 1e9:.2f} GB per launch; forward call "
+        P(f"    backward call (all its kernels) scaled traffic: {bwd_total / 1e9:.2f} GB per launch; forward call "
           f"{fwd_total / 1e9:.2f} GB   <- bench.py roofline.traffic (profiles/attention_hbm_traffic.txt)")
         _write_traffic(workload, {"backward_call": bwd_total, "forward_call": fwd_total})
         P("")
